@@ -1,0 +1,134 @@
+"""Oracle for the circular buffer C(N, K) (Section 3.2, Algorithm 1) -- test infrastructure.
+
+The paper fixes: N stored items, each traversable at most K times, after which
+it is discarded and its place taken by a new worker batch.  The order of
+traversal, and what happens when the ring is full or short, are this build's
+readings (parity unpinned): ring order from a read cursor, inserts never
+overwrite a live item, insert and sample are all-or-nothing.
+
+Plain Python, one loop per operation; the stored records are numpy arrays in
+slot-major order ``[N, T, ...]``.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+from . import quantize_bf16
+
+
+class BufferFull(Exception):
+    pass
+
+
+class NotEnoughLive(Exception):
+    pass
+
+
+class RingOracle:
+    """Integer bookkeeping only."""
+
+    def __init__(self, num_slots: int, K: int):
+        if num_slots < 1 or K < 1:
+            raise ValueError("num_slots and K must be positive")
+        self.N, self.K = num_slots, K
+        self.count = [-1] * num_slots   # -1 empty, else times traversed so far (0..K-1)
+        self.w = 0                      # write cursor
+        self.r = 0                      # read cursor
+
+    def num_live(self) -> int:
+        return sum(1 for c in self.count if c >= 0)
+
+    def insert(self, n: int) -> List[int]:
+        if n < 0:
+            raise ValueError("n < 0")
+        if self.N - self.num_live() < n:
+            raise BufferFull()
+        slots = []
+        for _ in range(n):
+            while self.count[self.w] >= 0:
+                self.w = (self.w + 1) % self.N
+            self.count[self.w] = 0
+            slots.append(self.w)
+            self.w = (self.w + 1) % self.N
+        return slots
+
+    def sample(self, B: int) -> Tuple[List[int], List[int]]:
+        if B < 0:
+            raise ValueError("B < 0")
+        if self.num_live() < B:
+            raise NotEnoughLive()
+        slots, counts = [], []
+        for _ in range(B):
+            while self.count[self.r] < 0:
+                self.r = (self.r + 1) % self.N
+            s = self.r
+            slots.append(s)
+            counts.append(self.count[s])          # traversals before this one
+            self.count[s] += 1
+            if self.count[s] == self.K:
+                self.count[s] = -1                # traversed K times: discarded
+            self.r = (self.r + 1) % self.N
+        return slots, counts
+
+
+class BufferOracle(RingOracle):
+    """Ring bookkeeping plus the stored records (slot-major), for gather checks."""
+
+    def __init__(self, dist: str, T: int, A: int, num_slots: int, K: int, storage: str = "f32"):
+        super().__init__(num_slots, K)
+        self.dist, self.T, self.A, self.storage = dist, T, A, storage
+        self.W = A if dist == "categorical" else 2 * A
+        fdt = np.float32 if storage == "f32" else np.uint16
+        N = num_slots
+        self.worker = np.zeros((N, T, self.W), fdt)
+        self.target = np.zeros((N, T, self.W), fdt)
+        self.actions = np.zeros((N, T), np.int32) if dist == "categorical" else np.zeros((N, T, A), fdt)
+        self.rewards = np.zeros((N, T), fdt)
+        self.dones = np.zeros((N, T), np.uint8)
+
+    def _store(self, x: np.ndarray) -> np.ndarray:
+        x = np.asarray(x, np.float32)
+        return x if self.storage == "f32" else quantize_bf16(x)[0]
+
+    def insert_records(self, worker, actions, rewards, dones, target=None) -> List[int]:
+        """Time-major fp32 inputs [T, n, ...]; returns the slots used."""
+        n = worker.shape[1]
+        slots = self.insert(n)
+        for i, s in enumerate(slots):
+            self.worker[s] = self._store(worker[:, i])
+            if self.dist == "categorical":
+                self.actions[s] = actions[:, i]
+            else:
+                self.actions[s] = self._store(actions[:, i])
+            self.rewards[s] = self._store(rewards[:, i])
+            self.dones[s] = dones[:, i]
+            if target is not None:
+                self.target[s] = self._store(target[:, i])
+        return slots
+
+    def put_target(self, slots, target) -> None:
+        for i, s in enumerate(slots):
+            self.target[s] = self._store(target[:, i])
+
+    def gather(self, slots) -> Dict[str, np.ndarray]:
+        """Time-major copies, in the storage dtype (bf16 as uint16 bit patterns)."""
+        B = len(slots)
+        out = dict(worker=np.empty((self.T, B, self.W), self.worker.dtype),
+                   target=np.empty((self.T, B, self.W), self.target.dtype),
+                   actions=np.empty((self.T, B) + self.actions.shape[2:], self.actions.dtype),
+                   rewards=np.empty((self.T, B), self.rewards.dtype),
+                   dones=np.empty((self.T, B), np.uint8))
+        for i, s in enumerate(slots):
+            out["worker"][:, i] = self.worker[s]
+            out["target"][:, i] = self.target[s]
+            out["actions"][:, i] = self.actions[s]
+            out["rewards"][:, i] = self.rewards[s]
+            out["dones"][:, i] = self.dones[s]
+        return out
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bfloat16 bit patterns to fp32 values."""
+    return (bits.astype(np.uint32) << 16).view(np.float32)
