@@ -1,0 +1,218 @@
+/*
+ * impact.h -- C ABI of the MI355X (gfx950) library for the IMPACT learner's hot
+ * path (arXiv 1912.00167): the circular buffer of replayed trajectories
+ * (Section 3.2, Algorithm 1 learner loop "obtain batch ... traversed k times")
+ * and the per-SGD-step loss with its analytic gradients (Section 3.1,
+ * Algorithm 1 "compute policy and value network gradients", Appendix E).
+ *
+ * General conventions
+ *   - Every call returns an impact_status_t: 0 on success, negative on error.
+ *     On error no state of a buffer handle has changed and no kernel has been
+ *     enqueued, unless stated otherwise.  No call throws or aborts.
+ *   - "device" pointers are HBM addresses usable from the current HIP device;
+ *     "host" pointers are ordinary process memory.  The caller owns every
+ *     device allocation it passes in; the library keeps only the host-side
+ *     handle.  Device pointers must be 16-byte aligned.
+ *   - Kernels are enqueued on the given stream (a hipStream_t passed as void*;
+ *     NULL is the default stream) and the calls do not wait for them.
+ *   - Tensors handed to the loss are time-major and C-contiguous:
+ *       dist tensors  [T][B][W]   W = A logits (categorical) or W = 2*D
+ *                                 (diagonal Gaussian: D means, then D log
+ *                                 standard deviations),
+ *       step scalars  [T][B],  bootstrap [B].
+ *     Inside the buffer the same records are slot-major, [slot][T][...].
+ *   - Arithmetic is fp32.  IMPACT_BF16 is a storage format only (bfloat16,
+ *     round-to-nearest-even at insert); values are widened to fp32 on load.
+ *   - One buffer handle may be used from several host threads (one mutex per
+ *     handle).  Device work of different calls is ordered only by the streams
+ *     the caller passes.
+ */
+#ifndef IMPACT_H
+#define IMPACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    IMPACT_OK = 0,
+    IMPACT_ERR_INVALID_ARG = -1,     /* NULL pointer, bad shape, non-finite hyper-parameter, misaligned pointer */
+    IMPACT_ERR_BUFFER_FULL = -2,     /* insert: fewer empty slots than trajectories offered */
+    IMPACT_ERR_NOT_ENOUGH_LIVE = -3, /* sample: fewer live slots than trajectories asked for */
+    IMPACT_ERR_HIP = -4,             /* a HIP runtime call or a kernel launch failed */
+    IMPACT_ERR_UNSUPPORTED = -5      /* a valid request this build has no kernel for */
+} impact_status_t;
+
+typedef enum { IMPACT_CATEGORICAL = 0, IMPACT_DIAG_GAUSSIAN = 1 } impact_dist_t;
+typedef enum { IMPACT_F32 = 0, IMPACT_BF16 = 1 } impact_dtype_t;
+
+typedef void *impact_stream_t;          /* a hipStream_t */
+typedef struct impact_buffer impact_buffer_t;
+
+/* Shape of the circular buffer C(N, K) of Section 3.2: num_slots stored
+ * trajectories of T steps, each handed out at most K times. */
+typedef struct {
+    int32_t dist;       /* impact_dist_t */
+    int32_t T;          /* steps per trajectory, >= 1 */
+    int32_t A;          /* number of actions, or action dimension D, >= 1 */
+    int32_t num_slots;  /* N, >= 1 */
+    int32_t K;          /* replay limit, >= 1 */
+    int32_t storage;    /* impact_dtype_t of the float fields kept in the buffer */
+} impact_buffer_desc_t;
+
+/* Hyper-parameters of the loss.
+ *   gamma, lambda           discount and GAE-lambda of the V-trace advantage (Section 3.1)
+ *   rho_bar, c_bar          V-trace truncation levels of rho_i and c_j (Section 2.2)
+ *   rho_clip                target-worker clipping rho >= 1 of J_AIS (Section 3.1); +inf gives
+ *                           the plain ratio pi_theta / pi_target
+ *   eps                     PPO clip parameter (Appendix E, last bullet); +inf disables the clip
+ *   vf_coeff, ent_coeff, kl_coeff   weights of the value, entropy and KL(pi_target || pi_theta)
+ *                           terms (Algorithm 1, Appendix B)
+ *   flags                   bit 0: use the shape-generic kernels even when a specialised one exists */
+typedef struct {
+    float gamma, lambda, rho_bar, c_bar;
+    float rho_clip;
+    float eps;
+    float vf_coeff, ent_coeff, kl_coeff;
+    uint32_t flags;
+} impact_loss_config_t;
+
+#define IMPACT_FLAG_FORCE_GENERIC 1u
+
+/* The buffer-resident part of a batch (what a worker sent plus the target
+ * network's evaluation appended at k = 0, Algorithm 1).  All device pointers.
+ *   worker_dist, target_dist  [T][B][W]
+ *   actions                   int32 [T][B] (categorical) or float [T][B][D] (Gaussian)
+ *   rewards                   [T][B]
+ *   dones                     uint8 [T][B]; 1 = the transition at t ended the episode
+ * Float fields have the dtype named next to the struct in each call. */
+typedef struct {
+    const void *worker_dist;
+    const void *target_dist;
+    const void *actions;
+    const void *rewards;
+    const uint8_t *dones;
+} impact_batch_t;
+
+/* Outputs of the loss, all device, all fp32, written in full by each call.
+ *   grad_learner_dist  [T][B][W]  dL/d(learner logits) or dL/d(mean | log-std)
+ *   grad_values        [T][B]     dL/dV
+ *   vs, adv            [T][B]     value targets and advantages; either may be NULL
+ *   loss5              [5]        {total, policy, value, mean entropy, mean KL} */
+typedef struct {
+    float *grad_learner_dist;
+    float *grad_values;
+    float *vs;
+    float *adv;
+    float *loss5;
+} impact_loss_out_t;
+
+/* Library version, "major.minor". */
+const char *impact_version(void);
+/* Static description of a status code. */
+const char *impact_status_string(impact_status_t);
+
+/* ----------------------------- circular buffer ----------------------------- */
+
+/* Bytes of device memory a buffer of this shape needs (0 if the descriptor is
+ * invalid).  Layout: one plane per field, slot-major, each plane starting on a
+ * 256-byte boundary and followed by at least 16 bytes of padding. */
+size_t impact_buffer_storage_bytes(const impact_buffer_desc_t *desc);
+
+/* Create the host-side handle over caller-owned device storage of at least
+ * impact_buffer_storage_bytes(desc) bytes (256-byte aligned).  The ring starts
+ * empty; the storage is not touched.  Errors: INVALID_ARG. */
+impact_status_t impact_buffer_create(const impact_buffer_desc_t *desc, void *dev_storage, size_t bytes,
+                                     impact_buffer_t **out);
+/* Free the handle (not the device storage).  NULL is allowed. */
+impact_status_t impact_buffer_destroy(impact_buffer_t *buf);
+
+/* Number of live slots (inserted and not yet traversed K times), or a negative status. */
+int32_t impact_buffer_num_live(impact_buffer_t *buf);
+
+/* Host bookkeeping half of an insert: choose n empty slots in ring order from the
+ * write cursor (never a live one, Section 3.2), mark them live with a traversal
+ * count of 0 and report them in out_slots (host, n entries).  No device work:
+ * the caller fills the slots itself.  All-or-nothing: BUFFER_FULL if fewer than
+ * n slots are empty. */
+impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *out_slots);
+
+/* "Send B_i to C(N,K)" (Algorithm 1, worker): store n new trajectories.
+ *   src        time-major fp32 device tensors [T][n][...]; target_dist may be NULL
+ *              (to be filled by impact_buffer_put_target before the slot is used)
+ *   out_slots  host, n entries: the slots chosen, in ring order from the write cursor,
+ *              skipping live slots (a live trajectory is never overwritten, Section 3.2)
+ * Values are converted to the storage dtype (bf16: round-to-nearest-even).
+ * All-or-nothing: BUFFER_FULL if fewer than n slots are empty.  n = 0 is a no-op. */
+impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impact_batch_t *src_f32,
+                                     int32_t *out_slots, impact_stream_t stream);
+
+/* "If k = 0, evaluate B on target, append target output to B" (Algorithm 1):
+ * write fp32 target-network outputs [T][n][W] (device) into the target_dist
+ * plane of the n slots listed in the host array `slots` (each in [0, num_slots)). */
+impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const int32_t *slots,
+                                         const float *target_dist, impact_stream_t stream);
+
+/* "Obtain batch B of size M traversed k times from C(N,K)" (Algorithm 1), host
+ * bookkeeping only: walk the read cursor over the ring, take the next B live
+ * slots, report each slot and how often it had been traversed before this call,
+ * count the traversal, and empty a slot once its count reaches K ("discard",
+ * Algorithm 1; Section 3.2).  out_slots/out_counts: host, B entries each.
+ * All-or-nothing: NOT_ENOUGH_LIVE if fewer than B slots are live.  B = 0 is a no-op. */
+impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *out_slots, int32_t *out_counts);
+
+/* Copy the records of B slots into time-major tensors [T][B][...] of the
+ * buffer's storage dtype (a byte copy, no conversion).  dev_slots: device int32
+ * [B], each in [0, num_slots) -- an out-of-range index is clamped into range,
+ * never dereferenced out of bounds.  dst pointers are device outputs; a NULL
+ * field is skipped. */
+impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
+                                     const impact_batch_t *dst, impact_stream_t stream);
+
+/* ---------------------------------- loss ----------------------------------- */
+
+/* Bytes of device workspace the loss calls need for a batch of this shape
+ * (partial sums of the five loss terms; 0 on invalid arguments). */
+size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A);
+
+/* One learner step of Algorithm 1 on a gathered batch.  Per trajectory b:
+ *   log pi_x(a_t|s_t) for x in {theta, target, worker}            (Section 2)
+ *   w_t = pi_target/pi_worker, rho_t = min(rho_bar, w_t), c_t = min(c_bar, w_t)
+ *   delta_t = rho_t (r_t + gamma_t V_{t+1} - V_t), gamma_t = gamma (1 - done_t), V_T = bootstrap
+ *   adv_t = delta_t + gamma_t lambda c_t adv_{t+1}, vs_t = V_t + adv_t   (Sections 2.2, 3.1)
+ *   R_t = pi_theta / max(pi_target, pi_worker / rho_clip)                  (J_AIS, Section 3.1)
+ *   s_t = min(R_t adv_t, clip(R_t, 1-eps, 1+eps) adv_t)                    (Appendix E)
+ *   L = -mean s + vf_coeff mean (V - vs)^2 / 2 - ent_coeff mean H(pi_theta)
+ *       + kl_coeff mean KL(pi_target || pi_theta),   means over the T*B steps
+ * and the gradients of L with respect to the learner's distribution parameters
+ * and values, with vs and adv held constant (Algorithm 1).
+ *   batch_dtype   dtype of the float fields of `batch` (learner_dist, values, bootstrap are fp32)
+ *   learner_dist  [T][B][W], values [T][B], bootstrap [B]  (device, fp32)
+ *   workspace     device, >= impact_loss_workspace_bytes(...)
+ * Errors: INVALID_ARG (NULL or misaligned pointers, T,B,A < 1, non-finite gamma/lambda/
+ * coefficients, negative truncation levels, rho_clip < 1, eps < 0), HIP.
+ * A categorical action outside [0, A) is clamped for addressing and turns all
+ * five losses into NaN. */
+impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
+                                    const float *learner_dist, const float *values, const float *bootstrap,
+                                    const impact_batch_t *batch, const impact_loss_config_t *cfg,
+                                    const impact_loss_out_t *out, void *workspace, size_t workspace_bytes,
+                                    impact_stream_t stream);
+
+/* The same step with the gather fused in: the buffer-resident fields of
+ * trajectory b are read in place from slot dev_slots[b] of `buf` (device int32
+ * [B]; out-of-range indices are clamped and turn the losses into NaN).
+ * dist, T, A and the batch dtype come from the buffer's descriptor. */
+impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
+                                                const float *learner_dist, const float *values,
+                                                const float *bootstrap, const impact_loss_config_t *cfg,
+                                                const impact_loss_out_t *out, void *workspace,
+                                                size_t workspace_bytes, impact_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IMPACT_H */

@@ -1,0 +1,325 @@
+"""ctypes binding of libimpact.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (``include/impact.h``)
+and passes raw device pointers taken from torch tensors.  No arithmetic of the loss
+or of the buffer happens in Python.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libimpact.so")
+
+IMPACT_OK = 0
+IMPACT_ERR_INVALID_ARG = -1
+IMPACT_ERR_BUFFER_FULL = -2
+IMPACT_ERR_NOT_ENOUGH_LIVE = -3
+IMPACT_ERR_HIP = -4
+IMPACT_ERR_UNSUPPORTED = -5
+
+IMPACT_CATEGORICAL = 0
+IMPACT_DIAG_GAUSSIAN = 1
+IMPACT_F32 = 0
+IMPACT_BF16 = 1
+IMPACT_FLAG_FORCE_GENERIC = 1
+
+EXPORTS = [
+    "impact_version", "impact_status_string",
+    "impact_buffer_storage_bytes", "impact_buffer_create", "impact_buffer_destroy", "impact_buffer_num_live",
+    "impact_buffer_reserve", "impact_buffer_insert", "impact_buffer_put_target", "impact_buffer_sample",
+    "impact_buffer_gather", "impact_loss_workspace_bytes", "impact_loss_fwd_bwd",
+    "impact_loss_fwd_bwd_from_buffer",
+]
+
+
+class ImpactError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({status_string(status)})")
+
+
+class impact_buffer_desc_t(ctypes.Structure):
+    _fields_ = [("dist", ctypes.c_int32), ("T", ctypes.c_int32), ("A", ctypes.c_int32),
+                ("num_slots", ctypes.c_int32), ("K", ctypes.c_int32), ("storage", ctypes.c_int32)]
+
+
+class impact_loss_config_t(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_float), ("lam", ctypes.c_float), ("rho_bar", ctypes.c_float),
+                ("c_bar", ctypes.c_float), ("rho_clip", ctypes.c_float), ("eps", ctypes.c_float),
+                ("vf_coeff", ctypes.c_float), ("ent_coeff", ctypes.c_float), ("kl_coeff", ctypes.c_float),
+                ("flags", ctypes.c_uint32)]
+
+
+class impact_batch_t(ctypes.Structure):
+    _fields_ = [("worker_dist", ctypes.c_void_p), ("target_dist", ctypes.c_void_p), ("actions", ctypes.c_void_p),
+                ("rewards", ctypes.c_void_p), ("dones", ctypes.c_void_p)]
+
+
+class impact_loss_out_t(ctypes.Structure):
+    _fields_ = [("grad_learner_dist", ctypes.c_void_p), ("grad_values", ctypes.c_void_p), ("vs", ctypes.c_void_p),
+                ("adv", ctypes.c_void_p), ("loss5", ctypes.c_void_p)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libimpact.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1912_00167_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.impact_version.restype = ctypes.c_char_p
+    L.impact_status_string.restype = ctypes.c_char_p
+    L.impact_status_string.argtypes = [ctypes.c_int]
+    L.impact_buffer_storage_bytes.restype = sz
+    L.impact_buffer_storage_bytes.argtypes = [ctypes.POINTER(impact_buffer_desc_t)]
+    L.impact_buffer_create.restype = ctypes.c_int
+    L.impact_buffer_create.argtypes = [ctypes.POINTER(impact_buffer_desc_t), vp, sz, ctypes.POINTER(vp)]
+    L.impact_buffer_destroy.restype = ctypes.c_int
+    L.impact_buffer_destroy.argtypes = [vp]
+    L.impact_buffer_num_live.restype = i32
+    L.impact_buffer_num_live.argtypes = [vp]
+    L.impact_buffer_reserve.restype = ctypes.c_int
+    L.impact_buffer_reserve.argtypes = [vp, i32, vp]
+    L.impact_buffer_insert.restype = ctypes.c_int
+    L.impact_buffer_insert.argtypes = [vp, i32, ctypes.POINTER(impact_batch_t), vp, vp]
+    L.impact_buffer_put_target.restype = ctypes.c_int
+    L.impact_buffer_put_target.argtypes = [vp, i32, vp, vp, vp]
+    L.impact_buffer_sample.restype = ctypes.c_int
+    L.impact_buffer_sample.argtypes = [vp, i32, vp, vp]
+    L.impact_buffer_gather.restype = ctypes.c_int
+    L.impact_buffer_gather.argtypes = [vp, i32, vp, ctypes.POINTER(impact_batch_t), vp]
+    L.impact_loss_workspace_bytes.restype = sz
+    L.impact_loss_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.impact_loss_fwd_bwd.restype = ctypes.c_int
+    L.impact_loss_fwd_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, ctypes.POINTER(impact_batch_t),
+                                      ctypes.POINTER(impact_loss_config_t), ctypes.POINTER(impact_loss_out_t),
+                                      vp, sz, vp]
+    L.impact_loss_fwd_bwd_from_buffer.restype = ctypes.c_int
+    L.impact_loss_fwd_bwd_from_buffer.argtypes = [vp, i32, vp, vp, vp, vp, ctypes.POINTER(impact_loss_config_t),
+                                                  ctypes.POINTER(impact_loss_out_t), vp, sz, vp]
+    _lib = L
+    return L
+
+
+def impact_version() -> str:
+    return load().impact_version().decode()
+
+
+def status_string(status: int) -> str:
+    return load().impact_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != IMPACT_OK:
+        raise ImpactError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to libimpact must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def dist_code(dist) -> int:
+    return {"categorical": IMPACT_CATEGORICAL, "gaussian": IMPACT_DIAG_GAUSSIAN,
+            IMPACT_CATEGORICAL: IMPACT_CATEGORICAL, IMPACT_DIAG_GAUSSIAN: IMPACT_DIAG_GAUSSIAN}[dist]
+
+
+def dtype_code(storage) -> int:
+    return {"f32": IMPACT_F32, "bf16": IMPACT_BF16, IMPACT_F32: IMPACT_F32, IMPACT_BF16: IMPACT_BF16,
+            torch.float32: IMPACT_F32, torch.bfloat16: IMPACT_BF16}[storage]
+
+
+def make_config(gamma=0.99, lam=1.0, rho_bar=1.0, c_bar=1.0, rho_clip=2.0, eps=0.2, vf_coeff=1.0,
+                ent_coeff=0.01, kl_coeff=0.0, flags=0) -> impact_loss_config_t:
+    return impact_loss_config_t(gamma, lam, rho_bar, c_bar, rho_clip, eps, vf_coeff, ent_coeff, kl_coeff, flags)
+
+
+def config_from_hyper(h, flags: int = 0) -> impact_loss_config_t:
+    return make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, h.eps, h.vf_coeff, h.ent_coeff,
+                       h.kl_coeff, flags)
+
+
+def _batch_struct(batch: Dict[str, torch.Tensor], need_target: bool = True) -> impact_batch_t:
+    tgt = batch.get("target")
+    if need_target and tgt is None:
+        raise ValueError("batch needs a target tensor")
+    return impact_batch_t(_ptr(batch["worker"]), _ptr(tgt), _ptr(batch["actions"]), _ptr(batch["rewards"]),
+                          _ptr(batch["dones"]))
+
+
+# ------------------------------------------------------------------------------------------
+# circular buffer
+# ------------------------------------------------------------------------------------------
+
+def impact_buffer_storage_bytes(dist, T: int, A: int, num_slots: int, K: int, storage) -> int:
+    d = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage))
+    return int(load().impact_buffer_storage_bytes(ctypes.byref(d)))
+
+
+class Buffer:
+    """Owner of a buffer handle and of the torch allocation behind it."""
+
+    def __init__(self, dist, T: int, A: int, num_slots: int, K: int, storage="f32", device="cuda"):
+        self.desc = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage))
+        nbytes = int(load().impact_buffer_storage_bytes(ctypes.byref(self.desc)))
+        if nbytes == 0:
+            raise ImpactError(IMPACT_ERR_INVALID_ARG, "impact_buffer_storage_bytes")
+        self.storage = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+        self.handle = ctypes.c_void_p()
+        _check(load().impact_buffer_create(ctypes.byref(self.desc), _ptr(self.storage), nbytes,
+                                           ctypes.byref(self.handle)), "impact_buffer_create")
+        self.dist, self.T, self.A, self.num_slots, self.K = self.desc.dist, T, A, num_slots, K
+        self.W = A if self.dist == IMPACT_CATEGORICAL else 2 * A
+        self.float_dtype = torch.float32 if self.desc.storage == IMPACT_F32 else torch.bfloat16
+        self.device = self.storage.device
+
+    def close(self) -> None:
+        if self.handle:
+            load().impact_buffer_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def impact_buffer_num_live(buf: Buffer) -> int:
+    return int(load().impact_buffer_num_live(buf.handle))
+
+
+def impact_buffer_reserve(buf: Buffer, n: int) -> np.ndarray:
+    slots = np.empty(max(n, 0), dtype=np.int32)
+    _check(load().impact_buffer_reserve(buf.handle, n, slots.ctypes.data_as(ctypes.c_void_p)), "impact_buffer_reserve")
+    return slots
+
+
+def impact_buffer_insert(buf: Buffer, src: Dict[str, torch.Tensor], stream=None) -> np.ndarray:
+    """src: time-major fp32 device tensors worker/actions/rewards/dones (+ optional target)."""
+    n = int(src["worker"].shape[1])
+    slots = np.empty(n, dtype=np.int32)
+    b = _batch_struct(src, need_target=False)
+    _check(load().impact_buffer_insert(buf.handle, n, ctypes.byref(b), slots.ctypes.data_as(ctypes.c_void_p),
+                                       _stream(stream)), "impact_buffer_insert")
+    return slots
+
+
+def impact_buffer_put_target(buf: Buffer, slots: np.ndarray, target: torch.Tensor, stream=None) -> None:
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    _check(load().impact_buffer_put_target(buf.handle, slots.size, slots.ctypes.data_as(ctypes.c_void_p),
+                                           _ptr(target), _stream(stream)), "impact_buffer_put_target")
+
+
+def impact_buffer_sample(buf: Buffer, B: int, out_slots: Optional[np.ndarray] = None,
+                         out_counts: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    if out_slots is None:
+        out_slots = np.empty(max(B, 0), dtype=np.int32)
+    if out_counts is None:
+        out_counts = np.empty(max(B, 0), dtype=np.int32)
+    _check(load().impact_buffer_sample(buf.handle, B, out_slots.ctypes.data_as(ctypes.c_void_p),
+                                       out_counts.ctypes.data_as(ctypes.c_void_p)), "impact_buffer_sample")
+    return out_slots, out_counts
+
+
+def alloc_batch(buf: Buffer, B: int) -> Dict[str, torch.Tensor]:
+    """Device tensors able to receive a gathered batch (storage dtype)."""
+    fd, dev, T = buf.float_dtype, buf.device, buf.T
+    acts = (torch.empty((T, B), dtype=torch.int32, device=dev) if buf.dist == IMPACT_CATEGORICAL
+            else torch.empty((T, B, buf.A), dtype=fd, device=dev))
+    return dict(worker=torch.empty((T, B, buf.W), dtype=fd, device=dev),
+                target=torch.empty((T, B, buf.W), dtype=fd, device=dev), actions=acts,
+                rewards=torch.empty((T, B), dtype=fd, device=dev),
+                dones=torch.empty((T, B), dtype=torch.uint8, device=dev))
+
+
+def impact_buffer_gather(buf: Buffer, dev_slots: torch.Tensor, dst: Optional[Dict[str, torch.Tensor]] = None,
+                         stream=None) -> Dict[str, torch.Tensor]:
+    B = int(dev_slots.numel())
+    if dst is None:
+        dst = alloc_batch(buf, B)
+    b = _batch_struct(dst)
+    _check(load().impact_buffer_gather(buf.handle, B, _ptr(dev_slots), ctypes.byref(b), _stream(stream)),
+           "impact_buffer_gather")
+    return dst
+
+
+# ------------------------------------------------------------------------------------------
+# loss
+# ------------------------------------------------------------------------------------------
+
+def impact_loss_workspace_bytes(dist, T: int, B: int, A: int) -> int:
+    return int(load().impact_loss_workspace_bytes(dist_code(dist), T, B, A))
+
+
+def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = True) -> Dict[str, torch.Tensor]:
+    out = dict(grad_dist=torch.empty((T, B, W), dtype=torch.float32, device=device),
+               grad_values=torch.empty((T, B), dtype=torch.float32, device=device),
+               loss5=torch.empty(5, dtype=torch.float32, device=device))
+    if want_targets:
+        out["vs"] = torch.empty((T, B), dtype=torch.float32, device=device)
+        out["adv"] = torch.empty((T, B), dtype=torch.float32, device=device)
+    return out
+
+
+def _out_struct(out: Dict[str, torch.Tensor]) -> impact_loss_out_t:
+    return impact_loss_out_t(_ptr(out["grad_dist"]), _ptr(out["grad_values"]), _ptr(out.get("vs")),
+                             _ptr(out.get("adv")), _ptr(out["loss5"]))
+
+
+def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, bootstrap: torch.Tensor,
+                        batch: Dict[str, torch.Tensor], cfg: impact_loss_config_t,
+                        out: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None,
+                        stream=None) -> Dict[str, torch.Tensor]:
+    d = dist_code(dist)
+    T, B, W = (int(x) for x in learner.shape)
+    A = W if d == IMPACT_CATEGORICAL else W // 2
+    if out is None:
+        out = alloc_loss_out(T, B, W, learner.device)
+    if workspace is None:
+        workspace = torch.empty(impact_loss_workspace_bytes(d, T, B, A), dtype=torch.uint8, device=learner.device)
+    b, o = _batch_struct(batch), _out_struct(out)
+    _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["worker"].dtype), T, B, A, _ptr(learner), _ptr(values),
+                                      _ptr(bootstrap), ctypes.byref(b), ctypes.byref(cfg), ctypes.byref(o),
+                                      _ptr(workspace), workspace.numel(), _stream(stream)), "impact_loss_fwd_bwd")
+    return out
+
+
+def impact_loss_fwd_bwd_from_buffer(buf: Buffer, dev_slots: torch.Tensor, learner: torch.Tensor,
+                                    values: torch.Tensor, bootstrap: torch.Tensor, cfg: impact_loss_config_t,
+                                    out: Optional[Dict[str, torch.Tensor]] = None,
+                                    workspace: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
+    T, B, W = (int(x) for x in learner.shape)
+    if out is None:
+        out = alloc_loss_out(T, B, W, learner.device)
+    if workspace is None:
+        workspace = torch.empty(impact_loss_workspace_bytes(buf.dist, T, B, buf.A), dtype=torch.uint8,
+                                device=learner.device)
+    o = _out_struct(out)
+    _check(load().impact_loss_fwd_bwd_from_buffer(buf.handle, B, _ptr(dev_slots), _ptr(learner), _ptr(values),
+                                                  _ptr(bootstrap), ctypes.byref(cfg), ctypes.byref(o),
+                                                  _ptr(workspace), workspace.numel(), _stream(stream)),
+           "impact_loss_fwd_bwd_from_buffer")
+    return out

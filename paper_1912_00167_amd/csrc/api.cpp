@@ -1,0 +1,379 @@
+// Host side of libimpact: argument checking, the circular buffer's integer bookkeeping,
+// and kernel dispatch.  Nothing here computes any part of the loss.
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "impact_internal.h"
+
+using namespace impact;
+
+namespace {
+
+constexpr size_t kPlaneAlign = 256;
+constexpr size_t kPlanePad = 16;   // readable bytes after each plane (vector loads may overrun a row range)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool desc_ok(const impact_buffer_desc_t *d)
+{
+    if (!d) return false;
+    if (d->dist != IMPACT_CATEGORICAL && d->dist != IMPACT_DIAG_GAUSSIAN) return false;
+    if (d->storage != IMPACT_F32 && d->storage != IMPACT_BF16) return false;
+    if (d->T < 1 || d->A < 1 || d->num_slots < 1 || d->K < 1) return false;
+    // keep every element index of a plane below 2^40 and W within int range
+    if ((double)d->num_slots * d->T * (2.0 * d->A) > 1.0e12) return false;
+    if (d->A > (1 << 20)) return false;
+    return true;
+}
+
+struct Planes {
+    size_t worker, target, actions, rewards, dones, total;
+};
+
+Planes plane_layout(const impact_buffer_desc_t &d)
+{
+    const size_t es = d.storage == IMPACT_F32 ? 4 : 2;
+    const size_t W = d.dist == IMPACT_CATEGORICAL ? (size_t)d.A : 2 * (size_t)d.A;
+    const size_t steps = (size_t)d.num_slots * d.T;
+    Planes p;
+    size_t off = 0;
+    p.worker = off; off = align_up(off + steps * W * es + kPlanePad, kPlaneAlign);
+    p.target = off; off = align_up(off + steps * W * es + kPlanePad, kPlaneAlign);
+    p.actions = off;
+    off = align_up(off + (d.dist == IMPACT_CATEGORICAL ? steps * 4 : steps * d.A * es) + kPlanePad, kPlaneAlign);
+    p.rewards = off; off = align_up(off + steps * es + kPlanePad, kPlaneAlign);
+    p.dones = off; off = align_up(off + steps + kPlanePad, kPlaneAlign);
+    p.total = off;
+    return p;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+struct impact_buffer {
+    impact_buffer_desc_t desc;
+    Planes planes;
+    char *storage;
+    std::vector<int32_t> count;   // -1 empty, else traversals so far (0 .. K-1)
+    int32_t w, r, live;
+    std::mutex mu;
+
+    int W() const { return desc.dist == IMPACT_CATEGORICAL ? desc.A : 2 * desc.A; }
+    int es() const { return desc.storage == IMPACT_F32 ? 4 : 2; }
+
+    // Ring order from the write cursor over empty slots.  Caller has checked there is room.
+    void reserve(int32_t n, int32_t *out)
+    {
+        const int32_t N = desc.num_slots;
+        for (int32_t i = 0; i < n; ++i) {
+            while (count[w] >= 0) w = (w + 1 == N) ? 0 : w + 1;
+            count[w] = 0;
+            out[i] = w;
+            w = (w + 1 == N) ? 0 : w + 1;
+        }
+        live += n;
+    }
+};
+
+extern "C" {
+
+const char *impact_version(void) { return "0.1"; }
+
+const char *impact_status_string(impact_status_t s)
+{
+    switch (s) {
+    case IMPACT_OK: return "ok";
+    case IMPACT_ERR_INVALID_ARG: return "invalid argument";
+    case IMPACT_ERR_BUFFER_FULL: return "buffer full";
+    case IMPACT_ERR_NOT_ENOUGH_LIVE: return "not enough live slots";
+    case IMPACT_ERR_HIP: return "HIP error";
+    case IMPACT_ERR_UNSUPPORTED: return "unsupported";
+    }
+    return "unknown status";
+}
+
+size_t impact_buffer_storage_bytes(const impact_buffer_desc_t *desc)
+{
+    if (!desc_ok(desc)) return 0;
+    return plane_layout(*desc).total;
+}
+
+impact_status_t impact_buffer_create(const impact_buffer_desc_t *desc, void *dev_storage, size_t bytes,
+                                     impact_buffer_t **out)
+{
+    if (!out) return IMPACT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!desc_ok(desc) || !dev_storage) return IMPACT_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_storage) % kPlaneAlign) return IMPACT_ERR_INVALID_ARG;
+    const Planes p = plane_layout(*desc);
+    if (bytes < p.total) return IMPACT_ERR_INVALID_ARG;
+    impact_buffer *b = new (std::nothrow) impact_buffer;
+    if (!b) return IMPACT_ERR_INVALID_ARG;
+    b->desc = *desc;
+    b->planes = p;
+    b->storage = static_cast<char *>(dev_storage);
+    try {
+        b->count.assign((size_t)desc->num_slots, -1);
+    } catch (...) {
+        delete b;
+        return IMPACT_ERR_INVALID_ARG;
+    }
+    b->w = b->r = b->live = 0;
+    *out = b;
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_destroy(impact_buffer_t *buf)
+{
+    delete buf;
+    return IMPACT_OK;
+}
+
+int32_t impact_buffer_num_live(impact_buffer_t *buf)
+{
+    if (!buf) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    return buf->live;
+}
+
+impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *out_slots)
+{
+    if (!buf || n < 0 || (n > 0 && !out_slots)) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    if (buf->desc.num_slots - buf->live < n) return IMPACT_ERR_BUFFER_FULL;
+    buf->reserve(n, out_slots);
+    return IMPACT_OK;
+}
+
+// Enqueue the copies of one field for a list of slots, one launch per run of consecutive slots.
+static void scatter_field(PlaneKind kind, const void *src, void *dst, int T, int n, int Wd, const int32_t *slots,
+                          hipStream_t s)
+{
+    int i = 0;
+    while (i < n) {
+        int j = i + 1;
+        while (j < n && slots[j] == slots[j - 1] + 1) ++j;
+        PlaneCopyArgs a{src, dst, T, n, Wd, i, slots[i], j - i};
+        launch_insert_plane(kind, a, s);
+        i = j;
+    }
+}
+
+impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impact_batch_t *src, int32_t *out_slots,
+                                     impact_stream_t stream)
+{
+    if (!buf || n < 0) return IMPACT_ERR_INVALID_ARG;
+    if (n == 0) return IMPACT_OK;
+    if (!src || !out_slots || !src->worker_dist || !src->actions || !src->rewards || !src->dones)
+        return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    if (buf->desc.num_slots - buf->live < n) return IMPACT_ERR_BUFFER_FULL;
+    const int32_t w0 = buf->w;
+    buf->reserve(n, out_slots);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const impact_buffer_desc_t &d = buf->desc;
+    const PlaneKind fk = d.storage == IMPACT_F32 ? PLANE_F32_TO_F32 : PLANE_F32_TO_BF16;
+    char *base = buf->storage;
+    (void)hipGetLastError();
+    scatter_field(fk, src->worker_dist, base + buf->planes.worker, d.T, n, buf->W(), out_slots, s);
+    if (src->target_dist)
+        scatter_field(fk, src->target_dist, base + buf->planes.target, d.T, n, buf->W(), out_slots, s);
+    if (d.dist == IMPACT_CATEGORICAL)
+        scatter_field(PLANE_I32, src->actions, base + buf->planes.actions, d.T, n, 1, out_slots, s);
+    else
+        scatter_field(fk, src->actions, base + buf->planes.actions, d.T, n, d.A, out_slots, s);
+    scatter_field(fk, src->rewards, base + buf->planes.rewards, d.T, n, 1, out_slots, s);
+    scatter_field(PLANE_U8, src->dones, base + buf->planes.dones, d.T, n, 1, out_slots, s);
+    if (hipGetLastError() != hipSuccess) {
+        // undo the bookkeeping: the slots just reserved become empty again
+        for (int32_t i = 0; i < n; ++i) buf->count[out_slots[i]] = -1;
+        buf->live -= n;
+        buf->w = w0;
+        return IMPACT_ERR_HIP;
+    }
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const int32_t *slots,
+                                         const float *target_dist, impact_stream_t stream)
+{
+    if (!buf || n < 0) return IMPACT_ERR_INVALID_ARG;
+    if (n == 0) return IMPACT_OK;
+    if (!slots || !target_dist) return IMPACT_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (slots[i] < 0 || slots[i] >= buf->desc.num_slots) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    const impact_buffer_desc_t &d = buf->desc;
+    const PlaneKind fk = d.storage == IMPACT_F32 ? PLANE_F32_TO_F32 : PLANE_F32_TO_BF16;
+    (void)hipGetLastError();
+    scatter_field(fk, target_dist, buf->storage + buf->planes.target, d.T, n, buf->W(), slots,
+                  static_cast<hipStream_t>(stream));
+    return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
+}
+
+impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *out_slots, int32_t *out_counts)
+{
+    if (!buf || B < 0) return IMPACT_ERR_INVALID_ARG;
+    if (B == 0) return IMPACT_OK;
+    if (!out_slots || !out_counts) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    if (buf->live < B) return IMPACT_ERR_NOT_ENOUGH_LIVE;
+    const int32_t N = buf->desc.num_slots, K = buf->desc.K;
+    int32_t r = buf->r;
+    for (int32_t i = 0; i < B; ++i) {
+        while (buf->count[r] < 0) r = (r + 1 == N) ? 0 : r + 1;
+        out_slots[i] = r;
+        out_counts[i] = buf->count[r];
+        if (++buf->count[r] == K) {
+            buf->count[r] = -1;
+            --buf->live;
+        }
+        r = (r + 1 == N) ? 0 : r + 1;
+    }
+    buf->r = r;
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
+                                     const impact_batch_t *dst, impact_stream_t stream)
+{
+    if (!buf || B < 0) return IMPACT_ERR_INVALID_ARG;
+    if (B == 0) return IMPACT_OK;
+    if (!dev_slots || !dst) return IMPACT_ERR_INVALID_ARG;
+    const impact_buffer_desc_t &d = buf->desc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const char *base = buf->storage;
+    const int es = buf->es();
+    (void)hipGetLastError();
+    auto go = [&](size_t plane, const void *out, int Wd, int eb) {
+        if (!out) return;
+        GatherArgs a{base + plane, const_cast<void *>(out), dev_slots, d.T, B, Wd, d.num_slots, eb};
+        launch_gather_plane(a, s);
+    };
+    go(buf->planes.worker, dst->worker_dist, buf->W(), es);
+    go(buf->planes.target, dst->target_dist, buf->W(), es);
+    if (d.dist == IMPACT_CATEGORICAL) go(buf->planes.actions, dst->actions, 1, 4);
+    else go(buf->planes.actions, dst->actions, d.A, es);
+    go(buf->planes.rewards, dst->rewards, 1, es);
+    go(buf->planes.dones, dst->dones, 1, 1);
+    return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
+}
+
+size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A)
+{
+    if ((dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) || T < 1 || B < 1 || A < 1) return 0;
+    return align_up((size_t)num_tiles(B) * PARTIAL_STRIDE * sizeof(float), 256);
+}
+
+static bool config_ok(const impact_loss_config_t *c)
+{
+    if (!c) return false;
+    const float fin[] = {c->gamma, c->lambda, c->rho_bar, c->c_bar, c->vf_coeff, c->ent_coeff, c->kl_coeff};
+    for (float x : fin)
+        if (!std::isfinite(x)) return false;
+    if (c->rho_bar < 0.f || c->c_bar < 0.f) return false;
+    if (std::isnan(c->rho_clip) || c->rho_clip < 1.f) return false;
+    if (std::isnan(c->eps) || c->eps < 0.f) return false;
+    return true;
+}
+
+static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int B, int A, int num_slots,
+                                const int32_t *dev_slots, const float *learner,
+                                const float *values, const float *bootstrap, const impact_batch_t &batch,
+                                const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
+                                size_t workspace_bytes, hipStream_t s)
+{
+    if (dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) return IMPACT_ERR_INVALID_ARG;
+    if (dtype != IMPACT_F32 && dtype != IMPACT_BF16) return IMPACT_ERR_INVALID_ARG;
+    if (T < 1 || B < 1 || A < 1 || A > (1 << 20)) return IMPACT_ERR_INVALID_ARG;
+    if (!config_ok(cfg) || !out) return IMPACT_ERR_INVALID_ARG;
+    if (!learner || !values || !bootstrap || !batch.worker_dist || !batch.target_dist || !batch.actions ||
+        !batch.rewards || !batch.dones)
+        return IMPACT_ERR_INVALID_ARG;
+    if (!out->grad_learner_dist || !out->grad_values || !out->loss5 || !workspace) return IMPACT_ERR_INVALID_ARG;
+    if (workspace_bytes < impact_loss_workspace_bytes(dist, T, B, A)) return IMPACT_ERR_INVALID_ARG;
+    const void *ptrs[] = {learner, values, bootstrap, batch.worker_dist, batch.target_dist, batch.actions,
+                          batch.rewards, out->grad_learner_dist, out->grad_values, workspace};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return IMPACT_ERR_INVALID_ARG;
+    if ((out->vs && !aligned16(out->vs)) || (out->adv && !aligned16(out->adv))) return IMPACT_ERR_INVALID_ARG;
+    if ((double)T * B * (2.0 * A) > 1.0e12) return IMPACT_ERR_INVALID_ARG;
+
+    LossArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.T = T; a.B = B; a.A = A;
+    a.learner = learner; a.values = values; a.bootstrap = bootstrap;
+    a.worker = batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
+    a.rewards = batch.rewards; a.dones = batch.dones;
+    a.slots = dev_slots; a.num_slots = num_slots;
+    a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
+    a.log_beta = std::isinf(cfg->rho_clip) ? -INFINITY : -std::log(cfg->rho_clip);
+    a.clip_lo = std::isinf(cfg->eps) ? -INFINITY : 1.f - cfg->eps;
+    a.clip_hi = std::isinf(cfg->eps) ? INFINITY : 1.f + cfg->eps;
+    a.vf_coeff = cfg->vf_coeff; a.ent_coeff = cfg->ent_coeff; a.kl_coeff = cfg->kl_coeff;
+    const double M = (double)T * (double)B;
+    a.inv_M = (float)(1.0 / M);
+    a.grad_dist = out->grad_learner_dist; a.grad_values = out->grad_values;
+    a.vs = out->vs; a.adv = out->adv;
+    a.partials = static_cast<float *>(workspace);
+
+    // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
+    const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
+    const int es = dtype == IMPACT_F32 ? 4 : 2;
+    bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
+    // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
+    if ((double)B * W * 4.0 * RW >= 2147483648.0) fast = false;
+    if (slot_major && (double)num_slots * T >= 2147483648.0) fast = false;
+    if (fast && slot_major) {
+        // every slot's trajectory must start on a 16-byte boundary in each staged plane
+        if (((size_t)T * W * es) % 16) fast = false;
+        if (dist == IMPACT_DIAG_GAUSSIAN && ((size_t)T * A * es) % 16) fast = false;
+    }
+    (void)hipGetLastError();
+    bool launched = false;
+    if (fast) {
+        launched = dist == IMPACT_CATEGORICAL ? launch_loss_cat_static(dtype, slot_major, a, s)
+                                              : launch_loss_gauss_static(dtype, slot_major, a, s);
+    }
+    if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
+    ReduceArgs r{a.partials, num_tiles(B), 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
+    launch_reduce(r, s);
+    return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
+}
+
+impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
+                                    const float *learner_dist, const float *values, const float *bootstrap,
+                                    const impact_batch_t *batch, const impact_loss_config_t *cfg,
+                                    const impact_loss_out_t *out, void *workspace, size_t workspace_bytes,
+                                    impact_stream_t stream)
+{
+    if (!batch) return IMPACT_ERR_INVALID_ARG;
+    return run_loss(dist, batch_dtype, false, T, B, A, 0, nullptr, learner_dist, values, bootstrap, *batch, cfg,
+                    out, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
+                                                const float *learner_dist, const float *values,
+                                                const float *bootstrap, const impact_loss_config_t *cfg,
+                                                const impact_loss_out_t *out, void *workspace,
+                                                size_t workspace_bytes, impact_stream_t stream)
+{
+    if (!buf || !dev_slots) return IMPACT_ERR_INVALID_ARG;
+    const impact_buffer_desc_t &d = buf->desc;
+    const char *base = buf->storage;
+    impact_batch_t batch;
+    batch.worker_dist = base + buf->planes.worker;
+    batch.target_dist = base + buf->planes.target;
+    batch.actions = base + buf->planes.actions;
+    batch.rewards = base + buf->planes.rewards;
+    batch.dones = reinterpret_cast<const uint8_t *>(base + buf->planes.dones);
+    return run_loss(d.dist, d.storage, true, d.T, B, d.A, d.num_slots, dev_slots, learner_dist, values,
+                    bootstrap, batch, cfg, out, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

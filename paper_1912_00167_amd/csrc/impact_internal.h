@@ -1,0 +1,88 @@
+// Internal declarations shared by the host code and the HIP kernels of libimpact.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "impact.h"
+
+namespace impact {
+
+// Tiling of the loss kernels: a workgroup of 256 threads owns NB consecutive
+// trajectories and sweeps time backwards in chunks of TC steps; thread
+// (tl, bl) handles step (t0 + tl, b0 + bl).  A wavefront covers RW = 64 / NB
+// consecutive time rows of the tile.
+constexpr int NB = 8;
+constexpr int TC = 32;
+constexpr int NTHREADS = NB * TC;
+constexpr int NWAVES = NTHREADS / 64;
+constexpr int RW = 64 / NB;
+constexpr int PARTIAL_STRIDE = 8;   // floats per workgroup in the partial-sum workspace
+
+struct LossArgs {
+    int T, B, A;
+    // learner side, always time-major fp32
+    const float *learner;     // [T][B][W]
+    const float *values;      // [T][B]
+    const float *bootstrap;   // [B]
+    // buffer-resident side: time-major [T][B][..] or slot-major [slot][T][..]
+    const void *worker;
+    const void *target;
+    const void *actions;
+    const void *rewards;
+    const uint8_t *dones;
+    const int32_t *slots;     // device [B]; slot-major only
+    int num_slots;
+    // hyper-parameters, pre-digested on the host
+    float gamma, lambda, rho_bar, c_bar;
+    float log_beta;           // -log(rho_clip); -inf when rho_clip = +inf
+    float clip_lo, clip_hi;   // 1 - eps, 1 + eps (-inf / +inf when eps = +inf)
+    float vf_coeff, ent_coeff, kl_coeff;
+    float inv_M;              // 1 / (T * B)
+    // outputs
+    float *grad_dist;         // [T][B][W]
+    float *grad_values;       // [T][B]
+    float *vs;                // [T][B] or null
+    float *adv;               // [T][B] or null
+    float *partials;          // [num_tiles][PARTIAL_STRIDE]
+};
+
+struct ReduceArgs {
+    const float *partials;
+    int num_tiles;
+    double inv_M;
+    float vf_coeff, ent_coeff, kl_coeff;
+    float *loss5;
+};
+
+inline int num_tiles(int B) { return (B + NB - 1) / NB; }
+
+// Launchers (defined in the .hip files).  `slot_major` selects the fused-gather addressing.
+// Return false when no specialised kernel exists for (A, alignment): the caller then uses the generic one.
+bool launch_loss_cat_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+void launch_reduce(const ReduceArgs &r, hipStream_t s);
+
+// Buffer data movement.  A "run" is cnt consecutive slots starting at slot0 that take
+// trajectories i0 .. i0+cnt-1 of a time-major source with n trajectories.
+struct PlaneCopyArgs {
+    const void *src;     // time-major [T][n][Wd]
+    void *dst;           // slot-major [N][T][Wd]
+    int T, n, Wd;
+    int i0, slot0, cnt;
+};
+enum PlaneKind { PLANE_F32_TO_F32, PLANE_F32_TO_BF16, PLANE_I32, PLANE_U8 };
+void launch_insert_plane(PlaneKind kind, const PlaneCopyArgs &a, hipStream_t s);
+
+struct GatherArgs {
+    const void *src;     // slot-major plane [N][T][Wd]
+    void *dst;           // time-major [T][B][Wd]
+    const int32_t *slots;
+    int T, B, Wd, num_slots;
+    int elem_bytes;      // 1, 2 or 4
+};
+void launch_gather_plane(const GatherArgs &a, hipStream_t s);
+
+}  // namespace impact

@@ -1,0 +1,111 @@
+"""Helpers shared by the GPU parity tests: run the HIP path through the binding, run the
+oracle on the same arrays, compare with the stated tolerance."""
+from __future__ import annotations
+
+import math
+import sys
+from dataclasses import replace
+
+import numpy as np
+
+import oracle
+import workloads
+from oracle.buffer import bf16_bits_to_f32
+
+ATOL, RTOL = 1e-6, 1e-5       # fp32 results against the fp64 oracle: |x - y| <= ATOL + RTOL |y|
+
+
+def say(msg: str) -> None:
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_device(x, torch, device="cuda"):
+    return {k: torch.from_numpy(np.ascontiguousarray(v)).to(device) for k, v in x.items()}
+
+
+def shape_workload(base: workloads.Workload, **kw) -> workloads.Workload:
+    return replace(base, **kw)
+
+
+def oracle_inputs(x, storage: str):
+    """What the oracle consumes: the same arrays, the buffer-resident float fields first rounded
+    to the storage dtype (by the oracle's own rounding) and then widened exactly."""
+    if storage == "f32":
+        return x
+    y = dict(x)
+    for k in ("worker", "target", "rewards"):
+        y[k] = oracle.quantize_bf16(x[k])[1]
+    if x["actions"].dtype != np.int32:
+        y["actions"] = oracle.quantize_bf16(x["actions"])[1]
+    return y
+
+
+def run_oracle(wl, x, hyper=None, n_threads=8):
+    h = wl.hyper if hyper is None else hyper
+    cfg = oracle.config_from_hyper(h)
+    xi = oracle_inputs(x, wl.storage)
+    return oracle.impact_loss(wl.dist, xi["learner"], xi["target"], xi["worker"], xi["actions"], xi["rewards"],
+                              xi["dones"], xi["values"], xi["bootstrap"], cfg, n_threads=n_threads), xi, cfg
+
+
+def max_violation(got, want, scale=1.0):
+    got = np.asarray(got, np.float64) * scale
+    want = np.asarray(want, np.float64) * scale
+    err = np.abs(got - want)
+    return float(np.max(err / (ATOL + RTOL * np.abs(want)))) if err.size else 0.0
+
+
+def check_against_oracle(wl, x, got, hyper=None, label=""):
+    """got: dict of numpy arrays from the GPU (grad_dist, grad_values, vs, adv, loss5)."""
+    h = wl.hyper if hyper is None else hyper
+    want, xi, cfg = run_oracle(wl, x, h)
+    M = wl.T * x["learner"].shape[1]
+    report = {}
+    for k in ("vs", "adv"):
+        if k in got:
+            report[k] = max_violation(got[k], want[k])
+    report["loss5"] = max_violation(got["loss5"], want["loss5"])
+    # gradients carry a 1/(T*B) factor: compare them rescaled, so that the absolute term stays meaningful
+    report["grad_values"] = max_violation(got["grad_values"], want["grad_values"], M)
+
+    gd_got, gd_want = got["grad_dist"].astype(np.float64) * M, want["grad_dist"] * M
+    viol = np.abs(gd_got - gd_want) / (ATOL + RTOL * np.abs(gd_want))
+    # The min/clip of the surrogate makes the policy gradient discontinuous where R = 1 +- eps.
+    # A step whose fp64 ratio lies within rounding distance of such a kink may legitimately fall on
+    # either side in fp32: there the GPU value must match one of the two branches.
+    if math.isfinite(h.eps):
+        R = want["ratio"]
+        near = (np.abs(R - (1 + h.eps)) <= 2e-5 * (1 + h.eps)) | (np.abs(R - (1 - h.eps)) <= 2e-5)
+        if near.any():
+            kw = dict(dist=wl.dist, learner=xi["learner"], target=xi["target"], worker=xi["worker"],
+                      actions=xi["actions"], values=xi["values"], vs=want["vs"])
+            open_cfg = oracle.make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, math.inf, h.vf_coeff,
+                                          h.ent_coeff, h.kl_coeff)
+            g_on = oracle.loss_given_targets(adv=want["adv"], cfg=open_cfg, **kw)["grad_dist"] * M
+            g_off = oracle.loss_given_targets(adv=np.zeros_like(want["adv"]), cfg=cfg, **kw)["grad_dist"] * M
+            for g_alt in (g_on, g_off):
+                alt = np.abs(gd_got - g_alt) / (ATOL + RTOL * np.abs(g_alt))
+                viol[near] = np.minimum(viol[near], alt[near])
+            report["near_kink_steps"] = int(near.sum())
+    report["grad_dist"] = float(viol.max())
+    say(f"    parity {label}: " + ", ".join(f"{k}={v:.3g}" if isinstance(v, float) else f"{k}={v}"
+                                              for k, v in report.items()))
+    for k in ("vs", "adv", "loss5", "grad_values", "grad_dist"):
+        if k in report:
+            assert report[k] <= 1.0, f"{label}: {k} exceeds tolerance by factor {report[k]:.3g}"
+    for k in ("grad_dist", "grad_values", "loss5"):
+        assert np.all(np.isfinite(got[k])), f"{label}: non-finite {k}"
+    return want
+
+
+def gpu_loss(torch, binding, wl, x, hyper=None, flags=0, want_targets=True):
+    """Time-major fp32 batch through impact_loss_fwd_bwd; returns numpy outputs."""
+    h = wl.hyper if hyper is None else hyper
+    d = to_device(x, torch)
+    T, Bn, W = x["learner"].shape
+    out = binding.alloc_loss_out(T, Bn, W, want_targets=want_targets)
+    cfg = binding.config_from_hyper(h, flags)
+    binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg, out=out)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}

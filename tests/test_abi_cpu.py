@@ -1,0 +1,181 @@
+"""The C-ABI library: it loads, exports what the header declares, and its host-side logic
+(argument checks, ring bookkeeping) behaves -- none of this needs a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.buffer import BufferFull, NotEnoughLive, RingOracle
+from paper_1912_00167_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_DEV = ctypes.c_void_p(0x7000_0000_0000)      # 256-aligned, never dereferenced by host-only calls
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1912_00167_amd import build
+        build.build()
+    return B.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "impact.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(impact_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.impact_version() == "0.1"
+    assert B.status_string(0) == "ok" and "full" in B.status_string(B.IMPACT_ERR_BUFFER_FULL)
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(B.impact_buffer_desc_t) == 24
+    assert ctypes.sizeof(B.impact_loss_config_t) == 40
+    assert ctypes.sizeof(B.impact_batch_t) == 5 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(B.impact_loss_out_t) == 5 * ctypes.sizeof(ctypes.c_void_p)
+
+
+def _create(lib, dist=0, T=4, A=3, N=8, K=2, storage=0, ptr=FAKE_DEV, nbytes=None):
+    d = B.impact_buffer_desc_t(dist, T, A, N, K, storage)
+    need = lib.impact_buffer_storage_bytes(ctypes.byref(d))
+    h = ctypes.c_void_p()
+    rc = lib.impact_buffer_create(ctypes.byref(d), ptr, need if nbytes is None else nbytes, ctypes.byref(h))
+    return rc, h, need
+
+
+def test_storage_bytes_cover_all_planes(lib):
+    for dist, storage in ((0, 0), (0, 1), (1, 0), (1, 1)):
+        T, A, N = 7, 5, 11
+        d = B.impact_buffer_desc_t(dist, T, A, N, 2, storage)
+        es = 4 if storage == 0 else 2
+        W = A if dist == 0 else 2 * A
+        payload = N * T * (2 * W * es + (4 if dist == 0 else A * es) + es + 1)
+        got = lib.impact_buffer_storage_bytes(ctypes.byref(d))
+        assert payload + 5 * 16 <= got <= payload + 5 * (16 + 256)
+        assert got % 256 == 0
+
+
+def test_invalid_descriptors_and_arguments(lib):
+    for kw in (dict(K=0), dict(N=0), dict(T=0), dict(A=0), dict(dist=2), dict(storage=3)):
+        d = dict(dist=0, T=4, A=3, N=8, K=2, storage=0)
+        d.update(kw)
+        desc = B.impact_buffer_desc_t(d["dist"], d["T"], d["A"], d["N"], d["K"], d["storage"])
+        assert lib.impact_buffer_storage_bytes(ctypes.byref(desc)) == 0
+        rc, h, _ = _create(lib, **d)
+        assert rc == B.IMPACT_ERR_INVALID_ARG and not h
+    rc, h, need = _create(lib, ptr=None)
+    assert rc == B.IMPACT_ERR_INVALID_ARG
+    rc, h, need = _create(lib, ptr=ctypes.c_void_p(0x7000_0000_0010))     # not 256-aligned
+    assert rc == B.IMPACT_ERR_INVALID_ARG
+    rc, h, need = _create(lib, nbytes=100)                                  # too small
+    assert rc == B.IMPACT_ERR_INVALID_ARG
+    rc, h, need = _create(lib)
+    assert rc == B.IMPACT_OK and h
+    out = (ctypes.c_int32 * 4)()
+    assert lib.impact_buffer_sample(h, 2, None, out) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_sample(h, -1, out, out) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_reserve(h, 2, None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_sample(None, 1, out, out) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_insert(h, 1, None, out, None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_put_target(h, 1, out, None, None) == B.IMPACT_ERR_INVALID_ARG
+    bad_slots = (ctypes.c_int32 * 1)(99)
+    assert lib.impact_buffer_put_target(h, 1, bad_slots, FAKE_DEV, None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_gather(h, 1, None, None, None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_sample(h, 0, None, None) == B.IMPACT_OK          # empty request: no-op
+    assert lib.impact_buffer_insert(h, 0, None, None, None) == B.IMPACT_OK
+    assert lib.impact_buffer_destroy(h) == B.IMPACT_OK
+    assert lib.impact_buffer_destroy(None) == B.IMPACT_OK
+
+
+def test_loss_argument_checks_happen_before_any_device_work(lib):
+    assert lib.impact_loss_workspace_bytes(0, 0, 8, 4) == 0
+    assert lib.impact_loss_workspace_bytes(2, 4, 8, 4) == 0
+    ws = lib.impact_loss_workspace_bytes(0, 100, 8192, 18)
+    assert ws >= (8192 // 8) * 8 * 4 and ws % 256 == 0
+    p = FAKE_DEV
+    batch = B.impact_batch_t(p, p, p, p, p)
+    out = B.impact_loss_out_t(p, p, None, None, p)
+    good = B.make_config()
+    call = lambda cfg=good, T=4, Bn=8, A=3, b=batch, o=out, w=p, wb=ws, dist=0, dt=0, learner=p: \
+        lib.impact_loss_fwd_bwd(dist, dt, T, Bn, A, learner, p, p, ctypes.byref(b) if b else None,
+                                ctypes.byref(cfg) if cfg else None, ctypes.byref(o) if o else None, w, wb, None)
+    E = B.IMPACT_ERR_INVALID_ARG
+    assert call(T=0) == E and call(Bn=0) == E and call(A=0) == E          # empty inputs
+    assert call(dist=5) == E and call(dt=7) == E
+    assert call(cfg=None) == E and call(b=None) == E and call(o=None) == E and call(w=None) == E
+    assert call(wb=8) == E                                                 # workspace too small
+    assert call(learner=None) == E
+    assert call(learner=ctypes.c_void_p(0x7000_0000_0004)) == E            # misaligned
+    assert call(b=B.impact_batch_t(p, None, p, p, p)) == E
+    assert call(o=B.impact_loss_out_t(p, None, None, None, p)) == E
+    for kw in (dict(gamma=float("nan")), dict(lam=float("inf")), dict(rho_bar=-1.0), dict(c_bar=-0.5),
+               dict(rho_clip=0.5), dict(rho_clip=float("nan")), dict(eps=-0.1), dict(vf_coeff=float("inf"))):
+        assert call(cfg=B.make_config(**kw)) == E, kw
+
+
+def _lib_state_walk(lib, N, K, seed, steps=300):
+    rng = np.random.default_rng(seed)
+    rc, h, _ = _create(lib, N=N, K=K)
+    assert rc == 0
+    ring = RingOracle(N, K)
+    for _ in range(steps):
+        if rng.random() < 0.5:
+            n = int(rng.integers(0, N + 2))
+            out = np.full(max(n, 1), -7, np.int32)
+            rc = lib.impact_buffer_reserve(h, n, out.ctypes.data_as(ctypes.c_void_p))
+            try:
+                want = ring.insert(n)
+                assert rc == B.IMPACT_OK
+                assert out[:n].tolist() == want
+            except BufferFull:
+                assert rc == B.IMPACT_ERR_BUFFER_FULL
+                assert np.all(out == -7)                       # untouched
+        else:
+            Bn = int(rng.integers(0, N + 2))
+            s = np.full(max(Bn, 1), -7, np.int32)
+            c = np.full(max(Bn, 1), -7, np.int32)
+            rc = lib.impact_buffer_sample(h, Bn, s.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p))
+            try:
+                ws, wc = ring.sample(Bn)
+                assert rc == B.IMPACT_OK
+                assert s[:Bn].tolist() == ws and c[:Bn].tolist() == wc
+            except NotEnoughLive:
+                assert rc == B.IMPACT_ERR_NOT_ENOUGH_LIVE
+                assert np.all(s == -7) and np.all(c == -7)
+        assert lib.impact_buffer_num_live(h) == ring.num_live()
+    lib.impact_buffer_destroy(h)
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 1), (4, 2), (8, 3), (64, 2), (257, 5)])
+def test_ring_bookkeeping_is_bit_exact_with_the_oracle(lib, N, K):
+    for seed in range(4):
+        _lib_state_walk(lib, N, K, seed)
+
+
+def test_ring_at_full_workload_size_matches_oracle(lib):
+    # the largest ring of the workloads: 65536 slots, K = 4, batches of 16384
+    N, K, Bn = 65536, 4, 16384
+    rc, h, _ = _create(lib, dist=1, T=128, A=17, N=N, K=K, storage=1)
+    assert rc == 0
+    ring = RingOracle(N, K)
+    out = np.empty(N, np.int32)
+    assert lib.impact_buffer_reserve(h, N, out.ctypes.data_as(ctypes.c_void_p)) == 0
+    assert out.tolist() == ring.insert(N)
+    s, c = np.empty(Bn, np.int32), np.empty(Bn, np.int32)
+    for step in range(N * K // Bn):
+        assert lib.impact_buffer_sample(h, Bn, s.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p)) == 0
+        ws, wc = ring.sample(Bn)
+        assert np.array_equal(s, np.asarray(ws, np.int32)) and np.array_equal(c, np.asarray(wc, np.int32))
+        if step == 11:      # three full passes done: nothing has been traversed K times yet
+            assert lib.impact_buffer_num_live(h) == N
+        if step == 13:      # half of the fourth pass: half of the ring discarded
+            assert lib.impact_buffer_num_live(h) == N // 2
+    assert lib.impact_buffer_num_live(h) == 0
+    assert lib.impact_buffer_sample(h, 1, s.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p)) \
+        == B.IMPACT_ERR_NOT_ENOUGH_LIVE
+    lib.impact_buffer_destroy(h)

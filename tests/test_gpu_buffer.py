@@ -1,0 +1,185 @@
+"""GPU parity of the circular buffer (insert, put_target, gather: bit-exact) and of the loss
+with the gather fused in, against the CPU oracles, through the C ABI."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import workloads
+from gpu_common import check_against_oracle, say, shape_workload, to_device
+from oracle.buffer import BufferOracle, bf16_bits_to_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_1912_00167_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()
+    return torch, binding
+
+
+def _bits(t, torch):
+    """Raw bytes of a device tensor as a numpy array (bf16 -> uint16 patterns)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def _assert_same_bytes(a, b, what):
+    a, b = np.ascontiguousarray(a), np.ascontiguousarray(b)
+    assert a.shape == b.shape and a.dtype.itemsize == b.dtype.itemsize, what
+    assert a.tobytes() == b.tobytes(), what
+
+
+def _fill(torch, binding, buf, ob, wl, n, stream, with_target=True):
+    x = workloads.make_trajectories(wl, n, stream=stream)
+    d = to_device(x, torch)
+    src = {k: d[k] for k in ("worker", "actions", "rewards", "dones")}
+    if with_target:
+        src["target"] = d["target"]
+    slots = binding.impact_buffer_insert(buf, src)
+    want = ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"],
+                             target=x["target"] if with_target else None)
+    assert slots.tolist() == want
+    return x, slots
+
+
+@pytest.mark.parametrize("dist", ["categorical", "gaussian"])
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_insert_sample_gather_bit_exact(env, dist, storage):
+    torch, binding = env
+    base = workloads.C1 if dist == "categorical" else workloads.C3
+    wl = shape_workload(base, T=13, A=5, num_slots=24, K=2, storage=storage)
+    say(f"case buffer round trip {dist} {storage}")
+    buf = binding.Buffer(dist, wl.T, wl.A, wl.num_slots, wl.K, storage)
+    ob = BufferOracle(dist, wl.T, wl.A, wl.num_slots, wl.K, storage)
+    _fill(torch, binding, buf, ob, wl, 10, 1)
+    # target appended later for the next group (Algorithm 1: evaluate on target when k = 0)
+    x2, slots2 = _fill(torch, binding, buf, ob, wl, 7, 2, with_target=False)
+    binding.impact_buffer_put_target(buf, slots2, to_device({"t": x2["target"]}, torch)["t"])
+    ob.put_target(slots2.tolist(), x2["target"])
+    rng = np.random.default_rng(0)
+    for step in range(12):
+        Bn = int(rng.integers(1, 9))
+        if binding.impact_buffer_num_live(buf) < Bn:
+            n = int(rng.integers(1, wl.num_slots - ob.num_live() + 1))
+            _fill(torch, binding, buf, ob, wl, n, 10 + step)      # lands in fragmented free slots
+        slots, counts = binding.impact_buffer_sample(buf, Bn)
+        ws, wc = ob.sample(Bn)
+        assert slots.tolist() == ws and counts.tolist() == wc
+        got = binding.impact_buffer_gather(buf, torch.from_numpy(slots).cuda())
+        torch.cuda.synchronize()
+        want = ob.gather(ws)
+        for k in ("worker", "target", "actions", "rewards", "dones"):
+            _assert_same_bytes(_bits(got[k], torch), want[k], f"{k} step {step}")
+    buf.close()
+
+
+def test_gather_full_ring_large(env):
+    torch, binding = env
+    wl = shape_workload(workloads.C2, B=512, num_slots=1024, K=1)
+    say("case gather C2-sized")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, "f32")
+    ob = BufferOracle(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, "f32")
+    _fill(torch, binding, buf, ob, wl, 1024, 0)
+    perm = np.random.default_rng(1).permutation(1024)[:512].astype(np.int32)
+    got = binding.impact_buffer_gather(buf, torch.from_numpy(perm).cuda())
+    torch.cuda.synchronize()
+    want = ob.gather(perm.tolist())
+    for k in ("worker", "target", "actions", "rewards", "dones"):
+        _assert_same_bytes(_bits(got[k], torch), want[k], k)
+    buf.close()
+
+
+def _fused_case(torch, binding, wl, n_fill, Bn, flags, seed, label):
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, n_fill, stream=seed)
+    d = to_device(x, torch)
+    slots_in = binding.impact_buffer_insert(buf, d)
+    assert slots_in.tolist() == list(range(n_fill))
+    # take a non-trivial subset in a shuffled order so that slot != batch index
+    slots, _ = binding.impact_buffer_sample(buf, Bn)
+    order = np.random.default_rng(seed).permutation(Bn)
+    slots = np.ascontiguousarray(slots[order])
+    xb = workloads.take_trajectories(x, slots)              # the batch those slots hold, time-major
+    dev_slots = torch.from_numpy(slots).cuda()
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    cfg = binding.config_from_hyper(wl.hyper, flags)
+    out = binding.impact_loss_fwd_bwd_from_buffer(buf, dev_slots, learner, values, boot, cfg)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    check_against_oracle(replace(wl, B=Bn), xb, got, label=label)
+    # the unfused route (gather, then the time-major loss) must agree bit for bit with the fused one
+    g = binding.impact_buffer_gather(buf, dev_slots)
+    out2 = binding.impact_loss_fwd_bwd(wl.dist, learner, values, boot, g, cfg)
+    torch.cuda.synchronize()
+    for k in ("vs", "adv", "grad_values", "grad_dist", "loss5"):
+        np.testing.assert_array_equal(got[k], out2[k].cpu().numpy(), err_msg=f"{label}: fused vs gather+loss {k}")
+    buf.close()
+
+
+FUSED = [
+    ("C1", dict(), 64, 32), ("C2", dict(B=128, num_slots=256), 256, 128),
+    ("C3", dict(B=128, num_slots=256), 256, 128),
+    ("C5", dict(B=64, num_slots=128), 128, 64),                       # bf16 storage, D = 17
+    ("C4", dict(B=64, num_slots=128, storage="bf16"), 128, 64),       # bf16 storage, categorical
+    ("C2", dict(T=37, B=21, A=7, num_slots=40), 40, 21),              # generic kernels, ragged
+    ("C5", dict(T=45, B=19, A=4, num_slots=32), 32, 19),              # generic kernels, bf16, ragged
+]
+
+
+@pytest.mark.parametrize("ci", range(len(FUSED)))
+@pytest.mark.parametrize("flags", [0, 1], ids=["specialised", "generic"])
+def test_loss_from_buffer(env, ci, flags):
+    torch, binding = env
+    name, kw, n_fill, Bn = FUSED[ci]
+    wl = shape_workload(workloads.WORKLOADS[name], **kw)
+    say(f"case fused {name} {kw} flags={flags}")
+    _fused_case(torch, binding, wl, n_fill, Bn, flags, seed=ci, label=f"fused {name} {kw} flags={flags}")
+
+
+def test_out_of_range_slot_is_flagged_not_dereferenced(env):
+    torch, binding = env
+    wl = shape_workload(workloads.C1, num_slots=16)
+    say("case bad slot")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, "f32")
+    x = workloads.make_trajectories(wl, 16, stream=0)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots = np.arange(8, dtype=np.int32)
+    slots[3] = 1_000_000
+    slots[5] = -2
+    xb = workloads.take_trajectories(x, np.clip(slots, 0, 15))
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    for flags in (0, 1):
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot,
+                                                      binding.config_from_hyper(wl.hyper, flags))
+        torch.cuda.synchronize()
+        assert torch.isnan(out["loss5"]).all()
+        assert torch.isfinite(out["grad_dist"]).all()
+    g = binding.impact_buffer_gather(buf, torch.from_numpy(slots).cuda())
+    torch.cuda.synchronize()
+    assert torch.isfinite(g["worker"]).all()
+    buf.close()
+
+
+def test_errors_from_the_device_side_calls(env):
+    torch, binding = env
+    buf = binding.Buffer("categorical", 4, 3, 4, 1, "f32")
+    wl = shape_workload(workloads.C1, T=4, A=3, num_slots=4)
+    x = to_device(workloads.make_trajectories(wl, 3, stream=0), torch)
+    say("case device-side errors")
+    binding.impact_buffer_insert(buf, x)
+    with pytest.raises(binding.ImpactError) as e:
+        binding.impact_buffer_insert(buf, x)                 # 3 more do not fit in 1 free slot
+    assert e.value.status == binding.IMPACT_ERR_BUFFER_FULL
+    assert binding.impact_buffer_num_live(buf) == 3
+    with pytest.raises(binding.ImpactError) as e:
+        binding.impact_buffer_sample(buf, 4)
+    assert e.value.status == binding.IMPACT_ERR_NOT_ENOUGH_LIVE
+    slots, counts = binding.impact_buffer_sample(buf, 3)
+    assert slots.tolist() == [0, 1, 2] and counts.tolist() == [0, 0, 0]
+    assert binding.impact_buffer_num_live(buf) == 0          # K = 1: discarded after one traversal
+    buf.close()

@@ -1,0 +1,123 @@
+"""GPU parity of the loss kernels against the CPU oracle, through the C ABI."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import workloads
+from gpu_common import check_against_oracle, gpu_loss, say, shape_workload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_1912_00167_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    binding.load()                       # fails loudly when libimpact.so is not built
+    return torch, binding
+
+
+FORCE_GENERIC = 1
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+@pytest.mark.parametrize("flags", [0, FORCE_GENERIC], ids=["specialised", "generic"])
+def test_workloads_small(env, name, flags):
+    torch, binding = env
+    wl = replace(workloads.WORKLOADS[name], storage="f32")
+    say(f"case {name} flags={flags} T={wl.T} B={wl.B} A={wl.A}")
+    x = workloads.make_batch(wl, stream=0)
+    got = gpu_loss(torch, binding, wl, x, flags=flags)
+    check_against_oracle(wl, x, got, label=f"{name}/{'generic' if flags else 'specialised'}")
+
+
+RAGGED = [
+    ("categorical", 1, 1, 2), ("categorical", 33, 37, 5), ("categorical", 70, 9, 7), ("categorical", 31, 64, 33),
+    ("categorical", 64, 8, 18), ("categorical", 45, 24, 18), ("categorical", 7, 16, 4), ("categorical", 100, 40, 9),
+    ("gaussian", 1, 1, 1), ("gaussian", 33, 37, 2), ("gaussian", 65, 9, 5), ("gaussian", 40, 24, 17),
+    ("gaussian", 96, 16, 3), ("gaussian", 50, 8, 6),
+]
+
+
+@pytest.mark.parametrize("dist,T,Bn,A", RAGGED)
+def test_ragged_and_odd_shapes(env, dist, T, Bn, A):
+    torch, binding = env
+    base = workloads.C2 if dist == "categorical" else workloads.C3
+    wl = shape_workload(base, T=T, B=Bn, A=A, storage="f32")
+    say(f"case ragged {dist} T={T} B={Bn} A={A}")
+    x = workloads.make_batch(wl, stream=T * 1000 + Bn)
+    got = gpu_loss(torch, binding, wl, x)
+    check_against_oracle(wl, x, got, label=f"{dist} T{T} B{Bn} A{A}")
+
+
+HYPERS = [
+    dict(lam=0.995), dict(lam=0.9, gamma=0.9), dict(rho_clip=math.inf), dict(eps=math.inf),
+    dict(kl_coeff=0.7, ent_coeff=0.05), dict(rho_bar=1.5, c_bar=0.7), dict(rho_bar=0.0), dict(c_bar=0.0),
+    dict(vf_coeff=0.5, ent_coeff=0.0, kl_coeff=0.0), dict(eps=0.0), dict(rho_clip=1.0),
+]
+
+
+@pytest.mark.parametrize("dist", ["categorical", "gaussian"])
+@pytest.mark.parametrize("hi", range(len(HYPERS)))
+def test_hyper_parameter_variants(env, dist, hi):
+    torch, binding = env
+    base = workloads.C4 if dist == "categorical" else workloads.C3
+    wl = shape_workload(base, T=40, B=64, storage="f32")
+    h = replace(wl.hyper, **HYPERS[hi])
+    say(f"case hyper {dist} {HYPERS[hi]}")
+    x = workloads.make_batch(wl, stream=50 + hi)
+    for flags in (0, FORCE_GENERIC):
+        got = gpu_loss(torch, binding, wl, x, hyper=h, flags=flags)
+        check_against_oracle(wl, x, got, hyper=h, label=f"{dist} {HYPERS[hi]} flags={flags}")
+
+
+def test_optional_outputs_may_be_null(env):
+    torch, binding = env
+    wl = shape_workload(workloads.C2, B=16)
+    x = workloads.make_batch(wl, stream=3)
+    say("case null vs/adv")
+    a = gpu_loss(torch, binding, wl, x, want_targets=True)
+    b = gpu_loss(torch, binding, wl, x, want_targets=False)
+    assert "vs" not in b
+    for k in ("grad_dist", "grad_values", "loss5"):
+        np.testing.assert_array_equal(a[k], b[k])      # same launch shape: bit-identical
+
+
+def test_results_are_deterministic(env):
+    torch, binding = env
+    wl = shape_workload(workloads.C3, B=64)
+    x = workloads.make_batch(wl, stream=4)
+    say("case determinism")
+    a = gpu_loss(torch, binding, wl, x)
+    b = gpu_loss(torch, binding, wl, x)
+    for k in a:
+        np.testing.assert_array_equal(a[k], b[k])
+
+
+def test_out_of_range_action_is_flagged_not_dereferenced(env):
+    torch, binding = env
+    wl = shape_workload(workloads.C1, B=8)
+    x = workloads.make_batch(wl, stream=5)
+    x["actions"][3, 2] = 99
+    x["actions"][0, 0] = -4
+    say("case bad action")
+    for flags in (0, FORCE_GENERIC):
+        got = gpu_loss(torch, binding, wl, x, flags=flags)
+        assert np.all(np.isnan(got["loss5"]))
+        assert np.all(np.isfinite(got["grad_dist"]))
+
+
+@pytest.mark.parametrize("name", ["C4", "C5"])
+def test_full_size_workloads_time_major(env, name):
+    """The two large workloads at full size, every output element against the oracle."""
+    torch, binding = env
+    wl = replace(workloads.WORKLOADS[name], storage="f32")
+    say(f"case full {name} T={wl.T} B={wl.B} A={wl.A}: generating")
+    x = workloads.make_batch(wl, stream=0)
+    say("  gpu")
+    got = gpu_loss(torch, binding, wl, x)
+    say("  oracle")
+    check_against_oracle(wl, x, got, label=f"{name} full")

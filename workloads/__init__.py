@@ -145,12 +145,23 @@ def make_trajectories(wl: Workload, n: int, stream: int = 0) -> Dict[str, np.nda
         target = derive(wl.target_mode, wl.target_noise, learner, None)
         worker = derive(wl.worker_mode, wl.worker_noise, learner, target)
     else:
+        # Means and log standard deviations follow the same recipe: the learner's are drawn
+        # fresh, the target's and worker's are the stated small offsets away (a target
+        # network is a lagged copy of the learner, a worker a lagged copy of either), so
+        # every policy's log-std stays in (about) the stated range.
         l_mean = normal((T, n, A), wl.learner_std)
         l_lstd = g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
         t_mean = derive(wl.target_mode, wl.target_noise, l_mean, None)
-        t_lstd = g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
         w_mean = derive(wl.worker_mode, wl.worker_noise, l_mean, t_mean)
-        w_lstd = g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
+
+        def derive_lstd(mode, noise, target_part):
+            if mode == "independent":
+                return g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
+            base = l_lstd if mode == "learner_plus" else target_part
+            return (base + normal(base.shape, noise)).astype(f32)
+
+        t_lstd = derive_lstd(wl.target_mode, wl.target_noise, None)
+        w_lstd = derive_lstd(wl.worker_mode, wl.worker_noise, t_lstd)
         learner = np.concatenate([l_mean, l_lstd], axis=2)
         target = np.concatenate([t_mean, t_lstd], axis=2)
         worker = np.concatenate([w_mean, w_lstd], axis=2)
