@@ -312,12 +312,12 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
     a.rewards = batch.rewards; a.dones = batch.dones;
     a.slots = dev_slots; a.num_slots = num_slots;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
-    a.log_beta = std::isinf(cfg->rho_clip) ? -INFINITY : -std::log(cfg->rho_clip);
-    a.clip_lo = std::isinf(cfg->eps) ? -INFINITY : 1.f - cfg->eps;
-    a.clip_hi = std::isinf(cfg->eps) ? INFINITY : 1.f + cfg->eps;
+    a.rho_clip = cfg->rho_clip;
+    a.clip_lo = std::isinf(cfg->eps) ? -(double)INFINITY : 1.0 - (double)cfg->eps;
+    a.clip_hi = std::isinf(cfg->eps) ? (double)INFINITY : 1.0 + (double)cfg->eps;
     a.vf_coeff = cfg->vf_coeff; a.ent_coeff = cfg->ent_coeff; a.kl_coeff = cfg->kl_coeff;
     const double M = (double)T * (double)B;
-    a.inv_M = (float)(1.0 / M);
+    a.inv_M = 1.0 / M;
     a.grad_dist = out->grad_learner_dist; a.grad_values = out->grad_values;
     a.vs = out->vs; a.adv = out->adv;
     a.partials = static_cast<float *>(workspace);

@@ -36,10 +36,10 @@ struct LossArgs {
     int num_slots;
     // hyper-parameters, pre-digested on the host
     float gamma, lambda, rho_bar, c_bar;
-    float log_beta;           // -log(rho_clip); -inf when rho_clip = +inf
-    float clip_lo, clip_hi;   // 1 - eps, 1 + eps (-inf / +inf when eps = +inf)
+    float rho_clip;           // target-worker clipping rho; may be +inf
+    double clip_lo, clip_hi;  // 1 - eps, 1 + eps (-inf / +inf when eps = +inf)
     float vf_coeff, ent_coeff, kl_coeff;
-    float inv_M;              // 1 / (T * B)
+    double inv_M;             // 1 / (T * B)
     // outputs
     float *grad_dist;         // [T][B][W]
     float *grad_values;       // [T][B]

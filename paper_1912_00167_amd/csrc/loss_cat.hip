@@ -4,17 +4,22 @@
 namespace impact {
 
 // One chunk step for thread (tl, bl), in this order:
-//   worker logits  -> log pi_worker(a)
-//   target logits  -> log pi_target(a); its unnormalised softmax stays in registers for the KL term
-//   delta_t, gamma_t lambda c_t -> workgroup scan -> adv_t   (needs target and worker only)
-//   learner logits -> log pi_theta(a), entropy, KL(pi_target || pi_theta), R_t, surrogate
+//   worker logits  -> S_w = sum_k exp(z_k - max), x_w(a) = z_a - max
+//   target logits  -> S_t, x_t(a); the unnormalised softmax stays in registers for the KL term
+//   w = pi_target(a) / pi_worker(a) = exp(x_t(a) - x_w(a)) S_w / S_t
+//   delta_t, gamma_t lambda c_t -> workgroup scan -> adv_t        (needs target and worker only)
+//   learner logits -> S_l, entropy, KL(pi_target || pi_theta), R_t, surrogate
 //   gradients      -> LDS -> coalesced stores
+//
+// Precision: the importance weights and everything downstream of them up to the advantage are
+// fp64 (sums of fp64 exponentials); the learner's softmax inside the gradient is fp32, its
+// normaliser accumulated in fp64.
 template <int A, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
 {
     __shared__ __align__(16) float region_all[NWAVES][64 * A];
-    __shared__ float sd[2][TC * NB];
-    __shared__ float sg[2][TC * NB];
+    __shared__ double sd[2][TC * NB];
+    __shared__ double sg[2][TC * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
@@ -38,9 +43,9 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
     const int own_buf = (SLOT ? (bl * RW + rl) : lane) * A;
     const int own_lrn = lane * A;
-    const float ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
+    const float ce = (float)(a.ent_coeff * a.inv_M), ck = (float)(a.kl_coeff * a.inv_M);
 
-    float carry = 0.f;
+    double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     const int nchunk = (a.T + TC - 1) / TC;
 
@@ -53,10 +58,12 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
         const int tc = min(t, a.T - 1);                // clamped: loads of masked steps stay in range
         const size_t s_tm = (size_t)tc * a.B + b;
 
-        float V = 0.f, adv;
+        float V = 0.f;
         int act = 0;
-        ScanInputs sc = {0.f, 0.f, 0.f};
-        float et[A], St = 0.f, tdot = 0.f, logSt = 0.f;
+        ScanInputs sc = {0.0, 0.0};
+        float et[A], mt = 0.f, xt_a = 0.f;              // target: exp(z_k - max), max, z_a - max
+        double St = 0.0, w = 0.0;
+        float tdot = 0.f;
 
         if (rows > 0) {
             V = a.values[s_tm];
@@ -69,9 +76,9 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
             act = ((const int *)a.actions)[s_buf];
             if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
 
-            // ---- worker: log pi_worker(a) ----
+            // ---- worker ----
             stage<ST, A, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
-            float logp_w;
+            double Sw = 0.0, xw;            // sum_k exp(z_k - max), z_a - max
             {
                 float z[A];
 #pragma unroll
@@ -80,15 +87,16 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 float m = z[0];
 #pragma unroll
                 for (int k = 1; k < A; ++k) m = fmaxf(m, z[k]);
-                float S = 0.f;
 #pragma unroll
-                for (int k = 0; k < A; ++k) S += exp_fast(z[k] - m);
-                logp_w = (za - m) - logf(S);
+                for (int k = 0; k < A; ++k) {
+                    Sw += exp64((double)z[k] - (double)m);
+                    sched_fence(k);
+                }
+                xw = (double)za - (double)m;
             }
 
-            // ---- target: log pi_target(a); keep e^t_k = exp(z^t_k - max) ----
+            // ---- target; keep e^t_k = exp(z^t_k - max) in fp32 for the KL term ----
             stage<ST, A, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
-            float logp_t;
             {
                 float x[A];
 #pragma unroll
@@ -99,27 +107,32 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 for (int k = 1; k < A; ++k) m = fmaxf(m, x[k]);
 #pragma unroll
                 for (int k = 0; k < A; ++k) {
-                    x[k] -= m;
-                    et[k] = exp_fast(x[k]);
-                    St += et[k];
-                    tdot = fmaf(et[k], x[k], tdot);      // sum e^t_k x^t_k
+                    const double xd = (double)x[k] - (double)m;
+                    const double e = exp64(xd);
+                    St += e;
+                    et[k] = (float)e;
+                    tdot = fmaf(et[k], (float)xd, tdot);      // sum e^t_k x^t_k
+                    sched_fence(k);
                 }
-                logSt = logf(St);
-                logp_t = (za - m) - logSt;
+                mt = m;
+                xt_a = za;
             }
-            sc = scan_inputs(a, logp_t, logp_w, r, done, V, Vn);
+            const double xt = (double)xt_a - (double)mt;
+            w = exp64(xt - xw) * (Sw / St);
+            sc = scan_inputs(a, w, r, done, V, Vn);
         }
 
         // ---- scan: adv_t ----
-        sd[par][tl * NB + bl] = valid ? sc.delta : 0.f;
-        sg[par][tl * NB + bl] = valid ? sc.gco : 0.f;
+        sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
+        sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
         chunk_scan(sd[par], sg[par], carry, tid);
-        adv = sd[par][tl * NB + bl];
+        const double adv = sd[par][tl * NB + bl];
 
         if (rows > 0) {
             // ---- learner: log pi_theta(a), entropy, KL, gradient ----
             stage_time_major<float, A>(a.learner, a.B, t_base, rows, b0, region, lane);
-            float s, H, KL;
+            double s;
+            float H, KL;
             {
                 float x[A], p[A];
 #pragma unroll
@@ -128,40 +141,47 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 float m = x[0];
 #pragma unroll
                 for (int k = 1; k < A; ++k) m = fmaxf(m, x[k]);
-                float Sl = 0.f, dot = 0.f, cross = 0.f;
+                double Sl = 0.0, Sl_others = 0.0;       // all actions / all but the one taken
+                float dot = 0.f, cross = 0.f;
 #pragma unroll
                 for (int k = 0; k < A; ++k) {
                     x[k] -= m;
                     p[k] = exp_fast(x[k]);
-                    Sl += p[k];
+                    Sl += (double)p[k];
+                    Sl_others += (k == act) ? 0.0 : (double)p[k];
                     dot = fmaf(p[k], x[k], dot);          // sum e_k x_k
                     cross = fmaf(et[k], x[k], cross);     // sum e^t_k x_k
                 }
-                const float logSl = logf(Sl);
-                const float invSl = 1.f / Sl, invSt = 1.f / St;
-                const float logp_l = (za - m) - logSl;
+                const float Slf = (float)Sl, Stf = (float)St;
+                const float logSl = logf(Slf), logSt = logf(Stf);
+                const float invSl = 1.f / Slf, invSt = 1.f / Stf;
                 H = logSl - dot * invSl;                              // -sum p_k log p_k
                 KL = (tdot - cross) * invSt - logSt + logSl;          // sum p^t_k (log p^t_k - log p_k)
-                const float R = expf(logp_l - sc.log_den);
-                float g;
+                // R1 = pi_theta(a) / pi_target(a)
+                const double xl = (double)za - (double)m;
+                const double R1 = exp64(xl - ((double)xt_a - (double)mt)) * (St / Sl);
+                const double R = surrogate_ratio(a, R1, w);
+                double g;
                 surrogate(a, R, adv, s, g);
+                const float gf = (float)g;
+                const float one_minus_pa = (float)(Sl_others / Sl);   // 1 - p_a without cancellation
 #pragma unroll
                 for (int k = 0; k < A; ++k) {
                     const float pk = p[k] * invSl;
                     const float lp = x[k] - logSl;
                     // dL/dz_k: policy term, entropy term, KL term
                     const float base = ce * pk * (lp + H) + ck * (pk - et[k] * invSt);
-                    region[own_lrn + k] = fmaf(g, ((k == act) ? 1.f : 0.f) - pk, base);
+                    region[own_lrn + k] = fmaf(gf, (k == act) ? one_minus_pa : -pk, base);
                 }
             }
             unstage_time_major<A>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
 
             if (valid) {
-                a.grad_values[s_tm] = -a.vf_coeff * adv * a.inv_M;   // V - vs = -adv
-                if (a.vs) a.vs[s_tm] = V + adv;
-                if (a.adv) a.adv[s_tm] = adv;
-                sum_s += s;
-                sum_v = fmaf(0.5f * adv, adv, sum_v);
+                a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
+                if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
+                if (a.adv) a.adv[s_tm] = (float)adv;
+                sum_s += (float)s;
+                sum_v += (float)(0.5 * adv * adv);
                 sum_h += H;
                 sum_k += KL;
             }

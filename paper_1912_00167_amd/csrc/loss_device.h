@@ -21,8 +21,34 @@ constexpr float kHalfLog2Pi = 0.91893853320467274178f;
 
 // e^x through the hardware base-2 exponential: one multiply and one v_exp_f32.  The rounding of
 // x*log2(e) adds a relative error of about |x| * 6e-8 to the 1-ulp result; results below the
-// normal range flush to zero.  Used for the per-element exponentials (|x| of order 10 at most).
+// normal range flush to zero.  Only used where an absolute error of a few 1e-8 in a probability
+// is harmless (the learner's softmax inside the gradient).
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+
+// e^x in fp64, relative error about 1e-13: x = n ln2 + r with |r| <= ln2/2, Taylor polynomial of
+// degree 10 in r (Horner), scaled by 2^n.  fp64 multiply-adds run at the same rate as unpacked
+// fp32 ones on this chip, so this costs about as much as a correctly rounded fp32 exponential.
+// Why fp64 at all: advantages and gradients are sums of O(1)..O(10) terms that often cancel, and
+// the accuracy target (1e-6 absolute) is far below the fp32 rounding of those terms.
+__device__ __forceinline__ double exp64(double x)
+{
+    x = fmax(x, -800.0);
+    const double n = __builtin_rint(x * 1.4426950408889634074);
+    double r = __builtin_fma(-n, 6.93147180369123816490e-01, x);
+    r = __builtin_fma(-n, 1.90821492927058770002e-10, r);
+    double p = 1.0 / 3628800.0;
+    p = __builtin_fma(p, r, 1.0 / 362880.0);
+    p = __builtin_fma(p, r, 1.0 / 40320.0);
+    p = __builtin_fma(p, r, 1.0 / 5040.0);
+    p = __builtin_fma(p, r, 1.0 / 720.0);
+    p = __builtin_fma(p, r, 1.0 / 120.0);
+    p = __builtin_fma(p, r, 1.0 / 24.0);
+    p = __builtin_fma(p, r, 1.0 / 6.0);
+    p = __builtin_fma(p, r, 0.5);
+    p = __builtin_fma(p, r, 1.0);
+    p = __builtin_fma(p, r, 1.0);
+    return ldexp(p, (int)n);
+}
 
 // The per-element loops are fully unrolled so that their arrays live in registers.  Left alone,
 // the instruction scheduler interleaves all iterations and keeps every temporary alive at once;
@@ -72,6 +98,17 @@ __device__ __forceinline__ int tile_of_block(int bid, int ntiles)
     return bid;
 }
 
+// Lanes of one wavefront exchange data through LDS without a workgroup barrier: the hardware
+// executes a wavefront's LDS instructions in order.  The compiler, however, reasons about one
+// lane at a time and may keep or reorder values across such an exchange unless told that other
+// lanes write the memory: this fence pair does that (it emits no instruction of its own).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---- staging: global <-> wave-private LDS region, order preserved -------------------------
 //
 // All loads of one tensor are issued back to back without branches: rows past the end of
@@ -99,11 +136,13 @@ __device__ __forceinline__ void stage_time_major(const E *__restrict__ g, int B,
         const unsigned off = (unsigned)min(r, rows - 1) * row_stride + (unsigned)v * 16u;
         tmp[it] = *(const uint4 *)(base + off);
     }
+    wave_lds_sync();   // every lane is done reading what the region held before
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int i = lane + 64 * it;
         if (it < NIT - 1 || i < TOTAL) ((uint4 *)region)[i] = tmp[it];
     }
+    wave_lds_sync();   // the new contents are visible to every lane
 }
 
 // RW consecutive rows of NB trajectories of a slot-major plane [slot][T][Wd].
@@ -127,11 +166,13 @@ __device__ __forceinline__ void stage_slot_major(const E *__restrict__ plane, in
         const char *p = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E));
         tmp[it] = ((const uint4 *)p)[min(v, last_vec)];
     }
+    wave_lds_sync();   // every lane is done reading what the region held before
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int i = lane + 64 * it;
         if (it < NIT - 1 || i < TOTAL) ((uint4 *)region)[i] = tmp[it];
     }
+    wave_lds_sync();   // the new contents are visible to every lane
 }
 
 template <typename E, int Wd, bool SLOT>
@@ -155,6 +196,7 @@ __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B,
     char *base = (char *)g + ((size_t)t_base * B + b0) * (Wd * 4);
     const unsigned row_stride = (unsigned)B * (unsigned)(Wd * 4);
     uint4 tmp[NIT];
+    wave_lds_sync();   // every lane has written the values of its own step
 #pragma unroll
     for (int it = 0; it < NIT; ++it) tmp[it] = ((const uint4 *)region)[min(lane + 64 * it, TOTAL - 1)];
 #pragma unroll
@@ -168,47 +210,51 @@ __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B,
 // ---- per-step scalar algebra shared by all kernels -----------------------------------------
 
 struct ScanInputs {
-    float delta;     // rho_t (r_t + gamma_t V_{t+1} - V_t)
-    float gco;       // gamma_t lambda c_t
-    float log_den;   // log max(pi_target, beta pi_worker): denominator of the surrogate ratio
+    double delta;    // rho_t (r_t + gamma_t V_{t+1} - V_t)
+    double gco;      // gamma_t lambda c_t
 };
 
-// Everything the scan needs depends on the target and worker policies only, so it is
-// available before the learner's tensor has been touched.
-__device__ __forceinline__ ScanInputs scan_inputs(const LossArgs &a, float logp_t, float logp_w, float r, bool done,
-                                                  float V, float Vn)
+// Everything the scan needs depends on the target and worker policies only (w = pi_target /
+// pi_worker at the action taken), so it is available before the learner's tensor has been touched.
+__device__ __forceinline__ ScanInputs scan_inputs(const LossArgs &a, double w, float r, bool done, float V, float Vn)
 {
     ScanInputs o;
-    const float w = expf(logp_t - logp_w);            // pi_target / pi_worker
-    const float rho = fminf(a.rho_bar, w);
-    const float cc = fminf(a.c_bar, w);
-    const float gam = done ? 0.f : a.gamma;
-    o.delta = rho * (r + gam * Vn - V);
-    o.gco = gam * a.lambda * cc;
-    o.log_den = fmaxf(logp_t, logp_w + a.log_beta);
+    const double rho = fmin((double)a.rho_bar, w);
+    const double cc = fmin((double)a.c_bar, w);
+    const double gam = done ? 0.0 : (double)a.gamma;
+    o.delta = rho * ((double)r + gam * (double)Vn - (double)V);
+    o.gco = gam * (double)a.lambda * cc;
     return o;
 }
 
-// Surrogate value and the weight g = dL/dlogp_theta(a) of the policy term.
-__device__ __forceinline__ void surrogate(const LossArgs &a, float R, float adv, float &s, float &g)
+// Surrogate ratio R = pi_theta / max(pi_target, pi_worker / rho_clip) from R1 = pi_theta / pi_target
+// and w = pi_target / pi_worker: the maximum picks pi_target when w >= 1 / rho_clip, and otherwise
+// R = R1 * w * rho_clip (the first form of J_AIS).  rho_clip = +inf never takes the second branch.
+__device__ __forceinline__ double surrogate_ratio(const LossArgs &a, double R1, double w)
 {
-    const float Rc = fminf(fmaxf(R, a.clip_lo), a.clip_hi);
-    s = fminf(R * adv, Rc * adv);
-    const bool clipped = (adv > 0.f && R > a.clip_hi) || (adv < 0.f && R < a.clip_lo);
-    g = clipped ? 0.f : -adv * R * a.inv_M;
+    return (w * (double)a.rho_clip >= 1.0) ? R1 : R1 * w * (double)a.rho_clip;
+}
+
+// Surrogate value s = min(R adv, clip(R) adv) and the weight g = dL/dlogp_theta(a) of the policy term.
+__device__ __forceinline__ void surrogate(const LossArgs &a, double R, double adv, double &s, double &g)
+{
+    const double Rc = fmin(fmax(R, a.clip_lo), a.clip_hi);
+    s = fmin(R * adv, Rc * adv);
+    const bool clipped = (adv > 0.0 && R > a.clip_hi) || (adv < 0.0 && R < a.clip_lo);
+    g = clipped ? 0.0 : -adv * R * a.inv_M;
 }
 
 // Backward scan of one chunk.  sd/sg hold delta and gamma*lambda*c for TC x NB steps
 // (zero for steps past T); threads tid < NB each run one trajectory and leave the
 // accumulated advantage in sd.  Two workgroup barriers.
-__device__ __forceinline__ void chunk_scan(float *sd, const float *sg, float &carry, int tid)
+__device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid)
 {
     __syncthreads();
     if (tid < NB) {
-        float acc = carry;
+        double acc = carry;
 #pragma unroll 8
         for (int j = TC - 1; j >= 0; --j) {
-            acc = fmaf(sg[j * NB + tid], acc, sd[j * NB + tid]);
+            acc = fma(sg[j * NB + tid], acc, sd[j * NB + tid]);
             sd[j * NB + tid] = acc;
         }
         carry = acc;

@@ -5,13 +5,18 @@ namespace impact {
 
 // Distribution tensors are [..][2D]: D means, then D log standard deviations.
 // Order per chunk: actions, worker, target (kept in registers), scan, learner.
+//
+// Precision: fp64 throughout.  log pi(a) is a sum of D terms -((a - mu)/sigma)^2 / 2 - log sigma
+// of size O(1)..O(10); the ratios pi_target/pi_worker and pi_theta/pi_target, the advantages
+// and the gradients (policy term against KL term) are differences of such sums, and the accuracy
+// target is far below fp32 rounding of the terms.  fp64 multiply-adds run at the unpacked-fp32 rate.
 template <int D, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
 {
     constexpr int W = 2 * D;
     __shared__ __align__(16) float region_all[NWAVES][64 * W];
-    __shared__ float sd[2][TC * NB];
-    __shared__ float sg[2][TC * NB];
+    __shared__ double sd[2][TC * NB];
+    __shared__ double sg[2][TC * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
@@ -35,9 +40,9 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
     const int own_step = SLOT ? (bl * RW + rl) : lane;   // position of my step in a staged buffer-side tensor
     const int own_lrn = lane * W;
-    const float ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
+    const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
-    float carry = 0.f;
+    double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     const int nchunk = (a.T + TC - 1) / TC;
 
@@ -50,10 +55,11 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
         const int tc = min(t, a.T - 1);                // clamped: loads of masked steps stay in range
         const size_t s_tm = (size_t)tc * a.B + b;
 
-        float V = 0.f, adv;
-        ScanInputs sc = {0.f, 0.f, 0.f};
+        float V = 0.f;
+        ScanInputs sc = {0.0, 0.0};
         float act[D];
         Held<ST, W> tg;
+        double lt = 0.0, w = 0.0;                      // log pi_target(a) + const, pi_target / pi_worker
 
         if (rows > 0) {
             V = a.values[s_tm];
@@ -69,88 +75,84 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
 #pragma unroll
             for (int d = 0; d < D; ++d) act[d] = widen(region_st[own_step * D + d]);
 
-            // ---- worker: log pi_worker(a) ----
+            // ---- worker: log pi_worker(a) (the common -D/2 log 2pi is dropped: only differences are used) ----
             stage<ST, W, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
-            float logp_w = 0.f;
+            double lw = 0.0;
             {
                 Held<ST, W> wk;
                 wk.load(region_st + own_step * W);
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
-                    const float ls = wk.get(D + d);
-                    const float z = (act[d] - wk.get(d)) * exp_fast(-ls);
-                    logp_w += fmaf(-0.5f * z, z, -ls);
+                    const double ls = (double)wk.get(D + d);
+                    const double diff = (double)act[d] - (double)wk.get(d);
+                    lw += __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
                     sched_fence(d);
                 }
-                logp_w -= D * kHalfLog2Pi;
             }
 
             // ---- target: log pi_target(a); mean and log-std stay in registers for the KL term ----
             stage<ST, W, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
             tg.load(region_st + own_step * W);
-            float logp_t = 0.f;
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const float ls = tg.get(D + d);
-                const float z = (act[d] - tg.get(d)) * exp_fast(-ls);
-                logp_t += fmaf(-0.5f * z, z, -ls);
+                const double ls = (double)tg.get(D + d);
+                const double diff = (double)act[d] - (double)tg.get(d);
+                lt += __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
                 sched_fence(d);
             }
-            logp_t -= D * kHalfLog2Pi;
-            sc = scan_inputs(a, logp_t, logp_w, r, done, V, Vn);
+            w = exp64(lt - lw);
+            sc = scan_inputs(a, w, r, done, V, Vn);
         }
 
         // ---- scan: adv_t ----
-        sd[par][tl * NB + bl] = valid ? sc.delta : 0.f;
-        sg[par][tl * NB + bl] = valid ? sc.gco : 0.f;
+        sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
+        sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
         chunk_scan(sd[par], sg[par], carry, tid);
-        adv = sd[par][tl * NB + bl];
+        const double adv = sd[par][tl * NB + bl];
 
         if (rows > 0) {
             // ---- learner: log pi_theta(a) and entropy first, then KL and gradients ----
             stage_time_major<float, W>(a.learner, a.B, t_base, rows, b0, region, lane);
-            float inv[D];
-            float logp_l = 0.f, H = 0.f, KL = 0.f;
+            double E[D];                                   // 1 / sigma_theta^2
+            double ll = 0.0, H = 0.0, KL = 0.0;
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const float ls = region[own_lrn + D + d];
-                inv[d] = exp_fast(-ls);                    // 1 / sigma_theta
-                const float z = (act[d] - region[own_lrn + d]) * inv[d];
-                logp_l += fmaf(-0.5f * z, z, -ls);
+                const double ls = (double)region[own_lrn + D + d];
+                const double diff = (double)act[d] - (double)region[own_lrn + d];
+                E[d] = exp64(-2.0 * ls);
+                ll += __builtin_fma(-0.5 * diff * diff, E[d], -ls);
                 H += ls;
                 sched_fence(d);
             }
-            logp_l -= D * kHalfLog2Pi;
-            H += D * (kHalfLog2Pi + 0.5f);
-            const float R = expf(logp_l - sc.log_den);
-            float s, g;
+            H += D * ((double)kHalfLog2Pi + 0.5);
+            const double R = surrogate_ratio(a, exp64(ll - lt), w);
+            double s, g;
             surrogate(a, R, adv, s, g);
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const float mu = region[own_lrn + d];
-                const float ls = region[own_lrn + D + d];
-                const float inv2 = inv[d] * inv[d];
-                const float diff = act[d] - mu;
-                const float z = diff * inv[d];
-                const float lst = tg.get(D + d);
-                const float dm = mu - tg.get(d);
-                const float q = fmaf(dm, dm, exp_fast(2.f * lst)) * inv2;   // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
-                KL += (ls - lst) + (0.5f * q - 0.5f);
+                const double mu = (double)region[own_lrn + d];
+                const double ls = (double)region[own_lrn + D + d];
+                const double diff = (double)act[d] - mu;
+                const double zz = diff * diff * E[d];                         // ((a - mu) / sigma)^2
+                const double lst = (double)tg.get(D + d);
+                const double dm = mu - (double)tg.get(d);
+                const double q = __builtin_fma(dm, dm, exp64(2.0 * lst)) * E[d];   // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
+                KL += (ls - lst) + (0.5 * q - 0.5);
                 // dL/dmu = g dlogp/dmu + kl/M dKL/dmu;  dL/dls = g dlogp/dls - ent/M + kl/M dKL/dls
-                region[own_lrn + d] = fmaf(g, diff * inv2, ck * dm * inv2);
-                region[own_lrn + D + d] = fmaf(g, fmaf(z, z, -1.f), fmaf(ck, 1.f - q, -ce));
+                region[own_lrn + d] = (float)((g * diff + ck * dm) * E[d]);
+                region[own_lrn + D + d] = (float)(__builtin_fma(g, zz - 1.0, __builtin_fma(ck, 1.0 - q, -ce)));
                 sched_fence(d);
             }
             unstage_time_major<W>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
 
             if (valid) {
-                a.grad_values[s_tm] = -a.vf_coeff * adv * a.inv_M;   // V - vs = -adv
-                if (a.vs) a.vs[s_tm] = V + adv;
-                if (a.adv) a.adv[s_tm] = adv;
-                sum_s += s;
-                sum_v = fmaf(0.5f * adv, adv, sum_v);
-                sum_h += H;
-                sum_k += KL;
+                a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
+                if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
+                if (a.adv) a.adv[s_tm] = (float)adv;
+                sum_s += (float)s;
+                sum_v += (float)(0.5 * adv * adv);
+                sum_h += (float)H;
+                sum_k += (float)KL;
             }
         }
     }

@@ -6,32 +6,35 @@
 
 namespace impact {
 
+// All arithmetic here is fp64 with the library's exp/log: simple, and accurate beyond need.
+
 template <typename ST>
-__device__ __forceinline__ void softmax_stats(const ST *z, int A, float &m, float &S)
+__device__ __forceinline__ void softmax_stats(const ST *z, int A, float &m, double &S)
 {
     m = widen(z[0]);
     for (int k = 1; k < A; ++k) m = fmaxf(m, widen(z[k]));
-    S = 0.f;
-    for (int k = 0; k < A; ++k) S += expf(widen(z[k]) - m);
+    S = 0.0;
+    for (int k = 0; k < A; ++k) S += exp((double)widen(z[k]) - (double)m);
 }
 
-template <typename ST>
-__device__ __forceinline__ float gauss_logp(const ST *p, const ST *act, int D)
+// log pi(a) without the common -D/2 log 2pi
+template <typename ST, typename AT>
+__device__ __forceinline__ double gauss_logp(const ST *p, const AT *act, int D)
 {
-    float lp = 0.f;
+    double lp = 0.0;
     for (int d = 0; d < D; ++d) {
-        const float ls = widen(p[D + d]);
-        const float z = (widen(act[d]) - widen(p[d])) * expf(-ls);
-        lp += fmaf(-0.5f * z, z, -ls);
+        const double ls = (double)widen(p[D + d]);
+        const double diff = (double)widen(act[d]) - (double)widen(p[d]);
+        lp += -0.5 * diff * diff * exp(-2.0 * ls) - ls;
     }
-    return lp - D * kHalfLog2Pi;
+    return lp;
 }
 
 template <int DIST, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
 {
-    __shared__ float sd[2][TC * NB];
-    __shared__ float sg[2][TC * NB];
+    __shared__ double sd[2][TC * NB];
+    __shared__ double sg[2][TC * NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
     const int A = a.A;
@@ -48,9 +51,9 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         slot = a.slots[b];
         if (slot < 0 || slot >= a.num_slots) { if (rl == 0 && wave == 0) bad = 1.f; slot = min(max(slot, 0), a.num_slots - 1); }
     }
-    const float ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
+    const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
-    float carry = 0.f;
+    double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     const int nchunk = (a.T + TC - 1) / TC;
 
@@ -61,12 +64,13 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         const size_t s_tm = (size_t)t * a.B + b;
         const size_t s_buf = SLOT ? ((size_t)slot * a.T + t) : s_tm;
 
-        float V = 0.f, H = 0.f, KL = 0.f;
-        ScanInputs sc = {0.f, 0.f, 0.f};
-        float R = 0.f;
+        float V = 0.f;
+        double H = 0.0, KL = 0.0, R = 0.0;
+        ScanInputs sc = {0.0, 0.0};
         int act = 0;
         // quantities the gradient pass needs again
-        float m_l = 0.f, logS_l = 0.f, m_t = 0.f, logS_t = 0.f;
+        float m_l = 0.f, m_t = 0.f;
+        double S_l = 1.0, S_t = 1.0;
         const float *zl = a.learner + s_tm * W;
         const ST *zt = (const ST *)a.target + s_buf * W;
         const ST *zw = (const ST *)a.worker + s_buf * W;
@@ -77,84 +81,81 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             const float Vn = (t + 1 < a.T) ? a.values[s_tm + a.B] : a.bootstrap[b];
             const float r = widen(((const ST *)a.rewards)[s_buf]);
             const bool done = a.dones[s_buf] != 0;
-            float logp_l, logp_t, logp_w;
+            double w, R1;
             if (DIST == IMPACT_CATEGORICAL) {
                 act = ((const int *)a.actions)[s_buf];
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
-                float m, S, S_l, S_t;
-                softmax_stats(zw, A, m, S);
-                logp_w = (widen(zw[act]) - m) - logf(S);
+                float m_w;
+                double S_w;
+                softmax_stats(zw, A, m_w, S_w);
                 softmax_stats(zt, A, m_t, S_t);
-                logS_t = logf(S_t);
-                logp_t = (widen(zt[act]) - m_t) - logS_t;
                 softmax_stats(zl, A, m_l, S_l);
-                logS_l = logf(S_l);
-                logp_l = (zl[act] - m_l) - logS_l;
-                float dot = 0.f, cross = 0.f;
+                const double xw = (double)widen(zw[act]) - (double)m_w;
+                const double xt = (double)widen(zt[act]) - (double)m_t;
+                const double xl = (double)zl[act] - (double)m_l;
+                w = exp(xt - xw) * (S_w / S_t);
+                R1 = exp(xl - xt) * (S_t / S_l);
+                const double logS_l = log(S_l), logS_t = log(S_t);
                 for (int k = 0; k < A; ++k) {
-                    const float xl = zl[k] - m_l, xt = widen(zt[k]) - m_t;
-                    dot = fmaf(expf(xl), xl, dot);
-                    cross = fmaf(expf(xt), xt - xl, cross);
+                    const double lpl = ((double)zl[k] - (double)m_l) - logS_l;
+                    const double lpt = ((double)widen(zt[k]) - (double)m_t) - logS_t;
+                    H -= exp(lpl) * lpl;
+                    KL += exp(lpt) * (lpt - lpl);
                 }
-                H = logS_l - dot / S_l;
-                KL = cross / S_t - logS_t + logS_l;
             } else {
-                logp_w = gauss_logp(zw, av, A);
-                logp_t = gauss_logp(zt, av, A);
-                logp_l = 0.f;
+                const double lw = gauss_logp(zw, av, A), lt = gauss_logp(zt, av, A), ll = gauss_logp(zl, av, A);
+                w = exp(lt - lw);
+                R1 = exp(ll - lt);
                 for (int d = 0; d < A; ++d) {
-                    const float mu = zl[d], ls = zl[A + d];
-                    const float inv = expf(-ls);
-                    const float z = (widen(av[d]) - mu) * inv;
-                    logp_l += fmaf(-0.5f * z, z, -ls);
+                    const double ls = (double)zl[A + d], lst = (double)widen(zt[A + d]);
+                    const double dm = (double)zl[d] - (double)widen(zt[d]);
                     H += ls;
-                    const float lst = widen(zt[A + d]);
-                    const float dm = mu - widen(zt[d]);
-                    const float q = fmaf(dm, dm, expf(2.f * lst)) * (inv * inv);
-                    KL += (ls - lst) + (0.5f * q - 0.5f);
+                    KL += (ls - lst) + 0.5 * (exp(2.0 * lst) + dm * dm) * exp(-2.0 * ls) - 0.5;
                 }
-                logp_l -= A * kHalfLog2Pi;
-                H += A * (kHalfLog2Pi + 0.5f);
+                H += A * ((double)kHalfLog2Pi + 0.5);
             }
-            sc = scan_inputs(a, logp_t, logp_w, r, done, V, Vn);
-            R = expf(logp_l - sc.log_den);
+            sc = scan_inputs(a, w, r, done, V, Vn);
+            R = surrogate_ratio(a, R1, w);
         }
-        sd[par][tl * NB + bl] = valid ? sc.delta : 0.f;
-        sg[par][tl * NB + bl] = valid ? sc.gco : 0.f;
+        sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
+        sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
         chunk_scan(sd[par], sg[par], carry, tid);
-        const float adv = sd[par][tl * NB + bl];
+        const double adv = sd[par][tl * NB + bl];
 
         if (valid) {
-            float s, g;
+            double s, g;
             surrogate(a, R, adv, s, g);
             float *gd = a.grad_dist + s_tm * W;
             if (DIST == IMPACT_CATEGORICAL) {
+                const double logS_l = log(S_l), logS_t = log(S_t);
+                double others = 0.0;                     // 1 - p_a as a sum, free of cancellation
+                for (int k = 0; k < A; ++k)
+                    if (k != act) others += exp(((double)zl[k] - (double)m_l) - logS_l);
                 for (int k = 0; k < A; ++k) {
-                    const float lp = (zl[k] - m_l) - logS_l;
-                    const float p = expf(lp);
-                    const float pt = expf((widen(zt[k]) - m_t) - logS_t);
-                    const float base = ce * p * (lp + H) + ck * (p - pt);
-                    gd[k] = fmaf(g, ((k == act) ? 1.f : 0.f) - p, base);
+                    const double lp = ((double)zl[k] - (double)m_l) - logS_l;
+                    const double p = exp(lp);
+                    const double pt = exp(((double)widen(zt[k]) - (double)m_t) - logS_t);
+                    const double base = ce * p * (lp + H) + ck * (p - pt);
+                    gd[k] = (float)(g * ((k == act) ? others : -p) + base);
                 }
             } else {
                 for (int d = 0; d < A; ++d) {
-                    const float mu = zl[d], ls = zl[A + d];
-                    const float inv = expf(-ls), inv2 = inv * inv;
-                    const float diff = widen(av[d]) - mu;
-                    const float z = diff * inv;
-                    const float dm = mu - widen(zt[d]);
-                    const float q = fmaf(dm, dm, expf(2.f * widen(zt[A + d]))) * inv2;
-                    gd[d] = fmaf(g, diff * inv2, ck * dm * inv2);
-                    gd[A + d] = fmaf(g, fmaf(z, z, -1.f), fmaf(ck, 1.f - q, -ce));
+                    const double mu = (double)zl[d], ls = (double)zl[A + d];
+                    const double E = exp(-2.0 * ls);
+                    const double diff = (double)widen(av[d]) - mu;
+                    const double dm = mu - (double)widen(zt[d]);
+                    const double q = (exp(2.0 * (double)widen(zt[A + d])) + dm * dm) * E;
+                    gd[d] = (float)((g * diff + ck * dm) * E);
+                    gd[A + d] = (float)(g * (diff * diff * E - 1.0) + ck * (1.0 - q) - ce);
                 }
             }
-            a.grad_values[s_tm] = -a.vf_coeff * adv * a.inv_M;   // V - vs = -adv
-            if (a.vs) a.vs[s_tm] = V + adv;
-            if (a.adv) a.adv[s_tm] = adv;
-            sum_s += s;
-            sum_v = fmaf(0.5f * adv, adv, sum_v);
-            sum_h += H;
-            sum_k += KL;
+            a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
+            if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
+            if (a.adv) a.adv[s_tm] = (float)adv;
+            sum_s += (float)s;
+            sum_v += (float)(0.5 * adv * adv);
+            sum_h += (float)H;
+            sum_k += (float)KL;
         }
     }
     store_partials(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);

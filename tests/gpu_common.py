@@ -41,8 +41,16 @@ def oracle_inputs(x, storage: str):
     return y
 
 
+def as_passed_to_c(h):
+    """The hyper-parameters as the C ABI receives them: fp32 values.  The oracle is given exactly
+    these (widened), so that both sides start from the same numbers."""
+    f = lambda v: float(np.float32(v))
+    return replace(h, gamma=f(h.gamma), lam=f(h.lam), rho_bar=f(h.rho_bar), c_bar=f(h.c_bar), rho_clip=f(h.rho_clip),
+                   eps=f(h.eps), vf_coeff=f(h.vf_coeff), ent_coeff=f(h.ent_coeff), kl_coeff=f(h.kl_coeff))
+
+
 def run_oracle(wl, x, hyper=None, n_threads=8):
-    h = wl.hyper if hyper is None else hyper
+    h = as_passed_to_c(wl.hyper if hyper is None else hyper)
     cfg = oracle.config_from_hyper(h)
     xi = oracle_inputs(x, wl.storage)
     return oracle.impact_loss(wl.dist, xi["learner"], xi["target"], xi["worker"], xi["actions"], xi["rewards"],
@@ -58,7 +66,7 @@ def max_violation(got, want, scale=1.0):
 
 def check_against_oracle(wl, x, got, hyper=None, label=""):
     """got: dict of numpy arrays from the GPU (grad_dist, grad_values, vs, adv, loss5)."""
-    h = wl.hyper if hyper is None else hyper
+    h = as_passed_to_c(wl.hyper if hyper is None else hyper)
     want, xi, cfg = run_oracle(wl, x, h)
     M = wl.T * x["learner"].shape[1]
     report = {}
