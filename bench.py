@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the IMPACT learner hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: the circular buffer's host-side sampling
+(slots and replay counts), the copy of the slot indices to the device, and the fused
+gather + loss + gradient kernel reading the sampled trajectories in place from the HBM-resident
+ring.  The ring, the learner's distribution tensors, values and outputs are resident in HBM
+before the timed region starts.
+
+Prints one JSON line: trajectory-steps per second, the HBM roofline of the dominant kernel and
+the CPU oracle's rate on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
+
+
+def algorithmic_bytes_per_step(wl) -> int:
+    """Each input read once, each output written once (single pass), per (t, b) step."""
+    es = 4 if wl.storage == "f32" else 2
+    if wl.dist == workloads.CATEGORICAL:
+        A = wl.A
+        reads = 4 * A + 2 * A * es + 4 + es + 1 + 4      # learner, target+worker, action, reward, done, value
+        writes = 4 * A + 12                              # grad logits, grad value, vs, adv
+    else:
+        D = wl.A
+        reads = 8 * D + 4 * D * es + D * es + es + 1 + 4  # learner, target+worker, actions, reward, done, value
+        writes = 8 * D + 12
+    return reads + writes
+
+
+def fill_ring(torch, binding, wl, buf, block: int):
+    """Insert num_slots synthetic trajectories block by block; return the learner-side tensors
+    (learner dist, values, bootstrap) per batch-sized group of consecutive slots."""
+    n_blocks = wl.num_slots // block
+    per_batch = wl.B // block
+    learner, values, boot = [], [], []
+    cur = dict(learner=[], values=[], bootstrap=[])
+    for i in range(n_blocks):
+        x = workloads.make_trajectories(wl, block, stream=1000 + i)
+        d = {k: torch.from_numpy(v).cuda() for k, v in x.items()}
+        slots = binding.impact_buffer_insert(buf, d)
+        assert slots[0] == i * block and slots[-1] == (i + 1) * block - 1
+        for k in cur:
+            cur[k].append(d[k])
+        if (i + 1) % per_batch == 0:
+            learner.append(torch.cat(cur["learner"], dim=1).contiguous())
+            values.append(torch.cat(cur["values"], dim=1).contiguous())
+            boot.append(torch.cat(cur["bootstrap"], dim=0).contiguous())
+            cur = dict(learner=[], values=[], bootstrap=[])
+        del d
+    torch.cuda.synchronize()
+    return learner, values, boot
+
+
+def cpu_baseline(wl, sample_B: int):
+    """Time the oracle (as it is) on a bounded sample of the workload, all host threads."""
+    import oracle
+    from oracle.buffer import BufferOracle, bf16_bits_to_f32
+
+    threads = min(oracle.max_threads(), os.cpu_count() or 1)
+    x = workloads.make_trajectories(wl, sample_B, stream=77)
+    ob = BufferOracle(wl.dist, wl.T, wl.A, sample_B, wl.K, wl.storage)
+    ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"], target=x["target"])
+    cfg = oracle.config_from_hyper(wl.hyper)
+    t0 = time.perf_counter()
+    slots, _ = ob.sample(sample_B)
+    g = ob.gather(slots)
+    if wl.storage == "bf16":
+        g = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in g.items()}
+    oracle.impact_loss(wl.dist, x["learner"], g["target"], g["worker"], g["actions"], g["rewards"], g["dones"],
+                       x["values"], x["bootstrap"], cfg, n_threads=threads)
+    dt = time.perf_counter() - t0
+    return dict(value=wl.T * sample_B / dt, unit="trajectory-steps/s", cores=threads, kind="oracle",
+                sample=f"{sample_B} of {wl.B} trajectories of {wl.name} (T={wl.T}), sample+gather+loss, "
+                       f"{dt:.2f} s wall")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1912_00167_amd import binding
+
+    binding.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = workloads.WORKLOADS[args.workload]
+    T, B, W = wl.T, wl.B, wl.W
+
+    buf = binding.Buffer(wl.dist, T, wl.A, wl.num_slots, wl.K, wl.storage)
+    block = min(B, 4096)
+    learner, values, boot = fill_ring(torch, binding, wl, buf, block)
+    n_batches = len(learner)                       # distinct batches per pass over the ring
+    outs = [binding.alloc_loss_out(T, B, W) for _ in range(2)]
+    workspace = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, T, B, wl.A), dtype=torch.uint8, device="cuda")
+    cfg = binding.config_from_hyper(wl.hyper)
+    stream = torch.cuda.current_stream()
+
+    depth = 4                                      # pinned staging buffers for the slot indices
+    pinned = [torch.empty(B, dtype=torch.int32).pin_memory() for _ in range(depth)]
+    pinned_np = [p.numpy() for p in pinned]
+    counts_np = np.empty(B, dtype=np.int32)
+    dev_slots = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(depth)]
+    copied = [None] * depth
+    state = dict(step=0)
+
+    def one_step(ev_pair=None):
+        i = state["step"]
+        j = i % depth
+        if copied[j] is not None:
+            copied[j].synchronize()                # the staging buffer is free again
+        if binding.impact_buffer_num_live(buf) < B:
+            binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))   # workers' refill: bookkeeping only, the data is in place
+        binding.impact_buffer_sample(buf, B, pinned_np[j], counts_np)
+        q = int(pinned_np[j][0]) // B              # ring order: batch q holds slots [qB, (q+1)B)
+        dev_slots[j].copy_(pinned[j], non_blocking=True)
+        ev = torch.cuda.Event()
+        ev.record(stream)
+        copied[j] = ev
+        if ev_pair is not None:
+            ev_pair[0].record(stream)
+        binding.impact_loss_fwd_bwd_from_buffer(buf, dev_slots[j], learner[q % n_batches], values[q % n_batches],
+                                                boot[q % n_batches], cfg, out=outs[i % 2], workspace=workspace,
+                                                stream=stream)
+        if ev_pair is not None:
+            ev_pair[1].record(stream)
+        state["step"] = i + 1
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(pairs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    loss = outs[(state["step"] - 1) % 2]["loss5"].cpu().numpy()
+    assert np.all(np.isfinite(loss)), f"non-finite loss {loss}"
+    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    steps_per_call = T * B
+    ms_per_step = wall * 1e3 / args.steps
+    bytes_per_call = algorithmic_bytes_per_step(wl) * steps_per_call
+    achieved = bytes_per_call / (kernel_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "trajectory-steps/sec for IMPACT loss fwd+bwd (+gather); % of HBM peak",
+        "value": steps_per_call / (ms_per_step * 1e-3),
+        "unit": "trajectory-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if wl.dist == workloads.GAUSSIAN else "f32+f64",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={T} B={B} A={wl.A} {wl.dist}, {wl.storage} buffer fields, "
+                               f"ring {wl.num_slots} slots K={wl.K}, fused gather+loss+grad",
+                   "algorithmic_bytes_per_step": algorithmic_bytes_per_step(wl),
+                   "loss5": [float(v) for v in loss]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms": kernel_ms, "kernel": "fused loss kernel + its one-workgroup reduction"},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, max(8, B // 16))
+    print(json.dumps(result))
+    buf.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

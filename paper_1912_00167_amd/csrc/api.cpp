@@ -327,7 +327,7 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
     const int es = dtype == IMPACT_F32 ? 4 : 2;
     bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
-    if ((double)B * W * 4.0 * RW >= 2147483648.0) fast = false;
+    if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
     if (slot_major && (double)num_slots * T >= 2147483648.0) fast = false;
     if (fast && slot_major) {
         // every slot's trajectory must start on a 16-byte boundary in each staged plane

@@ -9,16 +9,15 @@
 
 namespace impact {
 
-// Tiling of the loss kernels: a workgroup of 256 threads owns NB consecutive
-// trajectories and sweeps time backwards in chunks of TC steps; thread
-// (tl, bl) handles step (t0 + tl, b0 + bl).  A wavefront covers RW = 64 / NB
-// consecutive time rows of the tile.
+// Tiling of the loss kernels: a workgroup of 256 threads owns NB consecutive trajectories
+// and sweeps time backwards in chunks.  P lanes share one (t, b) step (each takes 1/P of the
+// actions / action dimensions), so a wavefront covers 64 / (NB * P) consecutive time rows of
+// the tile and a chunk is NWAVES times that.  The scan buffers are sized for P = 1.
 constexpr int NB = 8;
-constexpr int TC = 32;
-constexpr int NTHREADS = NB * TC;
+constexpr int NTHREADS = 256;
 constexpr int NWAVES = NTHREADS / 64;
-constexpr int RW = 64 / NB;
-constexpr int PARTIAL_STRIDE = 8;   // floats per workgroup in the partial-sum workspace
+constexpr int TC_MAX = NTHREADS / NB;       // time steps per chunk when P = 1
+constexpr int PARTIAL_STRIDE = 8;           // floats per workgroup in the partial-sum workspace
 
 struct LossArgs {
     int T, B, A;

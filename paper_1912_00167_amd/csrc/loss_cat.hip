@@ -18,13 +18,14 @@ template <int A, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
 {
     __shared__ __align__(16) float region_all[NWAVES][64 * A];
-    __shared__ double sd[2][TC * NB];
-    __shared__ double sg[2][TC * NB];
+    __shared__ double sd[2][TC_MAX * NB];
+    __shared__ double sg[2][TC_MAX * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    constexpr int RW = 64 / NB, TC = TC_MAX;
     const int rl = lane / NB, bl = lane % NB, tl = wave * RW + rl;
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
     const int b0 = tile * NB, b = b0 + bl;
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
             if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
 
             // ---- worker ----
-            stage<ST, A, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
+            stage<ST, A, RW, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
             double Sw = 0.0, xw;            // sum_k exp(z_k - max), z_a - max
             {
                 float z[A];
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
             }
 
             // ---- target; keep e^t_k = exp(z^t_k - max) in fp32 for the KL term ----
-            stage<ST, A, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
+            stage<ST, A, RW, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
             {
                 float x[A];
 #pragma unroll
@@ -125,12 +126,12 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
         // ---- scan: adv_t ----
         sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
         sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
-        chunk_scan(sd[par], sg[par], carry, tid);
+        chunk_scan<TC>(sd[par], sg[par], carry, tid);
         const double adv = sd[par][tl * NB + bl];
 
         if (rows > 0) {
             // ---- learner: log pi_theta(a), entropy, KL, gradient ----
-            stage_time_major<float, A>(a.learner, a.B, t_base, rows, b0, region, lane);
+            stage_time_major<float, A, RW>(a.learner, a.B, t_base, rows, b0, region, lane);
             double s;
             float H, KL;
             {
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                     region[own_lrn + k] = fmaf(gf, (k == act) ? one_minus_pa : -pk, base);
                 }
             }
-            unstage_time_major<A>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
+            unstage_time_major<A, RW>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
 
             if (valid) {
                 a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv

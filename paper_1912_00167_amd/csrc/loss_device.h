@@ -1,11 +1,10 @@
 // Device-side building blocks of the loss kernels (gfx950, wave64).
 //
-// Data flow of the specialised kernels: a workgroup owns NB consecutive
-// trajectories and walks time backwards in chunks of TC steps.  Each wavefront
-// brings its RW time rows of a tensor into a private LDS region with 16-byte
-// coalesced loads, after which every thread reads the W values of its own
-// (t, b) step from LDS.  Gradients take the reverse route.  Only the scalar
-// scan state crosses workgroup barriers.
+// Data flow of the specialised kernels: a workgroup owns NB consecutive trajectories and walks
+// time backwards in chunks.  Each wavefront brings its time rows of a tensor into a private LDS
+// region with coalesced vector loads, after which the P lanes that share a (t, b) step read
+// that step's values from LDS.  Gradients take the reverse route.  Only the scalar scan state
+// crosses workgroup barriers.
 #pragma once
 
 #include "impact_internal.h"
@@ -60,35 +59,6 @@ __device__ __forceinline__ void sched_fence(int k)
     if ((k % kSchedEvery) == kSchedEvery - 1) __builtin_amdgcn_sched_barrier(0);
 }
 
-// N values of one step kept in registers between two passes.  bfloat16 values stay packed
-// two per register and are widened on use.
-template <typename ST, int N>
-struct Held;
-template <int N>
-struct Held<float, N> {
-    float v[N];
-    __device__ __forceinline__ void load(const float *lds)
-    {
-#pragma unroll
-        for (int i = 0; i < N; ++i) v[i] = lds[i];
-    }
-    __device__ __forceinline__ float get(int i) const { return v[i]; }
-};
-template <int N>
-struct Held<bf16_t, N> {
-    static_assert(N % 2 == 0, "packed pairs");
-    uint32_t w[N / 2];
-    __device__ __forceinline__ void load(const bf16_t *lds)   // lds must be 4-byte aligned
-    {
-#pragma unroll
-        for (int i = 0; i < N / 2; ++i) w[i] = ((const uint32_t *)lds)[i];
-    }
-    __device__ __forceinline__ float get(int i) const
-    {
-        return __uint_as_float((i & 1) ? (w[i >> 1] & 0xffff0000u) : (w[i >> 1] << 16));
-    }
-};
-
 // Workgroup -> tile map.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs;
 // give each XCD a contiguous range of tiles so that neighbouring tiles, which share
 // 128-byte lines of the [T][B] tensors, meet in the same L2.
@@ -96,6 +66,33 @@ __device__ __forceinline__ int tile_of_block(int bid, int ntiles)
 {
     if ((ntiles & 7) == 0) return (bid & 7) * (ntiles >> 3) + (bid >> 3);
     return bid;
+}
+
+// ---- exchange between the P lanes of a step (adjacent lanes): DPP quad permutes ------------
+
+__device__ __forceinline__ int partner_lane_value(int x)   // the value lane ^ 1 holds
+{
+    return __builtin_amdgcn_update_dpp(0, x, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, false);
+}
+template <int P>
+__device__ __forceinline__ float pair_max(float x)
+{
+    if (P == 1) return x;
+    return fmaxf(x, __int_as_float(partner_lane_value(__float_as_int(x))));
+}
+template <int P>
+__device__ __forceinline__ float pair_sum(float x)
+{
+    if (P == 1) return x;
+    return x + __int_as_float(partner_lane_value(__float_as_int(x)));
+}
+template <int P>
+__device__ __forceinline__ double pair_sum(double x)
+{
+    if (P == 1) return x;
+    const double y = __hiloint2double(partner_lane_value(__double2hiint(x)), partner_lane_value(__double2loint(x)));
+    // add in a fixed order so that both lanes of the pair hold bit-identical sums
+    return (threadIdx.x & 1) ? y + x : x + y;
 }
 
 // Lanes of one wavefront exchange data through LDS without a workgroup barrier: the hardware
@@ -111,99 +108,99 @@ __device__ __forceinline__ void wave_lds_sync()
 
 // ---- staging: global <-> wave-private LDS region, order preserved -------------------------
 //
-// All loads of one tensor are issued back to back without branches: rows past the end of
-// the trajectory are redirected to the last valid row (a redundant but legal read) and simply
-// never used.  t_base, b0 and rows are wave-uniform.
+// A wavefront moves RWP rows (time-major) or RWP rows of each of its NB trajectories
+// (slot-major) of a tensor at a time.  A fixed group of lanes works on one row / trajectory and
+// walks it in steps of the group's width, so that consecutive iterations differ by a constant
+// on both sides and the whole transfer needs two address registers.  All loads of a tensor are
+// issued back to back without branches: rows past the end of the trajectory are redirected to
+// the last valid row (a redundant but legal read) and never used.  t_base, b0 and rows are
+// wave-uniform.
 
-// RW rows of a time-major tensor [T][B][Wd]; row segment = NB*Wd elements starting at b0.
-// LDS order afterwards: [row][bl][Wd], i.e. the step of lane (row*NB + bl) sits at lane*Wd.
-// rows = number of valid rows (1..RW).
-template <typename E, int Wd>
+template <int BYTES> struct VecOf;
+template <> struct VecOf<16> { typedef uint4 type; };
+template <> struct VecOf<8> { typedef uint2 type; };
+
+// RWP rows of a time-major tensor [T][B][Wd]; row segment = NB*Wd elements starting at b0.
+// LDS order afterwards: [row][bl][Wd].  rows = number of valid rows (1..RWP).
+template <typename E, int Wd, int RWP>
 __device__ __forceinline__ void stage_time_major(const E *__restrict__ g, int B, int t_base, int rows, int b0,
                                                  E *region, int lane)
 {
-    constexpr int SEGV = NB * Wd * (int)sizeof(E) / 16;
-    constexpr int TOTAL = RW * SEGV;
-    constexpr int NIT = (TOTAL + 63) / 64;
+    constexpr int LPR = 64 / RWP;                            // lanes per row
+    constexpr int SEGV = NB * Wd * (int)sizeof(E) / 16;      // 16-byte vectors per row segment
+    constexpr int NIT = (SEGV + LPR - 1) / LPR;
     static_assert((NB * Wd * sizeof(E)) % 16 == 0, "row segment must be a whole number of 16-byte vectors");
-    const char *base = (const char *)g + ((size_t)t_base * B + b0) * (Wd * sizeof(E));
-    const unsigned row_stride = (unsigned)B * (unsigned)(Wd * sizeof(E));
-    uint4 tmp[NIT];
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int i = min(lane + 64 * it, TOTAL - 1);
-        const int r = i / SEGV, v = i - r * SEGV;
-        const unsigned off = (unsigned)min(r, rows - 1) * row_stride + (unsigned)v * 16u;
-        tmp[it] = *(const uint4 *)(base + off);
-    }
+    const int r = lane / LPR, v0 = lane % LPR;
+    const char *src = (const char *)g + ((size_t)t_base * B + b0) * (Wd * sizeof(E)) +
+                      (size_t)((unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * sizeof(E))) + (unsigned)v0 * 16u);
+    char *dst = (char *)region + (r * SEGV + v0) * 16;
     wave_lds_sync();   // every lane is done reading what the region held before
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int i = lane + 64 * it;
-        if (it < NIT - 1 || i < TOTAL) ((uint4 *)region)[i] = tmp[it];
+        const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
+        // past the end of the segment (last iteration only): re-read this lane's first vector
+        const uint4 x = *(const uint4 *)(src + (inside ? LPR * it * 16 : 0));
+        if (inside) *(uint4 *)(dst + LPR * it * 16) = x;
     }
     wave_lds_sync();   // the new contents are visible to every lane
 }
 
-// RW consecutive rows of NB trajectories of a slot-major plane [slot][T][Wd].
+// RWP consecutive rows of NB trajectories of a slot-major plane [slot][T][Wd].
 // LDS order afterwards: [bl][row][Wd].  slot_row0[bl] = slot * T (first row of the trajectory).
-// The last vector of a short row range may read up to 12 bytes past it; the plane's padding
+// The last vector of a short row range may read up to 15 bytes past it; the plane's padding
 // makes that legal.
-template <typename E, int Wd>
+template <typename E, int Wd, int RWP>
 __device__ __forceinline__ void stage_slot_major(const E *__restrict__ plane, int t_base, int rows,
                                                  const int *slot_row0, E *region, int lane)
 {
-    constexpr int VPT = RW * Wd * (int)sizeof(E) / 16;
-    constexpr int TOTAL = NB * VPT;
-    constexpr int NIT = (TOTAL + 63) / 64;
-    static_assert((RW * Wd * sizeof(E)) % 16 == 0, "RW rows must be a whole number of 16-byte vectors");
-    const int last_vec = (rows * Wd * (int)sizeof(E) - 1) / 16;
-    uint4 tmp[NIT];
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int i = min(lane + 64 * it, TOTAL - 1);
-        const int bl = i / VPT, v = i - bl * VPT;
-        const char *p = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E));
-        tmp[it] = ((const uint4 *)p)[min(v, last_vec)];
-    }
+    constexpr int BYTES = RWP * Wd * (int)sizeof(E);         // per trajectory
+    constexpr int VB = (BYTES % 16 == 0) ? 16 : 8;
+    static_assert(BYTES % VB == 0, "RWP rows must be a whole number of vectors");
+    typedef typename VecOf<VB>::type vec_t;
+    constexpr int LPT = 64 / NB;                             // lanes per trajectory
+    constexpr int VPT = BYTES / VB;
+    constexpr int NIT = (VPT + LPT - 1) / LPT;
+    const int bl = lane / LPT, v0 = lane % LPT;
+    const int last_vec = (rows * Wd * (int)sizeof(E) - 1) / VB;
+    const char *src = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E));
+    char *dst = (char *)region + (bl * VPT + v0) * VB;
     wave_lds_sync();   // every lane is done reading what the region held before
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int i = lane + 64 * it;
-        if (it < NIT - 1 || i < TOTAL) ((uint4 *)region)[i] = tmp[it];
+        const vec_t x = *(const vec_t *)(src + min(v0 + LPT * it, last_vec) * VB);
+        if (VPT % LPT == 0 || it < NIT - 1 || v0 + LPT * it < VPT) *(vec_t *)(dst + LPT * it * VB) = x;
     }
     wave_lds_sync();   // the new contents are visible to every lane
 }
 
-template <typename E, int Wd, bool SLOT>
+template <typename E, int Wd, int RWP, bool SLOT>
 __device__ __forceinline__ void stage(const void *g, int B, int t_base, int rows, int b0, const int *slot_row0,
                                       void *region, int lane)
 {
     if (SLOT)
-        stage_slot_major<E, Wd>((const E *)g, t_base, rows, slot_row0, (E *)region, lane);
+        stage_slot_major<E, Wd, RWP>((const E *)g, t_base, rows, slot_row0, (E *)region, lane);
     else
-        stage_time_major<E, Wd>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
+        stage_time_major<E, Wd, RWP>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
 }
 
 // LDS region ([row][bl][Wd] floats) -> time-major global tensor, 16-byte stores.
-template <int Wd>
+template <int Wd, int RWP>
 __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B, int t_base, int rows, int b0,
                                                    const float *region, int lane)
 {
+    constexpr int LPR = 64 / RWP;
     constexpr int SEGV = NB * Wd * 4 / 16;
-    constexpr int TOTAL = RW * SEGV;
-    constexpr int NIT = (TOTAL + 63) / 64;
-    char *base = (char *)g + ((size_t)t_base * B + b0) * (Wd * 4);
-    const unsigned row_stride = (unsigned)B * (unsigned)(Wd * 4);
-    uint4 tmp[NIT];
+    constexpr int NIT = (SEGV + LPR - 1) / LPR;
+    const int r = lane / LPR, v0 = lane % LPR;
+    char *dst = (char *)g + ((size_t)t_base * B + b0) * (Wd * 4) +
+                (size_t)((unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)) + (unsigned)v0 * 16u);
+    const char *src = (const char *)region + (r * SEGV + v0) * 16;
     wave_lds_sync();   // every lane has written the values of its own step
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) tmp[it] = ((const uint4 *)region)[min(lane + 64 * it, TOTAL - 1)];
-#pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int i = lane + 64 * it;
-        const int r = i / SEGV, v = i - r * SEGV;
-        if (i < TOTAL && r < rows) *(uint4 *)(base + ((unsigned)r * row_stride + (unsigned)v * 16u)) = tmp[it];
+        const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
+        const uint4 x = *(const uint4 *)(src + (inside ? LPR * it * 16 : 0));
+        if (r < rows && inside) *(uint4 *)(dst + LPR * it * 16) = x;
     }
 }
 
@@ -244,16 +241,17 @@ __device__ __forceinline__ void surrogate(const LossArgs &a, double R, double ad
     g = clipped ? 0.0 : -adv * R * a.inv_M;
 }
 
-// Backward scan of one chunk.  sd/sg hold delta and gamma*lambda*c for TC x NB steps
-// (zero for steps past T); threads tid < NB each run one trajectory and leave the
-// accumulated advantage in sd.  Two workgroup barriers.
+// Backward scan of one chunk of TCH time steps.  sd/sg hold delta and gamma*lambda*c for
+// TCH x NB steps (zero for steps past T); threads tid < NB each run one trajectory and leave
+// the accumulated advantage in sd.  Two workgroup barriers.
+template <int TCH>
 __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid)
 {
     __syncthreads();
     if (tid < NB) {
         double acc = carry;
 #pragma unroll 8
-        for (int j = TC - 1; j >= 0; --j) {
+        for (int j = TCH - 1; j >= 0; --j) {
             acc = fma(sg[j * NB + tid], acc, sd[j * NB + tid]);
             sd[j * NB + tid] = acc;
         }

@@ -5,24 +5,31 @@ namespace impact {
 
 // Distribution tensors are [..][2D]: D means, then D log standard deviations.
 // Order per chunk: actions, worker, target (kept in registers), scan, learner.
+// P lanes share a step; lane p takes the DH = ceil(D / P) dimensions starting at p * DH.
 //
 // Precision: fp64 throughout.  log pi(a) is a sum of D terms -((a - mu)/sigma)^2 / 2 - log sigma
 // of size O(1)..O(10); the ratios pi_target/pi_worker and pi_theta/pi_target, the advantages
 // and the gradients (policy term against KL term) are differences of such sums, and the accuracy
 // target is far below fp32 rounding of the terms.  fp64 multiply-adds run at the unpacked-fp32 rate.
-template <int D, typename ST, bool SLOT>
+template <int D, int P, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
 {
     constexpr int W = 2 * D;
-    __shared__ __align__(16) float region_all[NWAVES][64 * W];
-    __shared__ double sd[2][TC * NB];
-    __shared__ double sg[2][TC * NB];
+    constexpr int DH = (D + P - 1) / P;            // dimensions per lane
+    constexpr int SPW = 64 / P;                    // steps per wavefront
+    constexpr int RWP = SPW / NB;                  // time rows per wavefront
+    constexpr int TCH = NWAVES * RWP;              // time rows per chunk
+    __shared__ __align__(16) float region_all[NWAVES][SPW * W];
+    __shared__ double sd[2][TCH * NB];
+    __shared__ double sg[2][TCH * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rl = lane / NB, bl = lane % NB, tl = wave * RW + rl;
+    const int step = lane / P, part = lane % P;    // step within the wavefront, share of its dimensions
+    const int rl = step / NB, bl = step % NB, tl = wave * RWP + rl;
+    const bool lead = part == 0;                   // the lane that stores the step's scalars
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
     const int b0 = tile * NB, b = b0 + bl;
     float *region = region_all[wave];
@@ -38,17 +45,19 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
         __syncthreads();
     }
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
-    const int own_step = SLOT ? (bl * RW + rl) : lane;   // position of my step in a staged buffer-side tensor
-    const int own_lrn = lane * W;
+    const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
+    const int d0 = part * DH;                             // my first dimension
+    // my i-th dimension; only the last one can fall past D (padding lane), where a valid one is re-read
+    auto dim = [&](int i) { return (P * DH != D && i == DH - 1) ? min(d0 + i, D - 1) : d0 + i; };
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
     double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
-    const int nchunk = (a.T + TC - 1) / TC;
+    const int nchunk = (a.T + TCH - 1) / TCH;
 
     for (int c = nchunk - 1; c >= 0; --c) {
-        const int t_base = c * TC + wave * RW;
-        const int rows = min(RW, a.T - t_base);        // valid time rows of this wave, may be <= 0
+        const int t_base = c * TCH + wave * RWP;
+        const int rows = min(RWP, a.T - t_base);       // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
         const bool valid = t < a.T;
         const int par = c & 1;
@@ -57,8 +66,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
 
         float V = 0.f;
         ScanInputs sc = {0.0, 0.0};
-        float act[D];
-        Held<ST, W> tg;
+        float act[DH], tgm[DH], tgl[DH];               // action, target mean, target log-std of my dimensions
         double lt = 0.0, w = 0.0;                      // log pi_target(a) + const, pi_target / pi_worker
 
         if (rows > 0) {
@@ -71,81 +79,94 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
             const bool done = a.dones[s_buf] != 0;
 
             // ---- actions ----
-            stage<ST, D, SLOT>(a.actions, a.B, t_base, rows, b0, slot_row0, region, lane);
+            stage<ST, D, RWP, SLOT>(a.actions, a.B, t_base, rows, b0, slot_row0, region, lane);
 #pragma unroll
-            for (int d = 0; d < D; ++d) act[d] = widen(region_st[own_step * D + d]);
+            for (int i = 0; i < DH; ++i) act[i] = widen(region_st[own_step * D + dim(i)]);
 
             // ---- worker: log pi_worker(a) (the common -D/2 log 2pi is dropped: only differences are used) ----
-            stage<ST, W, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
+            stage<ST, W, RWP, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
             double lw = 0.0;
-            {
-                Held<ST, W> wk;
-                wk.load(region_st + own_step * W);
 #pragma unroll
-                for (int d = 0; d < D; ++d) {
-                    const double ls = (double)wk.get(D + d);
-                    const double diff = (double)act[d] - (double)wk.get(d);
-                    lw += __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                    sched_fence(d);
-                }
+            for (int i = 0; i < DH; ++i) {
+                const double ls = (double)widen(region_st[own_step * W + D + dim(i)]);
+                const double diff = (double)act[i] - (double)widen(region_st[own_step * W + dim(i)]);
+                const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
+                lw += (d0 + i < D) ? term : 0.0;
+                sched_fence(i);
             }
+            lw = pair_sum<P>(lw);
 
             // ---- target: log pi_target(a); mean and log-std stay in registers for the KL term ----
-            stage<ST, W, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
-            tg.load(region_st + own_step * W);
+            stage<ST, W, RWP, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const double ls = (double)tg.get(D + d);
-                const double diff = (double)act[d] - (double)tg.get(d);
-                lt += __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                sched_fence(d);
+            for (int i = 0; i < DH; ++i) {
+                tgm[i] = widen(region_st[own_step * W + dim(i)]);
+                tgl[i] = widen(region_st[own_step * W + D + dim(i)]);
+                const double ls = (double)tgl[i];
+                const double diff = (double)act[i] - (double)tgm[i];
+                const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
+                lt += (d0 + i < D) ? term : 0.0;
+                sched_fence(i);
             }
+            lt = pair_sum<P>(lt);
             w = exp64(lt - lw);
             sc = scan_inputs(a, w, r, done, V, Vn);
         }
 
         // ---- scan: adv_t ----
-        sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
-        sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
-        chunk_scan(sd[par], sg[par], carry, tid);
+        if (lead) {
+            sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
+            sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
+        }
+        chunk_scan<TCH>(sd[par], sg[par], carry, tid);
         const double adv = sd[par][tl * NB + bl];
 
         if (rows > 0) {
             // ---- learner: log pi_theta(a) and entropy first, then KL and gradients ----
-            stage_time_major<float, W>(a.learner, a.B, t_base, rows, b0, region, lane);
-            double E[D];                                   // 1 / sigma_theta^2
+            stage_time_major<float, W, RWP>(a.learner, a.B, t_base, rows, b0, region, lane);
+            float *own = region + step * W;
+            double E[DH];                                  // 1 / sigma_theta^2
             double ll = 0.0, H = 0.0, KL = 0.0;
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const double ls = (double)region[own_lrn + D + d];
-                const double diff = (double)act[d] - (double)region[own_lrn + d];
-                E[d] = exp64(-2.0 * ls);
-                ll += __builtin_fma(-0.5 * diff * diff, E[d], -ls);
-                H += ls;
-                sched_fence(d);
+            for (int i = 0; i < DH; ++i) {
+                const double ls = (double)own[D + dim(i)];
+                const double diff = (double)act[i] - (double)own[dim(i)];
+                E[i] = exp64(-2.0 * ls);
+                const double term = __builtin_fma(-0.5 * diff * diff, E[i], -ls);
+                ll += (d0 + i < D) ? term : 0.0;
+                H += (d0 + i < D) ? ls : 0.0;
+                sched_fence(i);
             }
-            H += D * ((double)kHalfLog2Pi + 0.5);
+            ll = pair_sum<P>(ll);
+            H = pair_sum<P>(H) + D * ((double)kHalfLog2Pi + 0.5);
             const double R = surrogate_ratio(a, exp64(ll - lt), w);
             double s, g;
             surrogate(a, R, adv, s, g);
+            wave_lds_sync();   // re-read mean and log-std from LDS below rather than holding them in registers
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                const double mu = (double)region[own_lrn + d];
-                const double ls = (double)region[own_lrn + D + d];
-                const double diff = (double)act[d] - mu;
-                const double zz = diff * diff * E[d];                         // ((a - mu) / sigma)^2
-                const double lst = (double)tg.get(D + d);
-                const double dm = mu - (double)tg.get(d);
-                const double q = __builtin_fma(dm, dm, exp64(2.0 * lst)) * E[d];   // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
-                KL += (ls - lst) + (0.5 * q - 0.5);
+            for (int i = 0; i < DH; ++i) {
+                const double mu = (double)own[dim(i)];
+                const double ls = (double)own[D + dim(i)];
+                const double diff = (double)act[i] - mu;
+                const double zz = diff * diff * E[i];                            // ((a - mu) / sigma)^2
+                const double lst = (double)tgl[i];
+                const double dm = mu - (double)tgm[i];
+                const double q = __builtin_fma(dm, dm, exp64(2.0 * lst)) * E[i]; // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
+                const double kl_d = (ls - lst) + (0.5 * q - 0.5);
+                KL += (d0 + i < D) ? kl_d : 0.0;
                 // dL/dmu = g dlogp/dmu + kl/M dKL/dmu;  dL/dls = g dlogp/dls - ent/M + kl/M dKL/dls
-                region[own_lrn + d] = (float)((g * diff + ck * dm) * E[d]);
-                region[own_lrn + D + d] = (float)(__builtin_fma(g, zz - 1.0, __builtin_fma(ck, 1.0 - q, -ce)));
-                sched_fence(d);
+                const float gmu = (float)((g * diff + ck * dm) * E[i]);
+                const float gls = (float)(__builtin_fma(g, zz - 1.0, __builtin_fma(ck, 1.0 - q, -ce)));
+                if (P == 1 || d0 + i < D) {
+                    own[dim(i)] = gmu;
+                    own[D + dim(i)] = gls;
+                }
+                sched_fence(i);
             }
-            unstage_time_major<W>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
+            KL = pair_sum<P>(KL);
+            unstage_time_major<W, RWP>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
 
-            if (valid) {
+            if (valid && lead) {
                 a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
                 if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
                 if (a.adv) a.adv[s_tm] = (float)adv;
@@ -159,16 +180,16 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     store_partials(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
-template <int D>
+template <int D, int P>
 static bool launch_gauss_D(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
 {
     const dim3 grid(num_tiles(a.B)), block(NTHREADS);
     if (dtype == IMPACT_F32) {
-        if (slot_major) hipLaunchKernelGGL((loss_gauss_static<D, float, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_gauss_static<D, float, false>), grid, block, 0, s, a);
+        if (slot_major) hipLaunchKernelGGL((loss_gauss_static<D, P, float, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_gauss_static<D, P, float, false>), grid, block, 0, s, a);
     } else {
-        if (slot_major) hipLaunchKernelGGL((loss_gauss_static<D, bf16_t, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_gauss_static<D, bf16_t, false>), grid, block, 0, s, a);
+        if (slot_major) hipLaunchKernelGGL((loss_gauss_static<D, P, bf16_t, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_gauss_static<D, P, bf16_t, false>), grid, block, 0, s, a);
     }
     return true;
 }
@@ -177,9 +198,9 @@ static bool launch_gauss_D(int dtype, bool slot_major, const LossArgs &a, hipStr
 bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
 {
     switch (a.A) {
-    case 3: return launch_gauss_D<3>(dtype, slot_major, a, s);
-    case 6: return launch_gauss_D<6>(dtype, slot_major, a, s);
-    case 17: return launch_gauss_D<17>(dtype, slot_major, a, s);
+    case 3: return launch_gauss_D<3, 1>(dtype, slot_major, a, s);
+    case 6: return launch_gauss_D<6, 1>(dtype, slot_major, a, s);
+    case 17: return launch_gauss_D<17, 2>(dtype, slot_major, a, s);
     default: return false;
     }
 }

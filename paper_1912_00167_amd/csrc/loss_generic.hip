@@ -33,13 +33,14 @@ __device__ __forceinline__ double gauss_logp(const ST *p, const AT *act, int D)
 template <int DIST, typename ST, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
 {
-    __shared__ double sd[2][TC * NB];
-    __shared__ double sg[2][TC * NB];
+    __shared__ double sd[2][TC_MAX * NB];
+    __shared__ double sg[2][TC_MAX * NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
 
     const int A = a.A;
     const int W = (DIST == IMPACT_CATEGORICAL) ? A : 2 * A;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int RW = 64 / NB, TC = TC_MAX;
     const int rl = lane / NB, bl = lane % NB, tl = wave * RW + rl;
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
     const int b = tile * NB + bl;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         }
         sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
         sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
-        chunk_scan(sd[par], sg[par], carry, tid);
+        chunk_scan<TC>(sd[par], sg[par], carry, tid);
         const double adv = sd[par][tl * NB + bl];
 
         if (valid) {

@@ -3,6 +3,7 @@ oracle on the same arrays, compare with the stated tolerance."""
 from __future__ import annotations
 
 import math
+import os
 import sys
 from dataclasses import replace
 
@@ -16,8 +17,15 @@ ATOL, RTOL = 1e-6, 1e-5       # fp32 results against the fp64 oracle: |x - y| <=
 
 
 def say(msg: str) -> None:
+    """Name the case before its GPU step: on stdout, and in a file that survives output capture."""
     print(msg, flush=True)
     sys.stdout.flush()
+    try:
+        if os.path.isdir("gpurun_out"):
+            with open(os.path.join("gpurun_out", "gpu_test_progress.log"), "a") as f:
+                f.write(msg + "\n")
+    except OSError:
+        pass
 
 
 def to_device(x, torch, device="cuda"):
