@@ -23,6 +23,7 @@ def _compile(src: str) -> str:
     cmd = ["hipcc", "-c", os.path.join(CSRC, src), "-o", obj] + COMMON
     if src.endswith(".hip"):
         cmd += DEVICE
+    cmd += os.environ.get("IMPACT_HIPCC_FLAGS", "").split()
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

@@ -24,20 +24,17 @@ constexpr float kHalfLog2Pi = 0.91893853320467274178f;
 // is harmless (the learner's softmax inside the gradient).
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
 
-// e^x in fp64, relative error about 1e-13: x = n ln2 + r with |r| <= ln2/2, Taylor polynomial of
-// degree 10 in r (Horner), scaled by 2^n.  fp64 multiply-adds run at the same rate as unpacked
+// e^x in fp64, relative error about 2e-10: x = n ln2 + r with |r| <= ln2/2, Taylor polynomial of
+// degree 8 in r (Horner), scaled by 2^n.  fp64 multiply-adds run at the same rate as unpacked
 // fp32 ones on this chip, so this costs about as much as a correctly rounded fp32 exponential.
 // Why fp64 at all: advantages and gradients are sums of O(1)..O(10) terms that often cancel, and
 // the accuracy target (1e-6 absolute) is far below the fp32 rounding of those terms.
 __device__ __forceinline__ double exp64(double x)
 {
-    x = fmax(x, -800.0);
     const double n = __builtin_rint(x * 1.4426950408889634074);
     double r = __builtin_fma(-n, 6.93147180369123816490e-01, x);
     r = __builtin_fma(-n, 1.90821492927058770002e-10, r);
-    double p = 1.0 / 3628800.0;
-    p = __builtin_fma(p, r, 1.0 / 362880.0);
-    p = __builtin_fma(p, r, 1.0 / 40320.0);
+    double p = 1.0 / 40320.0;
     p = __builtin_fma(p, r, 1.0 / 5040.0);
     p = __builtin_fma(p, r, 1.0 / 720.0);
     p = __builtin_fma(p, r, 1.0 / 120.0);
@@ -46,14 +43,17 @@ __device__ __forceinline__ double exp64(double x)
     p = __builtin_fma(p, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
-    return ldexp(p, (int)n);
+    return ldexp(p, (int)n);   // the conversion saturates; ldexp then gives 0 or inf for absurd arguments
 }
 
 // The per-element loops are fully unrolled so that their arrays live in registers.  Left alone,
 // the instruction scheduler interleaves all iterations and keeps every temporary alive at once;
 // a fence every few iterations bounds the register footprint (other wavefronts supply the
 // latency hiding instead).
-constexpr int kSchedEvery = 2;
+#ifndef IMPACT_SCHED_EVERY
+#define IMPACT_SCHED_EVERY 2
+#endif
+constexpr int kSchedEvery = IMPACT_SCHED_EVERY;
 __device__ __forceinline__ void sched_fence(int k)
 {
     if ((k % kSchedEvery) == kSchedEvery - 1) __builtin_amdgcn_sched_barrier(0);
@@ -104,6 +104,16 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for every
+// outstanding global access of the wavefront, which would serialise the asynchronous loads that
+// are deliberately kept in flight across the scan; this one orders LDS traffic alone.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // ---- staging: global <-> wave-private LDS region, order preserved -------------------------
@@ -183,6 +193,69 @@ __device__ __forceinline__ void stage(const void *g, int B, int t_base, int rows
         stage_time_major<E, Wd, RWP>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
 }
 
+// ---- the same transfers as direct global -> LDS loads (no registers in between) ------------
+//
+// gfx950 can write a 16- or 4-byte load straight into LDS: lane L of the instruction deposits its
+// data at (wave-uniform LDS base) + L * size.  One instruction therefore fills 64 consecutive
+// vectors of the region, and the lane computes which row / trajectory its vector belongs to.
+// The loads are asynchronous (tracked by vmcnt): issue them early, use the data later.
+
+__device__ __forceinline__ void wait_lds_reads_done() { __builtin_amdgcn_s_waitcnt(0xC07F); }   // lgkmcnt(0)
+__device__ __forceinline__ void wait_dma_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }         // vmcnt(0)
+
+template <typename E, int Wd, int RWP>
+__device__ __forceinline__ void dma_time_major(const E *__restrict__ g, int B, int t_base, int rows, int b0,
+                                               E *region, int lane)
+{
+    constexpr int SEGV = NB * Wd * (int)sizeof(E) / 16;      // 16-byte vectors per row segment
+    constexpr int TOTAL = RWP * SEGV;
+    constexpr int NIT = (TOTAL + 63) / 64;
+    static_assert((NB * Wd * sizeof(E)) % 16 == 0, "row segment must be a whole number of 16-byte vectors");
+    const char *base = (const char *)g + ((size_t)t_base * B + b0) * (Wd * sizeof(E));
+    const unsigned row_stride = (unsigned)B * (unsigned)(Wd * sizeof(E));
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int i = lane + 64 * it;
+        const int r = i / SEGV, v = i - r * SEGV;
+        const char *src = base + ((unsigned)min(r, rows - 1) * row_stride + (unsigned)v * 16u);
+        if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL)
+            __builtin_amdgcn_global_load_lds(src, (char *)region + it * 1024, 16, 0, 0);
+    }
+}
+
+template <typename E, int Wd, int RWP>
+__device__ __forceinline__ void dma_slot_major(const E *__restrict__ plane, int t_base, int rows,
+                                               const int *slot_row0, E *region, int lane)
+{
+    constexpr int BYTES = RWP * Wd * (int)sizeof(E);         // per trajectory
+    constexpr int VB = (BYTES % 16 == 0) ? 16 : 4;
+    static_assert(BYTES % VB == 0, "RWP rows must be a whole number of vectors");
+    constexpr int VPT = BYTES / VB;
+    constexpr int TOTAL = NB * VPT;
+    constexpr int NIT = (TOTAL + 63) / 64;
+    const int last_vec = (rows * Wd * (int)sizeof(E) - 1) / VB;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int i = lane + 64 * it;
+        const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
+        const char *src = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E)) + min(v, last_vec) * VB;
+        if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL) {
+            if constexpr (VB == 16) __builtin_amdgcn_global_load_lds(src, (char *)region + it * 1024, 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(src, (char *)region + it * 256, 4, 0, 0);
+        }
+    }
+}
+
+template <typename E, int Wd, int RWP, bool SLOT>
+__device__ __forceinline__ void dma(const void *g, int B, int t_base, int rows, int b0, const int *slot_row0,
+                                    void *region, int lane)
+{
+    if (SLOT)
+        dma_slot_major<E, Wd, RWP>((const E *)g, t_base, rows, slot_row0, (E *)region, lane);
+    else
+        dma_time_major<E, Wd, RWP>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
+}
+
 // LDS region ([row][bl][Wd] floats) -> time-major global tensor, 16-byte stores.
 template <int Wd, int RWP>
 __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B, int t_base, int rows, int b0,
@@ -247,7 +320,7 @@ __device__ __forceinline__ void surrogate(const LossArgs &a, double R, double ad
 template <int TCH>
 __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid)
 {
-    __syncthreads();
+    lds_barrier();
     if (tid < NB) {
         double acc = carry;
 #pragma unroll 8
@@ -257,7 +330,7 @@ __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double 
         }
         carry = acc;
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 __device__ __forceinline__ float wave_sum(float x)

@@ -1,4 +1,6 @@
 // Specialised loss kernels for diagonal-Gaussian policies with a compile-time action dimension.
+#include <type_traits>
+
 #include "loss_device.h"
 
 namespace impact {
@@ -19,7 +21,18 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     constexpr int SPW = 64 / P;                    // steps per wavefront
     constexpr int RWP = SPW / NB;                  // time rows per wavefront
     constexpr int TCH = NWAVES * RWP;              // time rows per chunk
-    __shared__ __align__(16) float region_all[NWAVES][SPW * W];
+    // per-wavefront staging regions: actions, worker, target (storage dtype), learner / gradients (fp32)
+    __shared__ __align__(16) ST r_act_all[NWAVES][SPW * D];
+    __shared__ __align__(16) ST r_wk_all[NWAVES][SPW * W];
+    __shared__ __align__(16) ST r_tg_all[NWAVES][SPW * W];
+    // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
+    // while this chunk's gradients are still being produced in the other one
+    constexpr int LDS_ONE = NWAVES * SPW * ((D + 2 * W) * (int)sizeof(ST) + W * 4) + 4 * TCH * NB * 8 + 256;
+    constexpr int NLN = (LDS_ONE + NWAVES * SPW * W * 4 <= 64 * 1024) ? 2 : 1;
+    // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
+    // tell a read of one region from an asynchronous load still in flight into the other)
+    __shared__ __align__(16) float r_ln0_all[NWAVES][SPW * W];
+    __shared__ __align__(16) float r_ln1_all[NLN == 2 ? NWAVES : 1][NLN == 2 ? SPW * W : 4];
     __shared__ double sd[2][TCH * NB];
     __shared__ double sg[2][TCH * NB];
     __shared__ int slot_row0[NB];
@@ -32,8 +45,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     const bool lead = part == 0;                   // the lane that stores the step's scalars
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
     const int b0 = tile * NB, b = b0 + bl;
-    float *region = region_all[wave];
-    const ST *region_st = (const ST *)region;
+    ST *r_act = r_act_all[wave], *r_wk = r_wk_all[wave], *r_tg = r_tg_all[wave];
 
     float bad = 0.f;
     if (SLOT) {
@@ -49,18 +61,42 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     const int d0 = part * DH;                             // my first dimension
     // my i-th dimension; only the last one can fall past D (padding lane), where a valid one is re-read
     auto dim = [&](int i) { return (P * DH != D && i == DH - 1) ? min(d0 + i, D - 1) : d0 + i; };
+    // ... and only there a term has to be masked out of the sums
+    auto keep = [&](int i, double x) { return (P * DH != D && i == DH - 1 && d0 + i >= D) ? 0.0 : x; };
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
+
+    // Asynchronous loads of one chunk's tensors into this wavefront's regions.
+    auto fetch_buffer_side = [&](int c) {
+        const int t_base = c * TCH + wave * RWP;
+        const int rows = min(RWP, a.T - t_base);
+        if (rows > 0) {
+            dma<ST, D, RWP, SLOT>(a.actions, a.B, t_base, rows, b0, slot_row0, r_act, lane);
+            dma<ST, W, RWP, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, r_wk, lane);
+            dma<ST, W, RWP, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, r_tg, lane);
+        }
+    };
+    auto fetch_learner = [&](int c, float *region) {
+        const int t_base = c * TCH + wave * RWP;
+        const int rows = min(RWP, a.T - t_base);
+        if (rows > 0) dma_time_major<float, W, RWP>(a.learner, a.B, t_base, rows, b0, region, lane);
+    };
 
     double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     const int nchunk = (a.T + TCH - 1) / TCH;
+    fetch_buffer_side(nchunk - 1);
+    fetch_learner(nchunk - 1, r_ln0_all[wave]);
 
-    for (int c = nchunk - 1; c >= 0; --c) {
+    // One chunk; Q = parity counted from the first chunk processed (it selects the learner region).
+    auto chunk = [&](auto parity, int c) {
+        constexpr int Q = decltype(parity)::value;
+        float *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
+        float *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
         const int t_base = c * TCH + wave * RWP;
         const int rows = min(RWP, a.T - t_base);       // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
         const bool valid = t < a.T;
-        const int par = c & 1;
+        constexpr int par = Q;
         const int tc = min(t, a.T - 1);                // clamped: loads of masked steps stay in range
         const size_t s_tm = (size_t)tc * a.B + b;
 
@@ -78,41 +114,39 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
             const float r = widen(((const ST *)a.rewards)[s_buf]);
             const bool done = a.dones[s_buf] != 0;
 
+            wait_dma_done();
+            wave_lds_sync();
             // ---- actions ----
-            stage<ST, D, RWP, SLOT>(a.actions, a.B, t_base, rows, b0, slot_row0, region, lane);
 #pragma unroll
-            for (int i = 0; i < DH; ++i) act[i] = widen(region_st[own_step * D + dim(i)]);
+            for (int i = 0; i < DH; ++i) act[i] = widen(r_act[own_step * D + dim(i)]);
 
             // ---- worker: log pi_worker(a) (the common -D/2 log 2pi is dropped: only differences are used) ----
-            stage<ST, W, RWP, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, region, lane);
             double lw = 0.0;
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
-                const double ls = (double)widen(region_st[own_step * W + D + dim(i)]);
-                const double diff = (double)act[i] - (double)widen(region_st[own_step * W + dim(i)]);
+                const double ls = (double)widen(r_wk[own_step * W + D + dim(i)]);
+                const double diff = (double)act[i] - (double)widen(r_wk[own_step * W + dim(i)]);
                 const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                lw += (d0 + i < D) ? term : 0.0;
+                lw += keep(i, term);
                 sched_fence(i);
             }
             lw = pair_sum<P>(lw);
 
             // ---- target: log pi_target(a); mean and log-std stay in registers for the KL term ----
-            stage<ST, W, RWP, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, region, lane);
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
-                tgm[i] = widen(region_st[own_step * W + dim(i)]);
-                tgl[i] = widen(region_st[own_step * W + D + dim(i)]);
+                tgm[i] = widen(r_tg[own_step * W + dim(i)]);
+                tgl[i] = widen(r_tg[own_step * W + D + dim(i)]);
                 const double ls = (double)tgl[i];
                 const double diff = (double)act[i] - (double)tgm[i];
                 const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                lt += (d0 + i < D) ? term : 0.0;
+                lt += keep(i, term);
                 sched_fence(i);
             }
             lt = pair_sum<P>(lt);
             w = exp64(lt - lw);
             sc = scan_inputs(a, w, r, done, V, Vn);
         }
-
         // ---- scan: adv_t ----
         if (lead) {
             sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
@@ -121,10 +155,19 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
         chunk_scan<TCH>(sd[par], sg[par], carry, tid);
         const double adv = sd[par][tl * NB + bl];
 
+        // The buffer-side regions were consumed before the scan (and the other learner region, if there
+        // are two, when the previous chunk's gradients left it): start the next chunk's loads now, so
+        // that they fly during this chunk's learner pass.
+        wave_lds_sync();
+        wait_lds_reads_done();
+        if (c > 0) {
+            fetch_buffer_side(c - 1);
+            if (NLN == 2) fetch_learner(c - 1, r_ln_next);
+        }
+
         if (rows > 0) {
             // ---- learner: log pi_theta(a) and entropy first, then KL and gradients ----
-            stage_time_major<float, W, RWP>(a.learner, a.B, t_base, rows, b0, region, lane);
-            float *own = region + step * W;
+            float *own = r_ln + step * W;
             double E[DH];                                  // 1 / sigma_theta^2
             double ll = 0.0, H = 0.0, KL = 0.0;
 #pragma unroll
@@ -133,8 +176,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
                 const double diff = (double)act[i] - (double)own[dim(i)];
                 E[i] = exp64(-2.0 * ls);
                 const double term = __builtin_fma(-0.5 * diff * diff, E[i], -ls);
-                ll += (d0 + i < D) ? term : 0.0;
-                H += (d0 + i < D) ? ls : 0.0;
+                ll += keep(i, term);
+                H += keep(i, ls);
                 sched_fence(i);
             }
             ll = pair_sum<P>(ll);
@@ -151,20 +194,21 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
                 const double zz = diff * diff * E[i];                            // ((a - mu) / sigma)^2
                 const double lst = (double)tgl[i];
                 const double dm = mu - (double)tgm[i];
-                const double q = __builtin_fma(dm, dm, exp64(2.0 * lst)) * E[i]; // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
+                // sigma_t^2 only enters the KL term, where an fp32-grade value is ample
+                const double q = __builtin_fma(dm, dm, (double)exp_fast(2.f * tgl[i])) * E[i];   // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
                 const double kl_d = (ls - lst) + (0.5 * q - 0.5);
-                KL += (d0 + i < D) ? kl_d : 0.0;
+                KL += keep(i, kl_d);
                 // dL/dmu = g dlogp/dmu + kl/M dKL/dmu;  dL/dls = g dlogp/dls - ent/M + kl/M dKL/dls
                 const float gmu = (float)((g * diff + ck * dm) * E[i]);
                 const float gls = (float)(__builtin_fma(g, zz - 1.0, __builtin_fma(ck, 1.0 - q, -ce)));
-                if (P == 1 || d0 + i < D) {
+                if (P * DH == D || i < DH - 1 || d0 + i < D) {
                     own[dim(i)] = gmu;
                     own[D + dim(i)] = gls;
                 }
                 sched_fence(i);
             }
             KL = pair_sum<P>(KL);
-            unstage_time_major<W, RWP>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
+            unstage_time_major<W, RWP>(a.grad_dist, a.B, t_base, rows, b0, r_ln, lane);
 
             if (valid && lead) {
                 a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
@@ -176,6 +220,16 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
                 sum_k += (float)KL;
             }
         }
+        if (NLN == 1) {
+            // the gradients have left the learner region: start the next chunk's learner load into it
+            wave_lds_sync();
+            wait_lds_reads_done();
+            if (c > 0) fetch_learner(c - 1, r_ln_next);
+        }
+    };
+    for (int c = nchunk - 1; c >= 0; c -= 2) {
+        chunk(std::integral_constant<int, 0>{}, c);
+        if (c >= 1) chunk(std::integral_constant<int, 1>{}, c - 1);
     }
     store_partials(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
