@@ -22,6 +22,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
     __shared__ double sg[2][TC_MAX * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
+    __shared__ double exp_tbl[EXP_TABLE_SIZE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -33,14 +34,13 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
     const ST *region_st = (const ST *)region;
 
     float bad = 0.f;
-    if (SLOT) {
-        if (tid < NB) {
-            int s = a.slots[b0 + tid];
-            if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
-            slot_row0[tid] = s * a.T;
-        }
-        __syncthreads();
+    exp64_table_init(exp_tbl, tid);
+    if (SLOT && tid < NB) {
+        int s = a.slots[b0 + tid];
+        if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
+        slot_row0[tid] = s * a.T;
     }
+    __syncthreads();
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
     const int own_buf = (SLOT ? (bl * RW + rl) : lane) * A;
     const int own_lrn = lane * A;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 for (int k = 1; k < A; ++k) m = fmaxf(m, z[k]);
 #pragma unroll
                 for (int k = 0; k < A; ++k) {
-                    Sw += exp64((double)z[k] - (double)m);
+                    Sw += exp64((double)z[k] - (double)m, exp_tbl);
                     sched_fence(k);
                 }
                 xw = (double)za - (double)m;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
 #pragma unroll
                 for (int k = 0; k < A; ++k) {
                     const double xd = (double)x[k] - (double)m;
-                    const double e = exp64(xd);
+                    const double e = exp64(xd, exp_tbl);
                     St += e;
                     et[k] = (float)e;
                     tdot = fmaf(et[k], (float)xd, tdot);      // sum e^t_k x^t_k
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 xt_a = za;
             }
             const double xt = (double)xt_a - (double)mt;
-            w = exp64(xt - xw) * (Sw / St);
+            w = exp64(xt - xw, exp_tbl) * (Sw / St);
             sc = scan_inputs(a, w, r, done, V, Vn);
         }
 
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                 KL = (tdot - cross) * invSt - logSt + logSl;          // sum p^t_k (log p^t_k - log p_k)
                 // R1 = pi_theta(a) / pi_target(a)
                 const double xl = (double)za - (double)m;
-                const double R1 = exp64(xl - ((double)xt_a - (double)mt)) * (St / Sl);
+                const double R1 = exp64(xl - ((double)xt_a - (double)mt), exp_tbl) * (St / Sl);
                 const double R = surrogate_ratio(a, R1, w);
                 double g;
                 surrogate(a, R, adv, s, g);
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
                     region[own_lrn + k] = fmaf(gf, (k == act) ? one_minus_pa : -pk, base);
                 }
             }
-            unstage_time_major<A, RW>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
+            unstage_time_major<A, RW, false>(a.grad_dist, a.B, t_base, rows, b0, region, lane);
 
             if (valid) {
                 a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv

@@ -24,26 +24,37 @@ constexpr float kHalfLog2Pi = 0.91893853320467274178f;
 // is harmless (the learner's softmax inside the gradient).
 __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
 
-// e^x in fp64, relative error about 2e-10: x = n ln2 + r with |r| <= ln2/2, Taylor polynomial of
-// degree 8 in r (Horner), scaled by 2^n.  fp64 multiply-adds run at the same rate as unpacked
-// fp32 ones on this chip, so this costs about as much as a correctly rounded fp32 exponential.
+// e^x in fp64, relative error about 1e-10.  x = (64 m + j) ln2/64 + r with |r| <= ln2/128:
+// e^x = 2^m * 2^(j/64) * e^r, 2^(j/64) from a 64-entry table in LDS and e^r from its Taylor
+// polynomial of degree 3 (r^4/24 < 4e-11).  fp64 multiply-adds cost twice an fp32 one on this chip,
+// so the short polynomial matters; the table read goes down the LDS pipe instead of the VALU.
 // Why fp64 at all: advantages and gradients are sums of O(1)..O(10) terms that often cancel, and
 // the accuracy target (1e-6 absolute) is far below the fp32 rounding of those terms.
-__device__ __forceinline__ double exp64(double x)
+constexpr int EXP_TABLE_SIZE = 64;
+
+// Fill the table (first 64 threads of the workgroup); the caller synchronises before use.
+__device__ __forceinline__ void exp64_table_init(double *tbl, int tid)
 {
-    const double n = __builtin_rint(x * 1.4426950408889634074);
-    double r = __builtin_fma(-n, 6.93147180369123816490e-01, x);
-    r = __builtin_fma(-n, 1.90821492927058770002e-10, r);
-    double p = 1.0 / 40320.0;
-    p = __builtin_fma(p, r, 1.0 / 5040.0);
-    p = __builtin_fma(p, r, 1.0 / 720.0);
-    p = __builtin_fma(p, r, 1.0 / 120.0);
-    p = __builtin_fma(p, r, 1.0 / 24.0);
-    p = __builtin_fma(p, r, 1.0 / 6.0);
-    p = __builtin_fma(p, r, 0.5);
+    if (tid < EXP_TABLE_SIZE) tbl[tid] = exp2((double)tid * (1.0 / EXP_TABLE_SIZE));
+}
+
+__device__ __forceinline__ double exp64(double x, const double *tbl)
+{
+    const double n = __builtin_rint(x * (64.0 * 1.4426950408889634074));
+    double r = __builtin_fma(-n, 6.93147180369123816490e-01 / 64.0, x);
+    r = __builtin_fma(-n, 1.90821492927058770002e-10 / 64.0, r);
+    const int ni = (int)n;          // saturates for absurd arguments; ldexp then gives 0 or inf
+    const double scale = tbl[ni & (EXP_TABLE_SIZE - 1)];
+    double p = __builtin_fma(1.0 / 6.0, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
-    return ldexp(p, (int)n);   // the conversion saturates; ldexp then gives 0 or inf for absurd arguments
+    return ldexp(scale * p, ni >> 6);
+}
+
+// exp(-2 ls) / 2 = 1 / (2 sigma^2): the factor one half of the Gaussian exponent is folded in.
+__device__ __forceinline__ double half_inv_var(double ls, const double *tbl)
+{
+    return exp64(__builtin_fma(ls, -2.0, -6.93147180559945309417e-01), tbl);
 }
 
 // The per-element loops are fully unrolled so that their arrays live in registers.  Left alone,
@@ -199,9 +210,41 @@ __device__ __forceinline__ void stage(const void *g, int B, int t_base, int rows
 // data at (wave-uniform LDS base) + L * size.  One instruction therefore fills 64 consecutive
 // vectors of the region, and the lane computes which row / trajectory its vector belongs to.
 // The loads are asynchronous (tracked by vmcnt): issue them early, use the data later.
+//
+// They are issued from inline assembly, not through the compiler's builtin: the compiler tracks a
+// builtin load conservatively and drains the wavefront's whole queue of outstanding accesses (the
+// gradient stores of the previous chunk and the loads just issued for the next one included) before
+// the first LDS read that might alias it.  Issued this way the loads are invisible to that
+// tracking, and the kernels wait for them explicitly with the helpers below.  An access the
+// compiler does not know about can only make its own waits for other accesses longer, never too
+// short, because accesses retire in issue order.
+
+typedef __attribute__((address_space(3))) char lds_byte;
+
+// the LDS base address goes through M0, which is restored afterwards
+#define IMPACT_LDS_LOAD(OP)                                                                                    \
+    unsigned saved_m0;                                                                                         \
+    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_byte *)lds);                   \
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\t" OP " %1, off\n\ts_mov_b32 m0, %0" \
+                 : "=&s"(saved_m0)                                                                             \
+                 : "v"(src), "s"(base)                                                                         \
+                 : "memory")
+
+// lane L: 16 bytes from src (per lane) to lds (wave-uniform) + 16 L
+__device__ __forceinline__ void lds_load16(const void *src, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dwordx4"); }
+// lane L: 4 bytes from src to lds + 4 L
+__device__ __forceinline__ void lds_load4(const void *src, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dword"); }
+#undef IMPACT_LDS_LOAD
 
 __device__ __forceinline__ void wait_lds_reads_done() { __builtin_amdgcn_s_waitcnt(0xC07F); }   // lgkmcnt(0)
 __device__ __forceinline__ void wait_dma_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }         // vmcnt(0)
+// Wait until at most N of the wavefront's global loads and stores are outstanding; they retire in
+// issue order, so everything but the N youngest is complete afterwards.  (vmcnt(N), N < 64.)
+template <int N>
+__device__ __forceinline__ void wait_all_but_youngest()
+{
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
 
 template <typename E, int Wd, int RWP>
 __device__ __forceinline__ void dma_time_major(const E *__restrict__ g, int B, int t_base, int rows, int b0,
@@ -219,7 +262,7 @@ __device__ __forceinline__ void dma_time_major(const E *__restrict__ g, int B, i
         const int r = i / SEGV, v = i - r * SEGV;
         const char *src = base + ((unsigned)min(r, rows - 1) * row_stride + (unsigned)v * 16u);
         if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL)
-            __builtin_amdgcn_global_load_lds(src, (char *)region + it * 1024, 16, 0, 0);
+            lds_load16(src, (char *)region + it * 1024);
     }
 }
 
@@ -240,8 +283,8 @@ __device__ __forceinline__ void dma_slot_major(const E *__restrict__ plane, int 
         const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
         const char *src = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E)) + min(v, last_vec) * VB;
         if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL) {
-            if constexpr (VB == 16) __builtin_amdgcn_global_load_lds(src, (char *)region + it * 1024, 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(src, (char *)region + it * 256, 4, 0, 0);
+            if constexpr (VB == 16) lds_load16(src, (char *)region + it * 1024);
+            else lds_load4(src, (char *)region + it * 256);
         }
     }
 }
@@ -257,23 +300,34 @@ __device__ __forceinline__ void dma(const void *g, int B, int t_base, int rows, 
 }
 
 // LDS region ([row][bl][Wd] floats) -> time-major global tensor, 16-byte stores.
-template <int Wd, int RWP>
+// FULL: all RWP rows are valid.  Every store instruction then executes with all lanes enabled (lanes
+// past the end of a row segment repeat its last vector), so the number of stores in flight after this
+// call is a compile-time constant; the wait that precedes the next chunk's first use of prefetched
+// data can then leave exactly these stores outstanding.
+constexpr int unstage_stores(int Wd, int RWP)     // store instructions per call
+{
+    return (NB * Wd * 4 / 16 + 64 / RWP - 1) / (64 / RWP);
+}
+
+template <int Wd, int RWP, bool FULL>
 __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B, int t_base, int rows, int b0,
                                                    const float *region, int lane)
 {
     constexpr int LPR = 64 / RWP;
     constexpr int SEGV = NB * Wd * 4 / 16;
     constexpr int NIT = (SEGV + LPR - 1) / LPR;
+    static_assert(NIT == unstage_stores(Wd, RWP), "store count");
     const int r = lane / LPR, v0 = lane % LPR;
     char *dst = (char *)g + ((size_t)t_base * B + b0) * (Wd * 4) +
-                (size_t)((unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)) + (unsigned)v0 * 16u);
-    const char *src = (const char *)region + (r * SEGV + v0) * 16;
+                (size_t)((unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)));
+    const char *src = (const char *)region + r * SEGV * 16;
     wave_lds_sync();   // every lane has written the values of its own step
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
-        const uint4 x = *(const uint4 *)(src + (inside ? LPR * it * 16 : 0));
-        if (r < rows && inside) *(uint4 *)(dst + LPR * it * 16) = x;
+        const int v = (SEGV % LPR == 0 || it < NIT - 1) ? v0 + LPR * it : min(v0 + LPR * it, SEGV - 1);
+        const uint4 x = *(const uint4 *)(src + v * 16);
+        if (FULL || (r < rows && inside)) *(uint4 *)(dst + (unsigned)v * 16u) = x;
     }
 }
 

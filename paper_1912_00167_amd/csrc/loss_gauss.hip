@@ -27,7 +27,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     __shared__ __align__(16) ST r_tg_all[NWAVES][SPW * W];
     // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
     // while this chunk's gradients are still being produced in the other one
-    constexpr int LDS_ONE = NWAVES * SPW * ((D + 2 * W) * (int)sizeof(ST) + W * 4) + 4 * TCH * NB * 8 + 256;
+    constexpr int LDS_ONE = NWAVES * SPW * ((D + 2 * W) * (int)sizeof(ST) + W * 4) + 4 * TCH * NB * 8 + 1024;
     constexpr int NLN = (LDS_ONE + NWAVES * SPW * W * 4 <= 64 * 1024) ? 2 : 1;
     // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
     // tell a read of one region from an asynchronous load still in flight into the other)
@@ -37,6 +37,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     __shared__ double sg[2][TCH * NB];
     __shared__ int slot_row0[NB];
     __shared__ float red[NWAVES][PARTIAL_STRIDE];
+    __shared__ double exp_tbl[EXP_TABLE_SIZE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -48,14 +49,13 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     ST *r_act = r_act_all[wave], *r_wk = r_wk_all[wave], *r_tg = r_tg_all[wave];
 
     float bad = 0.f;
-    if (SLOT) {
-        if (tid < NB) {
-            int s = a.slots[b0 + tid];
-            if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
-            slot_row0[tid] = s * a.T;
-        }
-        __syncthreads();
+    exp64_table_init(exp_tbl, tid);
+    if (SLOT && tid < NB) {
+        int s = a.slots[b0 + tid];
+        if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
+        slot_row0[tid] = s * a.T;
     }
+    __syncthreads();
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
     const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
     const int d0 = part * DH;                             // my first dimension
@@ -66,85 +66,105 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
     // Asynchronous loads of one chunk's tensors into this wavefront's regions.
-    auto fetch_buffer_side = [&](int c) {
+    auto fetch_buffer_side = [&](int c, auto is_tail) {
         const int t_base = c * TCH + wave * RWP;
-        const int rows = min(RWP, a.T - t_base);
+        const int rows = decltype(is_tail)::value ? min(RWP, a.T - t_base) : RWP;
         if (rows > 0) {
             dma<ST, D, RWP, SLOT>(a.actions, a.B, t_base, rows, b0, slot_row0, r_act, lane);
             dma<ST, W, RWP, SLOT>(a.worker, a.B, t_base, rows, b0, slot_row0, r_wk, lane);
             dma<ST, W, RWP, SLOT>(a.target, a.B, t_base, rows, b0, slot_row0, r_tg, lane);
         }
     };
-    auto fetch_learner = [&](int c, float *region) {
+    auto fetch_learner = [&](int c, auto is_tail, float *region) {
         const int t_base = c * TCH + wave * RWP;
-        const int rows = min(RWP, a.T - t_base);
+        const int rows = decltype(is_tail)::value ? min(RWP, a.T - t_base) : RWP;
         if (rows > 0) dma_time_major<float, W, RWP>(a.learner, a.B, t_base, rows, b0, region, lane);
     };
 
     double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     const int nchunk = (a.T + TCH - 1) / TCH;
-    fetch_buffer_side(nchunk - 1);
-    fetch_learner(nchunk - 1, r_ln0_all[wave]);
+    // The per-step scalars of a chunk are loaded one chunk ahead as well, into registers: a load issued
+    // at the start of a chunk would have to wait for the previous chunk's gradient stores, since
+    // outstanding loads and stores of a wavefront retire in issue order.
+    float nx_V = 0.f, nx_Vnext = 0.f;
+    ST nx_r = 0;
+    uint8_t nx_done = 0;
+    const float Vboot = a.bootstrap[b];
+    auto fetch_scalars = [&](int c) {
+        const int t = c * TCH + tl;
+        const int tc = min(t, a.T - 1);                // clamped: loads of masked steps stay in range
+        const size_t s_tm = (size_t)tc * a.B + b;
+        const size_t s_buf = SLOT ? (size_t)(my_row0 + tc) : s_tm;
+        nx_V = a.values[s_tm];
+        nx_Vnext = a.values[(size_t)min(t + 1, a.T - 1) * a.B + b];
+        nx_r = ((const ST *)a.rewards)[s_buf];
+        nx_done = a.dones[s_buf];
+    };
+    fetch_buffer_side(nchunk - 1, std::true_type{});
+    fetch_learner(nchunk - 1, std::true_type{}, r_ln0_all[wave]);
+    fetch_scalars(nchunk - 1);
+    wait_dma_done();
 
     // One chunk; Q = parity counted from the first chunk processed (it selects the learner region).
-    auto chunk = [&](auto parity, int c) {
+    // TAIL: the chunk that holds the end of the trajectory, the only one that can be ragged, and the
+    // first to be processed.  All the others are full and their code is free of conditionals, which
+    // fixes the number of stores a chunk leaves in flight (see the wait at the top).
+    auto chunk = [&](auto parity, auto is_tail, int c) {
         constexpr int Q = decltype(parity)::value;
+        constexpr bool TAIL = decltype(is_tail)::value;
         float *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
         float *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
         const int t_base = c * TCH + wave * RWP;
-        const int rows = min(RWP, a.T - t_base);       // valid time rows of this wave, may be <= 0
+        const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
-        const bool valid = t < a.T;
+        const bool valid = !TAIL || t < a.T;
         constexpr int par = Q;
-        const int tc = min(t, a.T - 1);                // clamped: loads of masked steps stay in range
-        const size_t s_tm = (size_t)tc * a.B + b;
+        const size_t s_tm = (size_t)min(t, a.T - 1) * a.B + b;
 
-        float V = 0.f;
+        // This chunk's loads are complete once only the previous chunk's gradient stores remain
+        // (loads and stores of a wavefront retire in issue order).
+        wait_all_but_youngest<(NLN == 2 && !TAIL) ? unstage_stores(W, RWP) : 0>();
+        const float V = nx_V, Vnext = nx_Vnext, r = widen(nx_r);
+        const bool done = nx_done != 0;
         ScanInputs sc = {0.0, 0.0};
         float act[DH], tgm[DH], tgl[DH];               // action, target mean, target log-std of my dimensions
-        double lt = 0.0, w = 0.0;                      // log pi_target(a) + const, pi_target / pi_worker
+        // log pi(a) + D/2 log 2pi = -Q - S with Q = sum_d (a - mu)^2 / (2 sigma^2), S = sum_d log sigma
+        double Qt = 0.0, St = 0.0, w = 0.0;            // target's Q and S; pi_target / pi_worker
 
         if (rows > 0) {
-            V = a.values[s_tm];
-            const float Vnext = a.values[(size_t)min(t + 1, a.T - 1) * a.B + b];
-            const float Vboot = a.bootstrap[b];
             const float Vn = (t + 1 < a.T) ? Vnext : Vboot;
-            const size_t s_buf = SLOT ? (size_t)(my_row0 + tc) : s_tm;
-            const float r = widen(((const ST *)a.rewards)[s_buf]);
-            const bool done = a.dones[s_buf] != 0;
-
-            wait_dma_done();
             wave_lds_sync();
             // ---- actions ----
 #pragma unroll
             for (int i = 0; i < DH; ++i) act[i] = widen(r_act[own_step * D + dim(i)]);
 
-            // ---- worker: log pi_worker(a) (the common -D/2 log 2pi is dropped: only differences are used) ----
-            double lw = 0.0;
+            // ---- worker ----
+            double Qw = 0.0, Sw = 0.0;
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
                 const double ls = (double)widen(r_wk[own_step * W + D + dim(i)]);
                 const double diff = (double)act[i] - (double)widen(r_wk[own_step * W + dim(i)]);
-                const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                lw += keep(i, term);
+                Qw += keep(i, diff * diff * half_inv_var(ls, exp_tbl));
+                Sw += keep(i, ls);
                 sched_fence(i);
             }
-            lw = pair_sum<P>(lw);
 
-            // ---- target: log pi_target(a); mean and log-std stay in registers for the KL term ----
+            // ---- target; mean and log-std stay in registers for the KL term ----
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
                 tgm[i] = widen(r_tg[own_step * W + dim(i)]);
                 tgl[i] = widen(r_tg[own_step * W + D + dim(i)]);
                 const double ls = (double)tgl[i];
                 const double diff = (double)act[i] - (double)tgm[i];
-                const double term = __builtin_fma(-0.5 * diff * diff, exp64(-2.0 * ls), -ls);
-                lt += keep(i, term);
+                Qt += keep(i, diff * diff * half_inv_var(ls, exp_tbl));
+                St += keep(i, ls);
                 sched_fence(i);
             }
-            lt = pair_sum<P>(lt);
-            w = exp64(lt - lw);
+            Qt = pair_sum<P>(Qt);
+            St = pair_sum<P>(St);
+            // pi_target(a) / pi_worker(a) = exp((Q_w + S_w) - (Q_t + S_t))
+            w = exp64((pair_sum<P>(Qw + Sw) - Qt) - St, exp_tbl);
             sc = scan_inputs(a, w, r, done, V, Vn);
         }
         // ---- scan: adv_t ----
@@ -154,6 +174,12 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
         }
         chunk_scan<TCH>(sd[par], sg[par], carry, tid);
         const double adv = sd[par][tl * NB + bl];
+        // the per-step outputs that depend on the scan alone leave now, ahead of the next chunk's loads
+        if (valid && lead) {
+            a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
+            if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
+            if (a.adv) a.adv[s_tm] = (float)adv;
+        }
 
         // The buffer-side regions were consumed before the scan (and the other learner region, if there
         // are two, when the previous chunk's gradients left it): start the next chunk's loads now, so
@@ -161,59 +187,57 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
         wave_lds_sync();
         wait_lds_reads_done();
         if (c > 0) {
-            fetch_buffer_side(c - 1);
-            if (NLN == 2) fetch_learner(c - 1, r_ln_next);
+            fetch_buffer_side(c - 1, std::false_type{});
+            if (NLN == 2) fetch_learner(c - 1, std::false_type{}, r_ln_next);
+            fetch_scalars(c - 1);
         }
 
         if (rows > 0) {
             // ---- learner: log pi_theta(a) and entropy first, then KL and gradients ----
             float *own = r_ln + step * W;
-            double E[DH];                                  // 1 / sigma_theta^2
-            double ll = 0.0, H = 0.0, KL = 0.0;
+            double E[DH];                                  // 1 / (2 sigma_theta^2)
+            double Ql = 0.0, Sl = 0.0, Qk = 0.0;
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
                 const double ls = (double)own[D + dim(i)];
                 const double diff = (double)act[i] - (double)own[dim(i)];
-                E[i] = exp64(-2.0 * ls);
-                const double term = __builtin_fma(-0.5 * diff * diff, E[i], -ls);
-                ll += keep(i, term);
-                H += keep(i, ls);
+                E[i] = half_inv_var(ls, exp_tbl);
+                Ql += keep(i, diff * diff * E[i]);
+                Sl += keep(i, ls);
                 sched_fence(i);
             }
-            ll = pair_sum<P>(ll);
-            H = pair_sum<P>(H) + D * ((double)kHalfLog2Pi + 0.5);
-            const double R = surrogate_ratio(a, exp64(ll - lt), w);
+            Ql = pair_sum<P>(Ql);
+            Sl = pair_sum<P>(Sl);
+            const double H = Sl + D * ((double)kHalfLog2Pi + 0.5);
+            // pi_theta / pi_target = exp((Q_t + S_t) - (Q_l + S_l))
+            const double R = surrogate_ratio(a, exp64((Qt - Ql) + (St - Sl), exp_tbl), w);
             double s, g;
             surrogate(a, R, adv, s, g);
-            wave_lds_sync();   // re-read mean and log-std from LDS below rather than holding them in registers
+            // With E = 1 / (2 sigma^2):  dL/dmu = (2g (a - mu) + 2 ck (mu - mu_t)) E
+            //   dL/dls = 2g (a - mu)^2 E - 2 ck (sigma_t^2 + (mu - mu_t)^2) E + (ck - g - ce)
+            const double g2 = 2.0 * g, ck2 = 2.0 * ck, c0 = ck - g - ce;
 #pragma unroll
             for (int i = 0; i < DH; ++i) {
                 const double mu = (double)own[dim(i)];
-                const double ls = (double)own[D + dim(i)];
                 const double diff = (double)act[i] - mu;
-                const double zz = diff * diff * E[i];                            // ((a - mu) / sigma)^2
-                const double lst = (double)tgl[i];
                 const double dm = mu - (double)tgm[i];
                 // sigma_t^2 only enters the KL term, where an fp32-grade value is ample
-                const double q = __builtin_fma(dm, dm, (double)exp_fast(2.f * tgl[i])) * E[i];   // (sigma_t^2 + (mu - mu_t)^2) / sigma^2
-                const double kl_d = (ls - lst) + (0.5 * q - 0.5);
-                KL += keep(i, kl_d);
-                // dL/dmu = g dlogp/dmu + kl/M dKL/dmu;  dL/dls = g dlogp/dls - ent/M + kl/M dKL/dls
-                const float gmu = (float)((g * diff + ck * dm) * E[i]);
-                const float gls = (float)(__builtin_fma(g, zz - 1.0, __builtin_fma(ck, 1.0 - q, -ce)));
+                const double qh = __builtin_fma(dm, dm, (double)exp_fast(2.f * tgl[i])) * E[i];   // q / 2
+                Qk += keep(i, qh);
+                const float gmu = (float)(__builtin_fma(g2, diff, ck2 * dm) * E[i]);
+                const float gls = (float)__builtin_fma(g2, diff * diff * E[i], __builtin_fma(-ck2, qh, c0));
                 if (P * DH == D || i < DH - 1 || d0 + i < D) {
                     own[dim(i)] = gmu;
                     own[D + dim(i)] = gls;
                 }
                 sched_fence(i);
             }
-            KL = pair_sum<P>(KL);
-            unstage_time_major<W, RWP>(a.grad_dist, a.B, t_base, rows, b0, r_ln, lane);
+            // KL(pi_target || pi_theta) = sum_d [ log sigma - log sigma_t + q_d / 2 - 1/2 ]
+            const double KL = (Sl - St) + pair_sum<P>(Qk) - 0.5 * D;
+            if (TAIL) unstage_time_major<W, RWP, false>(a.grad_dist, a.B, t_base, rows, b0, r_ln, lane);
+            else unstage_time_major<W, RWP, true>(a.grad_dist, a.B, t_base, rows, b0, r_ln, lane);
 
             if (valid && lead) {
-                a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
-                if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
-                if (a.adv) a.adv[s_tm] = (float)adv;
                 sum_s += (float)s;
                 sum_v += (float)(0.5 * adv * adv);
                 sum_h += (float)H;
@@ -224,12 +248,16 @@ __global__ __launch_bounds__(NTHREADS) void loss_gauss_static(const LossArgs a)
             // the gradients have left the learner region: start the next chunk's learner load into it
             wave_lds_sync();
             wait_lds_reads_done();
-            if (c > 0) fetch_learner(c - 1, r_ln_next);
+            if (c > 0) fetch_learner(c - 1, std::false_type{}, r_ln_next);
         }
+        if (TAIL) wait_dma_done();   // the number of stores just issued varies: drain them
     };
-    for (int c = nchunk - 1; c >= 0; c -= 2) {
-        chunk(std::integral_constant<int, 0>{}, c);
-        if (c >= 1) chunk(std::integral_constant<int, 1>{}, c - 1);
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    chunk(P0{}, std::true_type{}, nchunk - 1);
+    for (int c = nchunk - 2; c >= 0; c -= 2) {
+        chunk(P1{}, std::false_type{}, c);
+        if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
     }
     store_partials(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
