@@ -34,7 +34,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_cat_static(const LossArgs a)
     const ST *region_st = (const ST *)region;
 
     float bad = 0.f;
-    exp64_table_init(exp_tbl, tid);
+    exp64_table_init(exp_tbl, tid, NTHREADS);
     if (SLOT && tid < NB) {
         int s = a.slots[b0 + tid];
         if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }

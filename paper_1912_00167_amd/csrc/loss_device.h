@@ -26,35 +26,52 @@ __device__ __forceinline__ float exp_fast(float x) { return __builtin_amdgcn_exp
 
 // e^x in fp64, relative error about 1e-10.  x = (64 m + j) ln2/64 + r with |r| <= ln2/128:
 // e^x = 2^m * 2^(j/64) * e^r, 2^(j/64) from a 64-entry table in LDS and e^r from its Taylor
-// polynomial of degree 3 (r^4/24 < 4e-11).  fp64 multiply-adds cost twice an fp32 one on this chip,
-// so the short polynomial matters; the table read goes down the LDS pipe instead of the VALU.
+// polynomial of degree 3 (r^4/24 < 4e-11).  Every VALU instruction costs the same issue slot here,
+// fp64 or not, so what counts is their number: the table read goes down the LDS pipe instead, and
+// adding 1.5 * 2^52 rounds to an integer and leaves it in the low mantissa bits in one operation.
 // Why fp64 at all: advantages and gradients are sums of O(1)..O(10) terms that often cancel, and
 // the accuracy target (1e-6 absolute) is far below the fp32 rounding of those terms.
-constexpr int EXP_TABLE_SIZE = 64;
+constexpr int EXP_TABLE_SIZE = 128;          // 2^(j/64), then 2^(j/64) / 2, j = 0..63
+constexpr double kRoundMagic = 6755399441055744.0;   // 1.5 * 2^52
+constexpr double kLn2Hi64 = 6.93147180369123816490e-01 / 64.0, kLn2Lo64 = 1.90821492927058770002e-10 / 64.0;
 
-// Fill the table (first 64 threads of the workgroup); the caller synchronises before use.
-__device__ __forceinline__ void exp64_table_init(double *tbl, int tid)
+// Fill the table (first 128 threads of the workgroup, or two rounds of a single wavefront); the
+// caller synchronises before use.
+__device__ __forceinline__ void exp64_table_init(double *tbl, int tid, int nthreads)
 {
-    if (tid < EXP_TABLE_SIZE) tbl[tid] = exp2((double)tid * (1.0 / EXP_TABLE_SIZE));
+    for (int j = tid; j < EXP_TABLE_SIZE; j += nthreads)
+        tbl[j] = exp2((double)(j & 63) * (1.0 / 64.0) - (double)(j >> 6));
 }
+
+__device__ __forceinline__ int low_word(double x) { return (int)(unsigned)__builtin_bit_cast(unsigned long long, x); }
 
 __device__ __forceinline__ double exp64(double x, const double *tbl)
 {
-    const double n = __builtin_rint(x * (64.0 * 1.4426950408889634074));
-    double r = __builtin_fma(-n, 6.93147180369123816490e-01 / 64.0, x);
-    r = __builtin_fma(-n, 1.90821492927058770002e-10 / 64.0, r);
-    const int ni = (int)n;          // saturates for absurd arguments; ldexp then gives 0 or inf
-    const double scale = tbl[ni & (EXP_TABLE_SIZE - 1)];
+    const double t = __builtin_fma(x, 64.0 * 1.4426950408889634074, kRoundMagic);
+    const double n = t - kRoundMagic;
+    const int ni = low_word(t);     // n as an integer; wraps for absurd arguments, where the result is 0 or inf anyway
+    double r = __builtin_fma(-n, kLn2Hi64, x);
+    r = __builtin_fma(-n, kLn2Lo64, r);
     double p = __builtin_fma(1.0 / 6.0, r, 0.5);
     p = __builtin_fma(p, r, 1.0);
     p = __builtin_fma(p, r, 1.0);
-    return ldexp(scale * p, ni >> 6);
+    return ldexp(tbl[ni & 63] * p, ni >> 6);
 }
 
-// exp(-2 ls) / 2 = 1 / (2 sigma^2): the factor one half of the Gaussian exponent is folded in.
+// exp(-2 ls) / 2 = 1 / (2 sigma^2): the factor one half of the Gaussian exponent is folded in (second
+// half of the table), and so is the factor -2: with k = round(-128 ls / ln2) and u = ls + k ln2/128,
+// exp(-2 ls) = 2^(k/64) exp(-2u), exp(-2u) = 1 - 2u + 2u^2 - 4/3 u^3.
 __device__ __forceinline__ double half_inv_var(double ls, const double *tbl)
 {
-    return exp64(__builtin_fma(ls, -2.0, -6.93147180559945309417e-01), tbl);
+    const double t = __builtin_fma(ls, -128.0 * 1.4426950408889634074, kRoundMagic);
+    const double k = t - kRoundMagic;
+    const int ki = low_word(t);
+    double u = __builtin_fma(k, 0.5 * kLn2Hi64, ls);
+    u = __builtin_fma(k, 0.5 * kLn2Lo64, u);
+    double p = __builtin_fma(-4.0 / 3.0, u, 2.0);
+    p = __builtin_fma(p, u, -2.0);
+    p = __builtin_fma(p, u, 1.0);
+    return ldexp(tbl[64 + (ki & 63)] * p, ki >> 6);
 }
 
 // The per-element loops are fully unrolled so that their arrays live in registers.  Left alone,
@@ -68,6 +85,21 @@ constexpr int kSchedEvery = IMPACT_SCHED_EVERY;
 __device__ __forceinline__ void sched_fence(int k)
 {
     if ((k % kSchedEvery) == kSchedEvery - 1) __builtin_amdgcn_sched_barrier(0);
+}
+
+// Wave priority 3 - (band mod 4); the immediate operand forces the switch.
+#ifndef IMPACT_PRIORITY_BAND
+#define IMPACT_PRIORITY_BAND 4
+#endif
+constexpr int kPriorityBand = IMPACT_PRIORITY_BAND;     // chunks per priority band
+__device__ __forceinline__ void set_priority_band(int band)
+{
+    switch (band & 3) {
+    case 0: __builtin_amdgcn_s_setprio(3); break;
+    case 1: __builtin_amdgcn_s_setprio(2); break;
+    case 2: __builtin_amdgcn_s_setprio(1); break;
+    default: __builtin_amdgcn_s_setprio(0); break;
+    }
 }
 
 // Workgroup -> tile map.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs;
@@ -220,20 +252,28 @@ __device__ __forceinline__ void stage(const void *g, int B, int t_base, int rows
 // short, because accesses retire in issue order.
 
 typedef __attribute__((address_space(3))) char lds_byte;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
-// the LDS base address goes through M0, which is restored afterwards
-#define IMPACT_LDS_LOAD(OP)                                                                                    \
-    unsigned saved_m0;                                                                                         \
-    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_byte *)lds);                   \
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\t" OP " %1, off\n\ts_mov_b32 m0, %0" \
-                 : "=&s"(saved_m0)                                                                             \
-                 : "v"(src), "s"(base)                                                                         \
+// a wave-uniform 64-bit address in scalar registers
+__device__ __forceinline__ const char *uniform_ptr(const void *p)
+{
+    const unsigned long long v = (unsigned long long)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const char *)(((unsigned long long)hi << 32) | lo);
+}
+
+// Lane L: 16 (4) bytes from base + offset (base wave-uniform, offset per lane, unsigned 32 bits) to
+// lds + 16 L (4 L), lds wave-uniform.  The LDS base address goes through M0, which is restored.
+#define IMPACT_LDS_LOAD(OP)                                                                                   \
+    unsigned saved_m0;                                                                                        \
+    const unsigned to = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_byte *)lds);                    \
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t" OP " %1, %2\n\ts_mov_b32 m0, %0" \
+                 : "=&s"(saved_m0)                                                                            \
+                 : "v"(offset), "s"(base), "s"(to)                                                            \
                  : "memory")
-
-// lane L: 16 bytes from src (per lane) to lds (wave-uniform) + 16 L
-__device__ __forceinline__ void lds_load16(const void *src, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dwordx4"); }
-// lane L: 4 bytes from src to lds + 4 L
-__device__ __forceinline__ void lds_load4(const void *src, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dword"); }
+__device__ __forceinline__ void lds_load16(const char *base, unsigned offset, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dwordx4"); }
+__device__ __forceinline__ void lds_load4(const char *base, unsigned offset, void *lds) { IMPACT_LDS_LOAD("global_load_lds_dword"); }
 #undef IMPACT_LDS_LOAD
 
 __device__ __forceinline__ void wait_lds_reads_done() { __builtin_amdgcn_s_waitcnt(0xC07F); }   // lgkmcnt(0)
@@ -246,89 +286,116 @@ __device__ __forceinline__ void wait_all_but_youngest()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <typename E, int Wd, int RWP>
-__device__ __forceinline__ void dma_time_major(const E *__restrict__ g, int B, int t_base, int rows, int b0,
-                                               E *region, int lane)
-{
-    constexpr int SEGV = NB * Wd * (int)sizeof(E) / 16;      // 16-byte vectors per row segment
-    constexpr int TOTAL = RWP * SEGV;
-    constexpr int NIT = (TOTAL + 63) / 64;
-    static_assert((NB * Wd * sizeof(E)) % 16 == 0, "row segment must be a whole number of 16-byte vectors");
-    const char *base = (const char *)g + ((size_t)t_base * B + b0) * (Wd * sizeof(E));
-    const unsigned row_stride = (unsigned)B * (unsigned)(Wd * sizeof(E));
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int i = lane + 64 * it;
-        const int r = i / SEGV, v = i - r * SEGV;
-        const char *src = base + ((unsigned)min(r, rows - 1) * row_stride + (unsigned)v * 16u);
-        if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL)
-            lds_load16(src, (char *)region + it * 1024);
-    }
-}
+// One wavefront's share of a chunk of one tensor: RWP time rows of NB trajectories, Wd elements of
+// type E per step.  An address splits into a wave-uniform part that moves from chunk to chunk (kept
+// in scalar registers, advanced by scalar arithmetic) and a per-lane offset that never changes and is
+// computed once, so that issuing a chunk's loads costs no vector arithmetic.
+//   time-major tensor [T][B][Wd]:        RWP row segments of NB * Wd elements, B * Wd elements apart
+//   slot-major plane [slot][T][Wd]:      NB pieces of RWP * Wd elements, one per trajectory
+template <typename E, int Wd, int RWP, bool SLOT>
+struct ChunkLoader {
+    static constexpr int ES = (int)sizeof(E);
+    static constexpr int SEGV = NB * Wd * ES / 16;                 // time-major: 16-byte vectors per row segment
+    static constexpr int BYTES = RWP * Wd * ES;                    // slot-major: bytes per trajectory
+    static constexpr int VB = SLOT ? ((BYTES % 16 == 0) ? 16 : 4) : 16;
+    static constexpr int VPT = BYTES / VB;
+    static constexpr int TOTAL = SLOT ? NB * VPT : RWP * SEGV;     // vectors per chunk
+    static constexpr int NIT = (TOTAL + 63) / 64;                  // load instructions per chunk
+    static_assert(SLOT || (NB * Wd * ES) % 16 == 0, "row segment must be a whole number of 16-byte vectors");
+    static_assert(!SLOT || BYTES % VB == 0, "RWP rows must be a whole number of vectors");
 
-template <typename E, int Wd, int RWP>
-__device__ __forceinline__ void dma_slot_major(const E *__restrict__ plane, int t_base, int rows,
-                                               const int *slot_row0, E *region, int lane)
-{
-    constexpr int BYTES = RWP * Wd * (int)sizeof(E);         // per trajectory
-    constexpr int VB = (BYTES % 16 == 0) ? 16 : 4;
-    static_assert(BYTES % VB == 0, "RWP rows must be a whole number of vectors");
-    constexpr int VPT = BYTES / VB;
-    constexpr int TOTAL = NB * VPT;
-    constexpr int NIT = (TOTAL + 63) / 64;
-    const int last_vec = (rows * Wd * (int)sizeof(E) - 1) / VB;
+    unsigned offset[NIT];
+
+    // rows: valid time rows (1..RWP); vectors of the missing rows re-read valid ones, so that every
+    // load stays inside the tensor
+    __device__ __forceinline__ void plan(int B, int rows, const int *slot_row0, int lane)
+    {
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const int i = lane + 64 * it;
-        const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
-        const char *src = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E)) + min(v, last_vec) * VB;
-        if (TOTAL % 64 == 0 || it < NIT - 1 || i < TOTAL) {
-            if constexpr (VB == 16) lds_load16(src, (char *)region + it * 1024);
-            else lds_load4(src, (char *)region + it * 256);
+        for (int it = 0; it < NIT; ++it) {
+            const int i = lane + 64 * it;
+            if (SLOT) {
+                const int last_vec = (rows * Wd * ES - 1) / VB;
+                const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
+                offset[it] = (unsigned)slot_row0[bl] * (unsigned)(Wd * ES) + (unsigned)(min(v, last_vec) * VB);
+            } else {
+                const int r = i / SEGV, v = i - r * SEGV;
+                offset[it] = (unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * ES)) + (unsigned)v * 16u;
+            }
         }
     }
-}
 
-template <typename E, int Wd, int RWP, bool SLOT>
-__device__ __forceinline__ void dma(const void *g, int B, int t_base, int rows, int b0, const int *slot_row0,
-                                    void *region, int lane)
-{
-    if (SLOT)
-        dma_slot_major<E, Wd, RWP>((const E *)g, t_base, rows, slot_row0, (E *)region, lane);
-    else
-        dma_time_major<E, Wd, RWP>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
-}
+    // wave-uniform address of the chunk whose first row (of this wavefront) is t_base
+    __device__ __forceinline__ static const char *chunk_base(const void *tensor, int B, int t_base, int b0)
+    {
+        const size_t first = SLOT ? (size_t)t_base * (Wd * ES) : ((size_t)t_base * B + b0) * (Wd * ES);
+        return uniform_ptr((const char *)tensor + first);
+    }
 
-// LDS region ([row][bl][Wd] floats) -> time-major global tensor, 16-byte stores.
-// FULL: all RWP rows are valid.  Every store instruction then executes with all lanes enabled (lanes
-// past the end of a row segment repeat its last vector), so the number of stores in flight after this
-// call is a compile-time constant; the wait that precedes the next chunk's first use of prefetched
-// data can then leave exactly these stores outstanding.
-constexpr int unstage_stores(int Wd, int RWP)     // store instructions per call
-{
-    return (NB * Wd * 4 / 16 + 64 / RWP - 1) / (64 / RWP);
-}
+    __device__ __forceinline__ void issue(const char *base, void *region, int lane) const
+    {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            if (TOTAL % 64 == 0 || it < NIT - 1 || lane + 64 * it < TOTAL) {
+                if constexpr (VB == 16) lds_load16(base, offset[it], (char *)region + it * 1024);
+                else lds_load4(base, offset[it], (char *)region + it * 256);
+            }
+        }
+    }
+};
+
+// LDS region ([row][bl][Wd] floats) -> time-major global tensor [T][B][Wd], 16-byte stores; the same
+// split into a wave-uniform chunk address and constant per-lane offsets.  64 / RWP lanes walk each row.
+template <int Wd, int RWP>
+struct ChunkStorer {
+    static constexpr int LPR = 64 / RWP;
+    static constexpr int SEGV = NB * Wd * 4 / 16;
+    static constexpr int NIT = (SEGV + LPR - 1) / LPR;             // store instructions per chunk
+
+    unsigned offset[NIT];      // into the tensor, from the chunk's address
+    unsigned from[NIT];        // into the LDS region
+
+    __device__ __forceinline__ void plan(int B, int lane)
+    {
+        const int r = lane / LPR, v0 = lane % LPR;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            // lanes past the end of a row segment repeat its last vector
+            const int v = (SEGV % LPR == 0 || it < NIT - 1) ? v0 + LPR * it : min(v0 + LPR * it, SEGV - 1);
+            offset[it] = (unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)) + (unsigned)v * 16u;
+            from[it] = (unsigned)(r * SEGV + v) * 16u;
+        }
+    }
+
+    __device__ __forceinline__ static char *chunk_base(float *tensor, int B, int t_base, int b0)
+    {
+        return (char *)uniform_ptr((char *)tensor + ((size_t)t_base * B + b0) * (Wd * 4));
+    }
+
+    // FULL: all RWP rows are valid.  Every store instruction then executes with all lanes enabled, so the
+    // number of stores in flight after this call is a compile-time constant; the wait that precedes the
+    // next chunk's first use of prefetched data can then leave exactly these stores outstanding.
+    template <bool FULL>
+    __device__ __forceinline__ void store(char *base, const float *region, int rows, int lane) const
+    {
+        const int r = lane / LPR, v0 = lane % LPR;
+        wave_lds_sync();   // every lane has written the values of its own step
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
+            const uint4 x = *(const uint4 *)((const char *)region + from[it]);
+            // written once and not read again by this kernel: a streaming store leaves the L2 to the loads
+            if (FULL || (r < rows && inside)) __builtin_nontemporal_store(*(const v4u *)&x, (v4u *)(base + offset[it]));
+        }
+    }
+};
 
 template <int Wd, int RWP, bool FULL>
 __device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B, int t_base, int rows, int b0,
                                                    const float *region, int lane)
 {
-    constexpr int LPR = 64 / RWP;
-    constexpr int SEGV = NB * Wd * 4 / 16;
-    constexpr int NIT = (SEGV + LPR - 1) / LPR;
-    static_assert(NIT == unstage_stores(Wd, RWP), "store count");
-    const int r = lane / LPR, v0 = lane % LPR;
-    char *dst = (char *)g + ((size_t)t_base * B + b0) * (Wd * 4) +
-                (size_t)((unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)));
-    const char *src = (const char *)region + r * SEGV * 16;
-    wave_lds_sync();   // every lane has written the values of its own step
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
-        const int v = (SEGV % LPR == 0 || it < NIT - 1) ? v0 + LPR * it : min(v0 + LPR * it, SEGV - 1);
-        const uint4 x = *(const uint4 *)(src + v * 16);
-        if (FULL || (r < rows && inside)) *(uint4 *)(dst + (unsigned)v * 16u) = x;
-    }
+    ChunkStorer<Wd, RWP> st;
+    st.plan(B, lane);
+    st.template store<FULL>(st.chunk_base(g, B, t_base, b0), region, rows, lane);
 }
 
 // ---- per-step scalar algebra shared by all kernels -----------------------------------------
@@ -371,10 +438,11 @@ __device__ __forceinline__ void surrogate(const LossArgs &a, double R, double ad
 // Backward scan of one chunk of TCH time steps.  sd/sg hold delta and gamma*lambda*c for
 // TCH x NB steps (zero for steps past T); threads tid < NB each run one trajectory and leave
 // the accumulated advantage in sd.  Two workgroup barriers.
-template <int TCH>
+template <int TCH, int NW = NWAVES>
 __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid)
 {
-    lds_barrier();
+    // a single-wavefront workgroup needs no hardware barrier
+    if (NW == 1) wave_lds_sync(); else lds_barrier();
     if (tid < NB) {
         double acc = carry;
 #pragma unroll 8
@@ -384,7 +452,7 @@ __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double 
         }
         carry = acc;
     }
-    lds_barrier();
+    if (NW == 1) wave_lds_sync(); else lds_barrier();
 }
 
 __device__ __forceinline__ float wave_sum(float x)
@@ -395,6 +463,7 @@ __device__ __forceinline__ float wave_sum(float x)
 }
 
 // Sum the per-thread loss terms over the workgroup and store them for the final reduction.
+template <int NW = NWAVES>
 __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], float *partials, int tile, int tid,
                                                float s, float v, float h, float k, float bad)
 {
@@ -407,7 +476,7 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], flo
     if (tid < 5) {
         float t = 0.f;
 #pragma unroll
-        for (int w = 0; w < NWAVES; ++w) t += red[w][tid];
+        for (int w = 0; w < NW; ++w) t += red[w][tid];
         partials[(size_t)tile * PARTIAL_STRIDE + tid] = t;
     }
 }
