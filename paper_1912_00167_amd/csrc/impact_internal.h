@@ -17,6 +17,7 @@ constexpr int NB = 8;
 constexpr int NTHREADS = 256;
 constexpr int NWAVES = NTHREADS / 64;
 constexpr int TC_MAX = NTHREADS / NB;       // time steps per chunk when P = 1
+constexpr int T_PRELOAD = 128;              // longest trajectory whose rewards and flags a single-wavefront tile keeps in LDS
 constexpr int PARTIAL_STRIDE = 8;           // floats per workgroup in the partial-sum workspace
 
 struct LossArgs {

@@ -44,6 +44,11 @@ __global__ __launch_bounds__(64 * NW) void loss_gauss_static(const LossArgs a)
     __shared__ int slot_row0[NB];
     __shared__ float red[NW][PARTIAL_STRIDE];
     __shared__ double exp_tbl[EXP_TABLE_SIZE];
+    // A wavefront that walks its trajectories alone (NW == 1) reads their rewards and termination flags
+    // from the buffer once, whole, instead of a few bytes per trajectory and chunk.
+    constexpr bool PRE = NW == 1 && SLOT;
+    __shared__ ST pre_r[PRE ? NB * T_PRELOAD : 1];
+    __shared__ uint8_t pre_d[PRE ? NB * T_PRELOAD : 4];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,6 +67,14 @@ __global__ __launch_bounds__(64 * NW) void loss_gauss_static(const LossArgs a)
         slot_row0[tid] = s * a.T;
     }
     __syncthreads();
+    if (PRE) {
+        for (int i = tid; i < NB * a.T; i += 64 * NW) {
+            const int j = i / a.T, t = i - j * a.T;
+            pre_r[j * T_PRELOAD + t] = ((const ST *)a.rewards)[slot_row0[j] + t];
+            pre_d[j * T_PRELOAD + t] = a.dones[slot_row0[j] + t];
+        }
+        __syncthreads();
+    }
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
     const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
     const int d0 = part * DH;                             // my first dimension
@@ -106,8 +119,10 @@ __global__ __launch_bounds__(64 * NW) void loss_gauss_static(const LossArgs a)
         const size_t s_buf = SLOT ? (size_t)(my_row0 + tc) : s_tm;
         nx_V = a.values[s_tm];
         nx_Vnext = a.values[(size_t)min(t + 1, a.T - 1) * a.B + b];
-        nx_r = ((const ST *)a.rewards)[s_buf];
-        nx_done = a.dones[s_buf];
+        if (!PRE) {
+            nx_r = ((const ST *)a.rewards)[s_buf];
+            nx_done = a.dones[s_buf];
+        }
     };
     // full chunks: wave-uniform chunk address plus constant lane offsets, as for the tensors above
     const unsigned step_tm = (unsigned)rl * (unsigned)a.B + (unsigned)bl;              // in a [T][B] tensor
@@ -118,10 +133,13 @@ __global__ __launch_bounds__(64 * NW) void loss_gauss_static(const LossArgs a)
         const size_t first_buf = SLOT ? (size_t)t_base : first_tm;
         const char *vbase = uniform_ptr(a.values + first_tm);
         nx_V = *(const float *)(vbase + step_tm * 4u);
-        nx_Vnext = *(const float *)(vbase + (step_tm + (unsigned)a.B) * 4u);           // row t + 1 exists: not the tail
-        nx_r = *(const ST *)(uniform_ptr((const ST *)a.rewards + first_buf) + step_buf * (unsigned)sizeof(ST));
-        nx_done = *(const uint8_t *)(uniform_ptr(a.dones + first_buf) + step_buf);
+        if (!PRE) {
+            nx_Vnext = *(const float *)(vbase + (step_tm + (unsigned)a.B) * 4u);       // row t + 1 exists: not the tail
+            nx_r = *(const ST *)(uniform_ptr((const ST *)a.rewards + first_buf) + step_buf * (unsigned)sizeof(ST));
+            nx_done = *(const uint8_t *)(uniform_ptr(a.dones + first_buf) + step_buf);
+        }
     };
+    float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)
     {
         const int t_base = (nchunk - 1) * TCH + wave * RWP;
         const int rows = min(RWP, a.T - t_base);
@@ -166,8 +184,17 @@ __global__ __launch_bounds__(64 * NW) void loss_gauss_static(const LossArgs a)
         // This chunk's loads are complete once only the previous chunk's gradient stores remain
         // (loads and stores of a wavefront retire in issue order).
         wait_all_but_youngest<(NLN == 2 && !TAIL) ? ChunkStorer<W, RWP>::NIT : 0>();
-        const float V = nx_V, Vnext = nx_Vnext, r = widen(nx_r);
-        const bool done = nx_done != 0;
+        const float V = nx_V;
+        float Vnext = nx_Vnext, r = widen(nx_r);
+        bool done = nx_done != 0;
+        if (PRE) {
+            const int at = bl * T_PRELOAD + min(t, a.T - 1);
+            r = widen(pre_r[at]);
+            done = pre_d[at] != 0;
+            // V_{t+1}: the next row of this chunk, or for its last row the first row of the chunk after it
+            if (!TAIL) Vnext = __shfl(rl == 0 ? V_later : V, (lane + NB * P) & 63, 64);
+            V_later = V;
+        }
         ScanInputs sc = {0.0, 0.0};
         double act[DH];                                // action (converted once, used by all three policies)
         float tgm[DH], tgl[DH];                        // target mean, target log-std of my dimensions
@@ -343,7 +370,8 @@ static int single_wave_threshold()
 template <int D, int P>
 static bool launch_gauss_D(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
 {
-    if (num_tiles(a.B) >= single_wave_threshold()) launch_gauss_NW<D, P, 1>(dtype, slot_major, a, s);
+    if (num_tiles(a.B) >= single_wave_threshold() && (!slot_major || a.T <= T_PRELOAD))
+        launch_gauss_NW<D, P, 1>(dtype, slot_major, a, s);
     else launch_gauss_NW<D, P, NWAVES>(dtype, slot_major, a, s);
     return true;
 }

@@ -141,6 +141,40 @@ def test_loss_from_buffer(env, ci, flags):
     _fused_case(torch, binding, wl, n_fill, Bn, flags, seed=ci, label=f"fused {name} {kw} flags={flags}")
 
 
+def test_fused_full_size_c5(env):
+    """The headline configuration as the benchmark launches it: a full ring of 65536 bf16 slots, 16384
+    sampled trajectories of 128 steps, D = 17; every output element against the oracle.  (The ring holds
+    16384 distinct trajectories four times over, which keeps the host-side generation short.)"""
+    torch, binding = env
+    wl = workloads.C5
+    distinct, block = 16384, 4096
+    say(f"case fused full C5 T={wl.T} B={wl.B} A={wl.A} slots={wl.num_slots}: generating")
+    parts = [workloads.make_trajectories(wl, block, stream=500 + i) for i in range(distinct // block)]
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    say("  filling the ring")
+    for rnd in range(wl.num_slots // distinct):
+        for i, part in enumerate(parts):
+            slots_in = binding.impact_buffer_insert(buf, to_device(part, torch))
+            assert int(slots_in[0]) == rnd * distinct + i * block
+    x = {k: np.concatenate([p_[k] for p_ in parts], axis=0 if k == "bootstrap" else 1) for k in parts[0]}
+    del parts
+    # one traversal of the whole ring, then a shuffled quarter of it: the batch's slots lie scattered
+    ring = np.concatenate([binding.impact_buffer_sample(buf, wl.B)[0].copy() for _ in range(wl.num_slots // wl.B)])
+    assert sorted(ring.tolist()) == list(range(wl.num_slots))
+    slots = np.ascontiguousarray(np.random.default_rng(5).permutation(ring)[: wl.B].astype(np.int32))
+    xb = workloads.take_trajectories(x, slots % distinct)
+    del x
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    say("  gpu")
+    out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(np.ascontiguousarray(slots)).cuda(), learner, values,
+                                                  boot, binding.config_from_hyper(wl.hyper))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    buf.close()
+    say("  oracle")
+    check_against_oracle(wl, xb, got, label="fused C5 full")
+
+
 def test_out_of_range_slot_is_flagged_not_dereferenced(env):
     torch, binding = env
     wl = shape_workload(workloads.C1, num_slots=16)
