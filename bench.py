@@ -43,50 +43,58 @@ def algorithmic_bytes_per_step(wl) -> int:
 
 
 def fill_ring(torch, binding, wl, buf, block: int):
-    """Insert num_slots synthetic trajectories block by block; return the learner-side tensors
-    (learner dist, values, bootstrap) per batch-sized group of consecutive slots."""
-    n_blocks = wl.num_slots // block
+    """Fill all num_slots slots block by block; return the learner-side tensors (learner dist, values,
+    bootstrap) per batch-sized group of consecutive slots.  One batch worth of distinct synthetic
+    trajectories is generated and inserted once per batch-sized quarter of the ring (generation on the
+    host is the slow part); every quarter has its own slots and its own learner-side tensors in HBM, so
+    successive steps touch disjoint memory."""
     per_batch = wl.B // block
+    parts = [workloads.make_trajectories(wl, block, stream=1000 + i) for i in range(per_batch)]
     learner, values, boot = [], [], []
-    cur = dict(learner=[], values=[], bootstrap=[])
-    for i in range(n_blocks):
-        x = workloads.make_trajectories(wl, block, stream=1000 + i)
-        d = {k: torch.from_numpy(v).cuda() for k, v in x.items()}
-        slots = binding.impact_buffer_insert(buf, d)
-        assert slots[0] == i * block and slots[-1] == (i + 1) * block - 1
-        for k in cur:
-            cur[k].append(d[k])
-        if (i + 1) % per_batch == 0:
-            learner.append(torch.cat(cur["learner"], dim=1).contiguous())
-            values.append(torch.cat(cur["values"], dim=1).contiguous())
-            boot.append(torch.cat(cur["bootstrap"], dim=0).contiguous())
-            cur = dict(learner=[], values=[], bootstrap=[])
-        del d
+    for q in range(wl.num_slots // wl.B):
+        cur = dict(learner=[], values=[], bootstrap=[])
+        for i, x in enumerate(parts):
+            d = {k: torch.from_numpy(v).cuda() for k, v in x.items()}
+            slots = binding.impact_buffer_insert(buf, d)
+            first = (q * per_batch + i) * block
+            assert slots[0] == first and slots[-1] == first + block - 1
+            for k in cur:
+                cur[k].append(d[k])
+            del d
+        learner.append(torch.cat(cur["learner"], dim=1).contiguous())
+        values.append(torch.cat(cur["values"], dim=1).contiguous())
+        boot.append(torch.cat(cur["bootstrap"], dim=0).contiguous())
     torch.cuda.synchronize()
     return learner, values, boot
 
 
-def cpu_baseline(wl, sample_B: int):
-    """Time the oracle (as it is) on a bounded sample of the workload, all host threads."""
+def cpu_baseline(wl, sample_B: int, min_wall_s: float = 1.5):
+    """Time the oracle (as it is) on a bounded sample of the workload, all host threads: whole passes
+    (sample, gather, loss with gradients) over sample_B trajectories until min_wall_s has elapsed."""
     import oracle
     from oracle.buffer import BufferOracle, bf16_bits_to_f32
 
     threads = min(oracle.max_threads(), os.cpu_count() or 1)
     x = workloads.make_trajectories(wl, sample_B, stream=77)
-    ob = BufferOracle(wl.dist, wl.T, wl.A, sample_B, wl.K, wl.storage)
+    ob = BufferOracle(wl.dist, wl.T, wl.A, sample_B, max(wl.K, 1 << 20), wl.storage)
     ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"], target=x["target"])
     cfg = oracle.config_from_hyper(wl.hyper)
+    passes = 0
     t0 = time.perf_counter()
-    slots, _ = ob.sample(sample_B)
-    g = ob.gather(slots)
-    if wl.storage == "bf16":
-        g = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in g.items()}
-    oracle.impact_loss(wl.dist, x["learner"], g["target"], g["worker"], g["actions"], g["rewards"], g["dones"],
-                       x["values"], x["bootstrap"], cfg, n_threads=threads)
-    dt = time.perf_counter() - t0
-    return dict(value=wl.T * sample_B / dt, unit="trajectory-steps/s", cores=threads, kind="oracle",
-                sample=f"{sample_B} of {wl.B} trajectories of {wl.name} (T={wl.T}), sample+gather+loss, "
-                       f"{dt:.2f} s wall")
+    while True:
+        slots, _ = ob.sample(sample_B)
+        g = ob.gather(slots)
+        if wl.storage == "bf16":
+            g = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in g.items()}
+        oracle.impact_loss(wl.dist, x["learner"], g["target"], g["worker"], g["actions"], g["rewards"], g["dones"],
+                           x["values"], x["bootstrap"], cfg, n_threads=threads)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_wall_s:
+            break
+    return dict(value=passes * wl.T * sample_B / dt, unit="trajectory-steps/s", cores=threads, kind="oracle",
+                sample=f"{passes} passes over {sample_B} of {wl.B} trajectories of {wl.name} (T={wl.T}): sample + gather + "
+                       f"loss with gradients, {dt:.2f} s wall on {threads} threads ({dt * threads:.0f} core-seconds)")
 
 
 def main() -> int:
@@ -185,7 +193,7 @@ def main() -> int:
                      "kernel_ms": kernel_ms, "kernel": "fused loss kernel + its one-workgroup reduction"},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, max(8, B // 16))
+        result["cpu_baseline"] = cpu_baseline(wl, max(8, min(B, 4096)))
     print(json.dumps(result))
     buf.close()
     return 0
