@@ -328,7 +328,7 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
     bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
-    if (slot_major && (double)num_slots * T >= 2147483648.0) fast = false;
+    if (slot_major && ((double)num_slots * T >= 2147483648.0 || (double)num_slots * T * W * es >= 4294967296.0)) fast = false;
     if (fast && slot_major) {
         // every slot's trajectory must start on a 16-byte boundary in each staged plane
         if (((size_t)T * W * es) % 16) fast = false;
