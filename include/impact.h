@@ -203,8 +203,11 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
                                     impact_stream_t stream);
 
 /* The same step with the gather fused in: the buffer-resident fields of
- * trajectory b are read in place from slot dev_slots[b] of `buf` (device int32
- * [B]; out-of-range indices are clamped and turn the losses into NaN).
+ * trajectory b are read in place from slot dev_slots[b] of `buf` (int32 [B] in
+ * device memory, or in page-locked host memory, which the kernel then reads
+ * across the bus once per tile and which must stay unchanged until the kernel
+ * has run; pageable host memory is refused with IMPACT_ERR_INVALID_ARG;
+ * out-of-range indices are clamped and turn the losses into NaN).
  * dist, T, A and the batch dtype come from the buffer's descriptor. */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
                                                 const float *learner_dist, const float *values,

@@ -364,6 +364,16 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
                                                 size_t workspace_bytes, impact_stream_t stream)
 {
     if (!buf || !dev_slots) return IMPACT_ERR_INVALID_ARG;
+    // The indices may also live in page-locked host memory: the kernel reads them once per tile, which
+    // spares the caller a copy and its launch.  Pageable host memory is not reachable from the device.
+    hipPointerAttribute_t where;
+    if (hipPointerGetAttributes(&where, dev_slots) == hipSuccess) {
+        if (where.type == hipMemoryTypeHost) dev_slots = static_cast<const int32_t *>(where.devicePointer);
+        else if (where.type == hipMemoryTypeUnregistered) return IMPACT_ERR_INVALID_ARG;
+        if (!dev_slots) return IMPACT_ERR_INVALID_ARG;
+    } else {
+        (void)hipGetLastError();
+    }
     const impact_buffer_desc_t &d = buf->desc;
     const char *base = buf->storage;
     impact_batch_t batch;

@@ -175,6 +175,29 @@ def test_fused_full_size_c5(env):
     check_against_oracle(wl, xb, got, label="fused C5 full")
 
 
+def test_slot_indices_in_host_memory(env):
+    """Page-locked host memory is read in place (same bits as a device copy); pageable memory is refused."""
+    torch, binding = env
+    wl = shape_workload(workloads.C3, B=64, num_slots=128)
+    say("case slots in host memory")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, 128, stream=3)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots = np.random.default_rng(1).permutation(128)[:64].astype(np.int32)
+    xb = workloads.take_trajectories(x, slots)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    cfg = binding.config_from_hyper(wl.hyper)
+    on_device = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot, cfg)
+    pinned = torch.from_numpy(slots).pin_memory()
+    in_place = binding.impact_loss_fwd_bwd_from_buffer(buf, pinned, learner, values, boot, cfg)
+    torch.cuda.synchronize()
+    for k in on_device:
+        np.testing.assert_array_equal(on_device[k].cpu().numpy(), in_place[k].cpu().numpy(), err_msg=k)
+    with pytest.raises(binding.ImpactError):
+        binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots.copy()), learner, values, boot, cfg)
+    buf.close()
+
+
 def test_out_of_range_slot_is_flagged_not_dereferenced(env):
     torch, binding = env
     wl = shape_workload(workloads.C1, num_slots=16)
