@@ -97,6 +97,78 @@ def cpu_baseline(wl, sample_B: int, min_wall_s: float = 1.5):
                        f"loss with gradients, {dt:.2f} s wall on {threads} threads ({dt * threads:.0f} core-seconds)")
 
 
+def branch_fractions(wl, n: int = 256):
+    """Clip and truncation fractions of the synthetic workload (oracle, small sample): the share of steps
+    whose surrogate sits on the clipped branch and whose importance weight exceeds rho_bar."""
+    import oracle
+
+    x = workloads.make_trajectories(wl, min(n, wl.B), stream=78)
+    if wl.storage == "bf16":
+        x = dict(x)
+        for k in ("target", "worker", "rewards") + (("actions",) if wl.dist == workloads.GAUSSIAN else ()):
+            x[k] = oracle.quantize_bf16(x[k])[1]
+    h = wl.hyper
+    o = oracle.impact_loss(wl.dist, x["learner"], x["target"], x["worker"], x["actions"], x["rewards"], x["dones"],
+                           x["values"], x["bootstrap"], oracle.config_from_hyper(h))
+    R, adv, lp = np.asarray(o["ratio"]), np.asarray(o["adv"]), np.asarray(o["logp3"])
+    clipped = ((adv > 0) & (R > 1 + h.eps)) | ((adv < 0) & (R < 1 - h.eps))
+    w = np.exp(lp[..., 1] - lp[..., 2])
+    return float(clipped.mean()), float((w > h.rho_bar).mean())
+
+
+def table(torch, binding, names, repeats: int = 5) -> None:
+    """Three lines per workload, as markdown on stdout: the loss on a pre-gathered time-major batch, the
+    gather alone, and the fused gather + loss.  HIP events around back-to-back calls, median of repeats."""
+    def timed(call, n_calls):
+        for i in range(max(3, n_calls // 5)):
+            call(i)
+        torch.cuda.synchronize()
+        us = []
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(n_calls):
+                call(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us.append(e0.elapsed_time(e1) * 1e3 / n_calls)
+        return float(np.median(us))
+
+    print("| workload | line | us/call | steps/s | algorithmic GB/s | % of 8 TB/s | clipped | truncated |")
+    print("|---|---|---|---|---|---|---|---|")
+    for name in names:
+        wl = workloads.WORKLOADS[name]
+        T, B, W = wl.T, wl.B, wl.W
+        buf = binding.Buffer(wl.dist, T, wl.A, wl.num_slots, wl.K, wl.storage)
+        learner, values, boot = fill_ring(torch, binding, wl, buf, min(B, 4096))
+        nq = len(learner)
+        slots = [torch.arange(q * B, (q + 1) * B, dtype=torch.int32, device="cuda") for q in range(nq)]
+        out = binding.alloc_loss_out(T, B, W)
+        ws = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, T, B, wl.A), dtype=torch.uint8, device="cuda")
+        cfg = binding.config_from_hyper(wl.hyper)
+        gathered = [binding.impact_buffer_gather(buf, slots[q]) for q in range(min(nq, 2))]
+        dst = binding.alloc_batch(buf, B)
+        n_calls = 100 if T * B < 500_000 else 20
+        t_tm = timed(lambda i: binding.impact_loss_fwd_bwd(wl.dist, learner[i % len(gathered)], values[i % len(gathered)],
+                                                           boot[i % len(gathered)], gathered[i % len(gathered)], cfg,
+                                                           out=out, workspace=ws), n_calls)
+        t_g = timed(lambda i: binding.impact_buffer_gather(buf, slots[i % nq], dst), n_calls)
+        t_f = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
+                                                                      boot[i % nq], cfg, out=out, workspace=ws), n_calls)
+        clip, trunc = branch_fractions(wl)
+        es = 4 if wl.storage == "f32" else 2
+        resident = (2 * W * es + (4 if wl.dist == workloads.CATEGORICAL else wl.A * es) + es + 1)   # buffer bytes per step
+        steps = T * B
+        for line, us, bps in (("loss, time-major batch", t_tm, algorithmic_bytes_per_step(wl)),
+                              ("gather alone", t_g, 2 * resident),
+                              ("fused gather + loss", t_f, algorithmic_bytes_per_step(wl))):
+            gbs = bps * steps / us / 1e3
+            print(f"| {wl.name} | {line} | {us:.1f} | {steps / us * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | "
+                  f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
+        buf.close()
+        del learner, values, boot, gathered, dst, out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -104,6 +176,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", action="store_true",
+                    help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -115,6 +189,9 @@ def main() -> int:
     binding.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.table:
+        table(torch, binding, sorted(workloads.WORKLOADS))
+        return 0
     wl = workloads.WORKLOADS[args.workload]
     T, B, W = wl.T, wl.B, wl.W
 
