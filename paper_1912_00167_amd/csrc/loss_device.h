@@ -1,9 +1,9 @@
 // Device-side building blocks of the loss kernels (gfx950, wave64).
 //
-// Data flow of the specialised kernels: a workgroup owns NB consecutive trajectories and walks
-// time backwards in chunks.  Each wavefront brings its time rows of a tensor into a private LDS
-// region with coalesced vector loads, after which the P lanes that share a (t, b) step read
-// that step's values from LDS.  Gradients take the reverse route.  Only the scalar scan state
+// Data flow of the specialised kernels: a tile of NB consecutive trajectories is walked backwards
+// in time in chunks.  Each wavefront brings its time rows of a tensor into a private LDS region with
+// direct global-to-LDS loads, after which the P lanes that share a (t, b) step read that step's
+// values from LDS.  Gradients take the reverse route through registers.  Only the scalar scan state
 // crosses workgroup barriers.
 #pragma once
 
@@ -159,84 +159,7 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// ---- staging: global <-> wave-private LDS region, order preserved -------------------------
-//
-// A wavefront moves RWP rows (time-major) or RWP rows of each of its NB trajectories
-// (slot-major) of a tensor at a time.  A fixed group of lanes works on one row / trajectory and
-// walks it in steps of the group's width, so that consecutive iterations differ by a constant
-// on both sides and the whole transfer needs two address registers.  All loads of a tensor are
-// issued back to back without branches: rows past the end of the trajectory are redirected to
-// the last valid row (a redundant but legal read) and never used.  t_base, b0 and rows are
-// wave-uniform.
-
-template <int BYTES> struct VecOf;
-template <> struct VecOf<16> { typedef uint4 type; };
-template <> struct VecOf<8> { typedef uint2 type; };
-
-// RWP rows of a time-major tensor [T][B][Wd]; row segment = NB*Wd elements starting at b0.
-// LDS order afterwards: [row][bl][Wd].  rows = number of valid rows (1..RWP).
-template <typename E, int Wd, int RWP>
-__device__ __forceinline__ void stage_time_major(const E *__restrict__ g, int B, int t_base, int rows, int b0,
-                                                 E *region, int lane)
-{
-    constexpr int LPR = 64 / RWP;                            // lanes per row
-    constexpr int SEGV = NB * Wd * (int)sizeof(E) / 16;      // 16-byte vectors per row segment
-    constexpr int NIT = (SEGV + LPR - 1) / LPR;
-    static_assert((NB * Wd * sizeof(E)) % 16 == 0, "row segment must be a whole number of 16-byte vectors");
-    const int r = lane / LPR, v0 = lane % LPR;
-    const char *src = (const char *)g + ((size_t)t_base * B + b0) * (Wd * sizeof(E)) +
-                      (size_t)((unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * sizeof(E))) + (unsigned)v0 * 16u);
-    char *dst = (char *)region + (r * SEGV + v0) * 16;
-    wave_lds_sync();   // every lane is done reading what the region held before
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
-        // past the end of the segment (last iteration only): re-read this lane's first vector
-        const uint4 x = *(const uint4 *)(src + (inside ? LPR * it * 16 : 0));
-        if (inside) *(uint4 *)(dst + LPR * it * 16) = x;
-    }
-    wave_lds_sync();   // the new contents are visible to every lane
-}
-
-// RWP consecutive rows of NB trajectories of a slot-major plane [slot][T][Wd].
-// LDS order afterwards: [bl][row][Wd].  slot_row0[bl] = slot * T (first row of the trajectory).
-// The last vector of a short row range may read up to 15 bytes past it; the plane's padding
-// makes that legal.
-template <typename E, int Wd, int RWP>
-__device__ __forceinline__ void stage_slot_major(const E *__restrict__ plane, int t_base, int rows,
-                                                 const int *slot_row0, E *region, int lane)
-{
-    constexpr int BYTES = RWP * Wd * (int)sizeof(E);         // per trajectory
-    constexpr int VB = (BYTES % 16 == 0) ? 16 : 8;
-    static_assert(BYTES % VB == 0, "RWP rows must be a whole number of vectors");
-    typedef typename VecOf<VB>::type vec_t;
-    constexpr int LPT = 64 / NB;                             // lanes per trajectory
-    constexpr int VPT = BYTES / VB;
-    constexpr int NIT = (VPT + LPT - 1) / LPT;
-    const int bl = lane / LPT, v0 = lane % LPT;
-    const int last_vec = (rows * Wd * (int)sizeof(E) - 1) / VB;
-    const char *src = (const char *)plane + (size_t)(slot_row0[bl] + t_base) * (Wd * sizeof(E));
-    char *dst = (char *)region + (bl * VPT + v0) * VB;
-    wave_lds_sync();   // every lane is done reading what the region held before
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const vec_t x = *(const vec_t *)(src + min(v0 + LPT * it, last_vec) * VB);
-        if (VPT % LPT == 0 || it < NIT - 1 || v0 + LPT * it < VPT) *(vec_t *)(dst + LPT * it * VB) = x;
-    }
-    wave_lds_sync();   // the new contents are visible to every lane
-}
-
-template <typename E, int Wd, int RWP, bool SLOT>
-__device__ __forceinline__ void stage(const void *g, int B, int t_base, int rows, int b0, const int *slot_row0,
-                                      void *region, int lane)
-{
-    if (SLOT)
-        stage_slot_major<E, Wd, RWP>((const E *)g, t_base, rows, slot_row0, (E *)region, lane);
-    else
-        stage_time_major<E, Wd, RWP>((const E *)g, B, t_base, rows, b0, (E *)region, lane);
-}
-
-// ---- the same transfers as direct global -> LDS loads (no registers in between) ------------
+// ---- global -> wave-private LDS region: direct loads (no registers in between) -------------
 //
 // gfx950 can write a 16- or 4-byte load straight into LDS: lane L of the instruction deposits its
 // data at (wave-uniform LDS base) + L * size.  One instruction therefore fills 64 consecutive
@@ -388,15 +311,6 @@ struct ChunkStorer {
         }
     }
 };
-
-template <int Wd, int RWP, bool FULL>
-__device__ __forceinline__ void unstage_time_major(float *__restrict__ g, int B, int t_base, int rows, int b0,
-                                                   const float *region, int lane)
-{
-    ChunkStorer<Wd, RWP> st;
-    st.plan(B, lane);
-    st.template store<FULL>(st.chunk_base(g, B, t_base, b0), region, rows, lane);
-}
 
 // ---- per-step scalar algebra shared by all kernels -----------------------------------------
 

@@ -1,0 +1,311 @@
+// The pipeline all specialised loss kernels share; the distribution-specific arithmetic comes in
+// through a Policy class (GaussPolicy in loss_gauss.hip, CatPolicy in loss_cat.hip):
+//   W, ACT, LANES          tensor widths per step and the number of lanes that share a step
+//   Kept                   registers that live from the behaviour pass to the learner pass
+//   behaviour(...)         worker and target passes at the action taken: returns pi_target / pi_worker
+//   learner(...)           ratio, surrogate, entropy, KL and the gradients, written over the learner's
+//                          distribution parameters in LDS
+#pragma once
+#include <type_traits>
+
+#include "loss_device.h"
+
+namespace impact {
+
+// Order per chunk: (wait for the chunk's data) behaviour pass, scan, (issue the next chunk's loads)
+// learner pass, gradient stores.
+//
+// NW wavefronts per workgroup.  Four (the usual tiling: the wavefronts split each chunk's rows and
+// meet in the scan) keep a small batch spread over the chip.  With one, every wavefront is a workgroup
+// of its own that walks its 8 trajectories alone, without barriers: once the batch is large enough to
+// fill the chip that way, the wavefronts of a compute unit drift apart in phase, and while some are
+// held up issuing loads into a full memory queue the others compute.
+template <class Policy, typename ST, bool SLOT, int NW>
+__global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
+{
+    constexpr int W = Policy::W;                   // elements of a distribution tensor per step
+    constexpr int ACT = Policy::ACT;               // elements of the action tensor per step; 0: one int32 index
+    constexpr int ACTR = ACT > 0 ? ACT : 1;
+    constexpr int P = Policy::LANES;               // lanes that share a step
+    constexpr int SPW = 64 / P;                    // steps per wavefront
+    constexpr int RWP = SPW / NB;                  // time rows per wavefront
+    constexpr int TCH = NW * RWP;              // time rows per chunk
+    // per-wavefront staging regions: actions, worker, target (storage dtype), learner / gradients (fp32)
+    __shared__ __align__(16) ST r_act_all[ACT > 0 ? NW : 1][ACT > 0 ? SPW * ACT : 8];
+    __shared__ __align__(16) ST r_wk_all[NW][SPW * W];
+    __shared__ __align__(16) ST r_tg_all[NW][SPW * W];
+    // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
+    // while this chunk's gradients are still being produced in the other one
+    constexpr int LDS_ONE = NW * SPW * ((ACT + 2 * W) * (int)sizeof(ST) + W * 4) + 4 * TCH * NB * 8 + 1024;
+    constexpr int NLN = (LDS_ONE + NW * SPW * W * 4 <= 64 * 1024) ? 2 : 1;
+    // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
+    // tell a read of one region from an asynchronous load still in flight into the other)
+    __shared__ __align__(16) float r_ln0_all[NW][SPW * W];
+    __shared__ __align__(16) float r_ln1_all[NLN == 2 ? NW : 1][NLN == 2 ? SPW * W : 4];
+    __shared__ double sd[2][TCH * NB];
+    __shared__ double sg[2][TCH * NB];
+    __shared__ int slot_row0[NB];
+    __shared__ float red[NW][PARTIAL_STRIDE];
+    __shared__ double exp_tbl[EXP_TABLE_SIZE];
+    // A wavefront that walks its trajectories alone (NW == 1) reads their rewards and termination flags
+    // from the buffer once, whole, instead of a few bytes per trajectory and chunk.
+    constexpr bool PRE = NW == 1 && SLOT;
+    __shared__ ST pre_r[PRE ? NB * T_PRELOAD : 1];
+    __shared__ uint8_t pre_d[PRE ? NB * T_PRELOAD : 4];
+    __shared__ int pre_a[PRE && ACT == 0 ? NB * T_PRELOAD : 1];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int step = lane / P, part = lane % P;    // step within the wavefront, share of its dimensions
+    const int rl = step / NB, bl = step % NB, tl = wave * RWP + rl;
+    const bool lead = part == 0;                   // the lane that stores the step's scalars
+    const int tile = tile_of_block(blockIdx.x, gridDim.x);
+    const int b0 = tile * NB, b = b0 + bl;
+    ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[wave], *r_tg = r_tg_all[wave];
+
+    float bad = 0.f;
+    exp64_table_init(exp_tbl, tid, 64 * NW);
+    if (SLOT && tid < NB) {
+        int s = a.slots[b0 + tid];
+        if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
+        slot_row0[tid] = s * a.T;
+    }
+    __syncthreads();
+    if (PRE) {
+        for (int i = tid; i < NB * a.T; i += 64 * NW) {
+            const int j = i / a.T, t = i - j * a.T;
+            pre_r[j * T_PRELOAD + t] = ((const ST *)a.rewards)[slot_row0[j] + t];
+            pre_d[j * T_PRELOAD + t] = a.dones[slot_row0[j] + t];
+            if (ACT == 0) pre_a[j * T_PRELOAD + t] = ((const int *)a.actions)[slot_row0[j] + t];
+        }
+        __syncthreads();
+    }
+    const int my_row0 = SLOT ? slot_row0[bl] : 0;
+    const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
+    const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
+
+    // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
+    // have the same geometry and share their lane offsets).  The plans are made for full chunks; the
+    // tail chunk, the only one that can be ragged, is fetched first with plans of its own.
+    ChunkLoader<ST, ACTR, RWP, SLOT> ld_act;
+    ChunkLoader<ST, W, RWP, SLOT> ld_dist;
+    ChunkLoader<float, W, RWP, false> ld_lrn;
+    ChunkStorer<W, RWP> st_grad;
+    auto fetch_buffer_side = [&](int c) {
+        const int t_base = c * TCH + wave * RWP;
+        if (ACT > 0) ld_act.issue(ld_act.chunk_base(a.actions, a.B, t_base, b0), r_act, lane);
+        ld_dist.issue(ld_dist.chunk_base(a.worker, a.B, t_base, b0), r_wk, lane);
+        ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
+    };
+    auto fetch_learner = [&](int c, float *region) {
+        ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, c * TCH + wave * RWP, b0), region, lane);
+    };
+
+    double carry = 0.0;
+    float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
+    const int nchunk = (a.T + TCH - 1) / TCH;
+    // The per-step scalars of a chunk are loaded one chunk ahead as well, into registers: a load issued
+    // at the start of a chunk would have to wait for the previous chunk's gradient stores, since
+    // outstanding loads and stores of a wavefront retire in issue order.
+    float nx_V = 0.f, nx_Vnext = 0.f;
+    ST nx_r = 0;
+    uint8_t nx_done = 0;
+    int nx_act = 0;                                // categorical: the action index is one more per-step scalar
+    const float Vboot = a.bootstrap[b];
+    // tail chunk: every index clamped, loads of masked steps stay in range
+    auto fetch_scalars_tail = [&](int c) {
+        const int t = c * TCH + tl;
+        const int tc = min(t, a.T - 1);
+        const size_t s_tm = (size_t)tc * a.B + b;
+        const size_t s_buf = SLOT ? (size_t)(my_row0 + tc) : s_tm;
+        nx_V = a.values[s_tm];
+        nx_Vnext = a.values[(size_t)min(t + 1, a.T - 1) * a.B + b];
+        if (!PRE) {
+            nx_r = ((const ST *)a.rewards)[s_buf];
+            nx_done = a.dones[s_buf];
+            if (ACT == 0) nx_act = ((const int *)a.actions)[s_buf];
+        }
+    };
+    // full chunks: wave-uniform chunk address plus constant lane offsets, as for the tensors above
+    const unsigned step_tm = (unsigned)rl * (unsigned)a.B + (unsigned)bl;              // in a [T][B] tensor
+    const unsigned step_buf = SLOT ? (unsigned)(my_row0 + rl) : step_tm;               // in a buffer-side one
+    auto fetch_scalars = [&](int c) {
+        const int t_base = c * TCH + wave * RWP;
+        const size_t first_tm = (size_t)t_base * a.B + b0;
+        const size_t first_buf = SLOT ? (size_t)t_base : first_tm;
+        const char *vbase = uniform_ptr(a.values + first_tm);
+        nx_V = *(const float *)(vbase + step_tm * 4u);
+        if (!PRE) {
+            nx_Vnext = *(const float *)(vbase + (step_tm + (unsigned)a.B) * 4u);       // row t + 1 exists: not the tail
+            nx_r = *(const ST *)(uniform_ptr((const ST *)a.rewards + first_buf) + step_buf * (unsigned)sizeof(ST));
+            nx_done = *(const uint8_t *)(uniform_ptr(a.dones + first_buf) + step_buf);
+            if (ACT == 0) nx_act = *(const int *)(uniform_ptr((const int *)a.actions + first_buf) + step_buf * 4u);
+        }
+    };
+    float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)
+    {
+        const int t_base = (nchunk - 1) * TCH + wave * RWP;
+        const int rows = min(RWP, a.T - t_base);
+        if (rows > 0) {
+            if (ACT > 0) ld_act.plan(a.B, rows, slot_row0, lane);
+            ld_dist.plan(a.B, rows, slot_row0, lane);
+            ld_lrn.plan(a.B, rows, slot_row0, lane);
+            fetch_buffer_side(nchunk - 1);
+            fetch_learner(nchunk - 1, r_ln0_all[wave]);
+        }
+        fetch_scalars_tail(nchunk - 1);
+        if (ACT > 0) ld_act.plan(a.B, RWP, slot_row0, lane);
+        ld_dist.plan(a.B, RWP, slot_row0, lane);
+        ld_lrn.plan(a.B, RWP, slot_row0, lane);
+        st_grad.plan(a.B, lane);
+    }
+    wait_dma_done();
+
+    // One chunk; Q = parity counted from the first chunk processed (it selects the learner region).
+    // TAIL: the chunk that holds the end of the trajectory, the only one that can be ragged, and the
+    // first to be processed.  All the others are full and their code is free of conditionals, which
+    // fixes the number of stores a chunk leaves in flight (see the wait at the top).
+    auto chunk = [&](auto parity, auto is_tail, int c) {
+        constexpr int Q = decltype(parity)::value;
+        constexpr bool TAIL = decltype(is_tail)::value;
+        float *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
+        float *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
+        const int t_base = c * TCH + wave * RWP;
+        const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
+        const int t = t_base + rl;
+        const bool valid = !TAIL || t < a.T;
+        constexpr int par = Q;
+        const size_t s_tm = (size_t)min(t, a.T - 1) * a.B + b;
+
+        // Even progress.  The instruction arbiter of a SIMD serves the oldest ready wavefront first, so of
+        // the wavefronts that share a SIMD the first to arrive runs ahead and finishes early, and the others
+        // run alone at the end.  Priority therefore steps down every few chunks (3, 2, 1, 0, then 3 again):
+        // the leader crosses into the next band first and the others outrank it until they follow.  Long
+        // bands matter: while one wavefront is clearly favoured the two drift apart in phase and fill each
+        // other's stalls, which alternating every chunk would undo.
+        set_priority_band((nchunk - 1 - c) / kPriorityBand);
+        // This chunk's loads are complete once only the previous chunk's gradient stores remain
+        // (loads and stores of a wavefront retire in issue order).
+        wait_all_but_youngest<(NLN == 2 && !TAIL) ? ChunkStorer<W, RWP>::NIT : 0>();
+        const float V = nx_V;
+        float Vnext = nx_Vnext, r = widen(nx_r);
+        bool done = nx_done != 0;
+        int action = nx_act;
+        if (PRE) {
+            const int at = bl * T_PRELOAD + min(t, a.T - 1);
+            r = widen(pre_r[at]);
+            done = pre_d[at] != 0;
+            if (ACT == 0) action = pre_a[at];
+            // V_{t+1}: the next row of this chunk, or for its last row the first row of the chunk after it
+            if (!TAIL) Vnext = __shfl(rl == 0 ? V_later : V, (lane + NB * P) & 63, 64);
+            V_later = V;
+        }
+        ScanInputs sc = {0.0, 0.0};
+        typename Policy::Kept kept;                    // what the learner pass needs again of this pass
+        double w = 0.0;                                // pi_target(a) / pi_worker(a)
+
+        if (rows > 0) {
+            const float Vn = (t + 1 < a.T) ? Vnext : Vboot;
+            wave_lds_sync();
+            w = Policy::behaviour(kept, r_act + own_step * ACTR, action, r_wk + own_step * W, r_tg + own_step * W, part,
+                                  exp_tbl, bad);
+            sc = scan_inputs(a, w, r, done, V, Vn);
+        }
+        // ---- scan: adv_t ----
+        if (lead) {
+            sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
+            sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
+        }
+        chunk_scan<TCH, NW>(sd[par], sg[par], carry, tid);
+        const double adv = sd[par][tl * NB + bl];
+        // the per-step outputs that depend on the scan alone leave now, ahead of the next chunk's loads
+        if (valid && lead) {
+            const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);        // V - vs = -adv
+            const float vs_t = (float)((double)V + adv), adv_t = (float)adv;
+            if (TAIL) {
+                a.grad_values[s_tm] = gV;
+                if (a.vs) a.vs[s_tm] = vs_t;
+                if (a.adv) a.adv[s_tm] = adv_t;
+            } else {
+                const size_t first_tm = (size_t)t_base * a.B + b0;
+                *(float *)(uniform_ptr(a.grad_values + first_tm) + step_tm * 4u) = gV;
+                if (a.vs) *(float *)(uniform_ptr(a.vs + first_tm) + step_tm * 4u) = vs_t;
+                if (a.adv) *(float *)(uniform_ptr(a.adv + first_tm) + step_tm * 4u) = adv_t;
+            }
+        }
+
+        // The buffer-side regions were consumed before the scan (and the other learner region, if there
+        // are two, when the previous chunk's gradients left it): start the next chunk's loads now, so
+        // that they fly during this chunk's learner pass.
+        wave_lds_sync();
+        wait_lds_reads_done();
+        if (c > 0) {
+            fetch_buffer_side(c - 1);
+            if (NLN == 2) fetch_learner(c - 1, r_ln_next);
+            fetch_scalars(c - 1);
+        }
+
+        if (rows > 0) {
+            // ---- learner: ratio, surrogate, entropy, KL; gradients replace the learner's rows in LDS ----
+            double s, H, KL;
+            Policy::learner(kept, r_ln + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
+            char *gbase = st_grad.chunk_base(a.grad_dist, a.B, t_base, b0);
+            if (TAIL) st_grad.template store<false>(gbase, r_ln, rows, lane);
+            else st_grad.template store<true>(gbase, r_ln, rows, lane);
+
+            if (valid && lead) {
+                sum_s += (float)s;
+                sum_v += (float)(0.5 * adv * adv);
+                sum_h += (float)H;
+                sum_k += (float)KL;
+            }
+        }
+        if (NLN == 1) {
+            // the gradients have left the learner region: start the next chunk's learner load into it
+            wave_lds_sync();
+            wait_lds_reads_done();
+            if (c > 0) fetch_learner(c - 1, r_ln_next);
+        }
+        if (TAIL) wait_dma_done();   // the number of stores just issued varies: drain them
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    chunk(P0{}, std::true_type{}, nchunk - 1);
+    for (int c = nchunk - 2; c >= 0; c -= 2) {
+        chunk(P1{}, std::false_type{}, c);
+        if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
+    }
+    store_partials<NW>(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
+}
+
+
+// Workgroup shape by batch size: single-wavefront workgroups once there are enough tiles to give every
+// SIMD two of them (and, for the fused form, the trajectory fits the preload arrays).
+inline bool single_wave_tiles(const LossArgs &a, bool slot_major)
+{
+    static const int threshold = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        return 8 * cus;
+    }();
+    return num_tiles(a.B) >= threshold && (!slot_major || a.T <= T_PRELOAD);
+}
+
+template <class Policy>
+void launch_loss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+{
+    const dim3 grid(num_tiles(a.B));
+#define IMPACT_LAUNCH(ST, SLOT, NW) hipLaunchKernelGGL((loss_static<Policy, ST, SLOT, NW>), grid, dim3(64 * NW), 0, s, a)
+    if (single_wave_tiles(a, slot_major)) {
+        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(float, true, 1); else IMPACT_LAUNCH(float, false, 1); }
+        else { if (slot_major) IMPACT_LAUNCH(bf16_t, true, 1); else IMPACT_LAUNCH(bf16_t, false, 1); }
+    } else {
+        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(float, true, NWAVES); else IMPACT_LAUNCH(float, false, NWAVES); }
+        else { if (slot_major) IMPACT_LAUNCH(bf16_t, true, NWAVES); else IMPACT_LAUNCH(bf16_t, false, NWAVES); }
+    }
+#undef IMPACT_LAUNCH
+}
+
+}  // namespace impact
