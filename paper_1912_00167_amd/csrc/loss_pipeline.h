@@ -279,33 +279,45 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
 }
 
 
-// Workgroup shape by batch size: single-wavefront workgroups once there are enough tiles to give every
-// SIMD two of them (and, for the fused form, the trajectory fits the preload arrays).
-inline bool single_wave_tiles(const LossArgs &a, bool slot_major)
+// Workgroup shape by batch size: the fewer tiles, the more wavefronts share one, so that a SIMD has
+// about two wavefronts to switch between; single-wavefront workgroups once there are 8 tiles per compute
+// unit (and, for the fused form, the trajectory fits the preload arrays).
+inline int waves_per_tile(const LossArgs &a, bool slot_major)
 {
-    static const int threshold = [] {
-        int dev = 0, cus = 0;
+    static const int cus = [] {
+        int dev = 0, n = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-        return 8 * cus;
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        return n;
     }();
-    return num_tiles(a.B) >= threshold && (!slot_major || a.T <= T_PRELOAD);
+    const int tiles = num_tiles(a.B);
+    if (tiles >= 8 * cus && (!slot_major || a.T <= T_PRELOAD)) return 1;
+    if (tiles >= 4 * cus) return 2;
+    return NWAVES;
+}
+
+template <class Policy, int NW>
+void launch_loss_static_nw(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+{
+    const dim3 grid(num_tiles(a.B)), block(64 * NW);
+    if (dtype == IMPACT_F32) {
+        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, true, NW>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_static<Policy, float, false, NW>), grid, block, 0, s, a);
+    } else {
+        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, true, NW>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_static<Policy, bf16_t, false, NW>), grid, block, 0, s, a);
+    }
 }
 
 template <class Policy>
 void launch_loss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
 {
-    const dim3 grid(num_tiles(a.B));
-#define IMPACT_LAUNCH(ST, SLOT, NW) hipLaunchKernelGGL((loss_static<Policy, ST, SLOT, NW>), grid, dim3(64 * NW), 0, s, a)
-    if (single_wave_tiles(a, slot_major)) {
-        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(float, true, 1); else IMPACT_LAUNCH(float, false, 1); }
-        else { if (slot_major) IMPACT_LAUNCH(bf16_t, true, 1); else IMPACT_LAUNCH(bf16_t, false, 1); }
-    } else {
-        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(float, true, NWAVES); else IMPACT_LAUNCH(float, false, NWAVES); }
-        else { if (slot_major) IMPACT_LAUNCH(bf16_t, true, NWAVES); else IMPACT_LAUNCH(bf16_t, false, NWAVES); }
+    switch (waves_per_tile(a, slot_major)) {
+    case 1: launch_loss_static_nw<Policy, 1>(dtype, slot_major, a, s); break;
+    case 2: launch_loss_static_nw<Policy, 2>(dtype, slot_major, a, s); break;
+    default: launch_loss_static_nw<Policy, NWAVES>(dtype, slot_major, a, s); break;
     }
-#undef IMPACT_LAUNCH
 }
 
 }  // namespace impact
