@@ -46,9 +46,63 @@ void launch_insert_plane(PlaneKind kind, const PlaneCopyArgs &a, hipStream_t s)
     }
 }
 
-// dst[t][b][k] = plane[slots[b]][t][k]: a byte copy in units of the element size.
+// dst[t][b][.] = plane[slots[b]][t][.]: a byte copy, done in words of WB bytes (the largest of 4, 2, 1
+// that divides a record).  A workgroup transposes a tile of GATHER_NB trajectories x RT rows through
+// LDS: each wavefront reads whole trajectories' pieces (RT records, contiguous in the plane), then
+// each wavefront writes whole rows (GATHER_NB records, contiguous in the batch tensor).
+constexpr int GATHER_NB = 8;
+constexpr int GATHER_TILE_BYTES = 16384;
+
+template <typename Word>
+__global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr, int RT)
+{
+    __shared__ __align__(16) unsigned char tile_bytes[GATHER_TILE_BYTES];
+    __shared__ int slot_of[GATHER_NB];
+    Word *tile = (Word *)tile_bytes;
+    constexpr int WB = (int)sizeof(Word), VW = 16 / WB;        // words per 16-byte vector
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.x * GATHER_NB, t0 = blockIdx.y * RT;
+    const int nb = min(GATHER_NB, a.B - b0), rows = min(RT, a.T - t0);
+    if (tid < GATHER_NB) slot_of[tid] = min(max(a.slots[min(b0 + tid, a.B - 1)], 0), a.num_slots - 1);
+    __syncthreads();
+    // in: a trajectory's share of the tile is one contiguous piece of the plane, copied as it lies
+    const int piece = rows * wpr;                  // words
+    const int stride = RT * wpr;                   // words between trajectories in the tile
+    const bool vec_in = (stride % VW) == 0 && (piece % VW) == 0;
+    for (int j = wave; j < nb; j += 4) {
+        const Word *src = (const Word *)a.src + ((size_t)slot_of[j] * a.T + t0) * wpr;
+        if (vec_in && ((size_t)src % 16) == 0) {
+            for (int i = lane; i < piece / VW; i += 64) ((uint4 *)(tile + j * stride))[i] = ((const uint4 *)src)[i];
+        } else {
+            for (int i = lane; i < piece; i += 64) tile[j * stride + i] = src[i];
+        }
+    }
+    __syncthreads();
+    // out: a row of the batch tensor is the tile's nb records of that time step, one after the other
+    const int row_words = nb * wpr;
+    const float inv_wpr = 1.0f / (float)wpr;
+    auto from_tile = [&](int r, int c) {           // word c of row r (c < 8 * wpr: exact in float)
+        const int j = (int)(((float)c + 0.5f) * inv_wpr), k = c - j * wpr;
+        return tile[j * stride + r * wpr + k];
+    };
+    for (int r = wave; r < rows; r += 4) {
+        Word *dst = (Word *)a.dst + ((size_t)(t0 + r) * a.B + b0) * wpr;
+        if ((row_words % VW) == 0 && ((size_t)dst % 16) == 0) {
+            for (int v = lane; v < row_words / VW; v += 64) {
+                Word w[VW];
+#pragma unroll
+                for (int q = 0; q < VW; ++q) w[q] = from_tile(r, v * VW + q);
+                ((uint4 *)dst)[v] = *(const uint4 *)w;
+            }
+        } else {
+            for (int c = lane; c < row_words; c += 64) dst[c] = from_tile(r, c);
+        }
+    }
+}
+
+// The same copy one element per thread, for records too long for the tile (thousands of actions).
 template <typename E>
-__global__ __launch_bounds__(256) void gather_plane(const GatherArgs a)
+__global__ __launch_bounds__(256) void gather_elements(const GatherArgs a)
 {
     const size_t row = (size_t)a.B * a.Wd;
     const size_t total = row * a.T;
@@ -56,21 +110,37 @@ __global__ __launch_bounds__(256) void gather_plane(const GatherArgs a)
         const int t = (int)(e / row);
         const size_t rem = e - (size_t)t * row;
         const int b = (int)(rem / a.Wd), k = (int)(rem - (size_t)b * a.Wd);
-        int slot = a.slots[b];
-        slot = min(max(slot, 0), a.num_slots - 1);
+        const int slot = min(max(a.slots[b], 0), a.num_slots - 1);
         ((E *)a.dst)[e] = ((const E *)a.src)[((size_t)slot * a.T + t) * a.Wd + k];
     }
 }
 
 void launch_gather_plane(const GatherArgs &a, hipStream_t s)
 {
+    const size_t rec = (size_t)a.Wd * a.elem_bytes;           // bytes of one record
     const size_t total = (size_t)a.T * a.B * a.Wd;
     if (total == 0) return;
-    const unsigned blocks = (unsigned)min((size_t)65536, (total + 255) / 256);
-    switch (a.elem_bytes) {
-    case 4: hipLaunchKernelGGL((gather_plane<uint32_t>), dim3(blocks), dim3(256), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((gather_plane<uint16_t>), dim3(blocks), dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((gather_plane<uint8_t>), dim3(blocks), dim3(256), 0, s, a); break;
+    // (also for the per-step scalars: a tile of 8 trajectories' rewards or flags is too little work per workgroup)
+    // ... and small planes, where the element-wise kernel's shorter dependency chain wins
+    if (GATHER_NB * rec > GATHER_TILE_BYTES || a.T > 65535 || rec < 16 || total * a.elem_bytes < ((size_t)4 << 20)) {
+        const unsigned blocks = (unsigned)min((size_t)65536, (total + 255) / 256);
+        switch (a.elem_bytes) {
+        case 4: hipLaunchKernelGGL((gather_elements<uint32_t>), dim3(blocks), dim3(256), 0, s, a); break;
+        case 2: hipLaunchKernelGGL((gather_elements<uint16_t>), dim3(blocks), dim3(256), 0, s, a); break;
+        default: hipLaunchKernelGGL((gather_elements<uint8_t>), dim3(blocks), dim3(256), 0, s, a); break;
+        }
+        return;
+    }
+    const int WB = rec % 4 == 0 ? 4 : rec % 2 == 0 ? 2 : 1;
+    const int wpr = (int)(rec / WB);
+    int RT = max(1, (int)(GATHER_TILE_BYTES / (GATHER_NB * rec)));
+    if (RT >= 16) RT &= ~15;                       // whole 16-byte vectors per trajectory piece, whatever the record size
+    RT = min(RT, a.T);
+    const dim3 grid((a.B + GATHER_NB - 1) / GATHER_NB, (a.T + RT - 1) / RT), block(256);
+    switch (WB) {
+    case 4: hipLaunchKernelGGL((gather_tiles<uint32_t>), grid, block, 0, s, a, wpr, RT); break;
+    case 2: hipLaunchKernelGGL((gather_tiles<uint16_t>), grid, block, 0, s, a, wpr, RT); break;
+    default: hipLaunchKernelGGL((gather_tiles<uint8_t>), grid, block, 0, s, a, wpr, RT); break;
     }
 }
 

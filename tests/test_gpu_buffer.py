@@ -78,6 +78,44 @@ def test_insert_sample_gather_bit_exact(env, dist, storage):
     buf.close()
 
 
+def test_gather_long_records_and_ragged_tiles(env):
+    """Records longer than the gather kernel's tile (element-wise copy) and shapes that leave partial tiles."""
+    torch, binding = env
+    for A, T, n, storage in ((700, 5, 11, "f32"), (33, 70, 19, "bf16"), (3, 257, 9, "bf16")):
+        wl = shape_workload(workloads.C1, T=T, A=A, num_slots=24, K=1, storage=storage)
+        say(f"case gather A={A} T={T} n={n} {storage}")
+        buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, storage)
+        ob = BufferOracle(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, storage)
+        _fill(torch, binding, buf, ob, wl, 24, 4)
+        perm = np.random.default_rng(A).permutation(24)[:n].astype(np.int32)
+        got = binding.impact_buffer_gather(buf, torch.from_numpy(perm).cuda())
+        torch.cuda.synchronize()
+        want = ob.gather(perm.tolist())
+        for k in ("worker", "target", "actions", "rewards", "dones"):
+            _assert_same_bytes(_bits(got[k], torch), want[k], f"{k} A={A}")
+        buf.close()
+
+
+@pytest.mark.parametrize("case", [("categorical", 18, 64, "f32"), ("gaussian", 17, 128, "bf16"), ("gaussian", 6, 100, "f32")])
+def test_gather_large_planes(env, case):
+    """Planes of several MB take the tiled gather kernel (vector and word paths, ragged batch)."""
+    torch, binding = env
+    dist, A, T, storage = case
+    base = workloads.C4 if dist == "categorical" else workloads.C5
+    wl = shape_workload(base, T=T, A=A, num_slots=1200, K=1, storage=storage)
+    say(f"case gather large {case}")
+    buf = binding.Buffer(dist, T, A, wl.num_slots, wl.K, storage)
+    ob = BufferOracle(dist, T, A, wl.num_slots, wl.K, storage)
+    _fill(torch, binding, buf, ob, wl, 1200, 6)
+    perm = np.random.default_rng(2).permutation(1200)[:1157].astype(np.int32)
+    got = binding.impact_buffer_gather(buf, torch.from_numpy(perm).cuda())
+    torch.cuda.synchronize()
+    want = ob.gather(perm.tolist())
+    for k in ("worker", "target", "actions", "rewards", "dones"):
+        _assert_same_bytes(_bits(got[k], torch), want[k], k)
+    buf.close()
+
+
 def test_gather_full_ring_large(env):
     torch, binding = env
     wl = shape_workload(workloads.C2, B=512, num_slots=1024, K=1)
