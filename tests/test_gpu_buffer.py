@@ -150,12 +150,17 @@ def _fused_case(torch, binding, wl, n_fill, Bn, flags, seed, label):
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in out.items()}
     check_against_oracle(replace(wl, B=Bn), xb, got, label=label)
-    # the unfused route (gather, then the time-major loss) must agree bit for bit with the fused one
+    # The unfused route (gather, then the time-major loss) must agree with the fused one.  The two may run
+    # different kernels (the fused specialised ones need 16-byte aligned trajectories in the planes), so the
+    # comparison is to the parity tolerance, on gradients scaled by M like the comparison with the oracle.
     g = binding.impact_buffer_gather(buf, dev_slots)
     out2 = binding.impact_loss_fwd_bwd(wl.dist, learner, values, boot, g, cfg)
     torch.cuda.synchronize()
+    M = wl.T * Bn
     for k in ("vs", "adv", "grad_values", "grad_dist", "loss5"):
-        np.testing.assert_array_equal(got[k], out2[k].cpu().numpy(), err_msg=f"{label}: fused vs gather+loss {k}")
+        scale = M if k.startswith("grad") else 1
+        np.testing.assert_allclose(got[k] * scale, out2[k].cpu().numpy() * scale, rtol=1e-5, atol=1e-6,
+                                   err_msg=f"{label}: fused vs gather+loss {k}")
     buf.close()
 
 
@@ -211,6 +216,21 @@ def test_fused_full_size_c5(env):
     buf.close()
     say("  oracle")
     check_against_oracle(wl, xb, got, label="fused C5 full")
+
+
+@pytest.mark.parametrize("case", [("C2", dict(T=22, A=6, B=16384, num_slots=16384), "f32"),
+                                  ("C2", dict(T=24, A=18, B=16384, num_slots=16384), "bf16"),
+                                  ("C2", dict(T=13, A=18, B=16384, num_slots=16384), "bf16"),
+                                  ("C3", dict(T=50, A=6, B=16384, num_slots=16384), "bf16"),
+                                  ("C4", dict(T=21, A=9, B=8192, num_slots=8192), "f32")])
+def test_fused_large_batch_short_ragged_trajectories(env, case):
+    """Batches large enough for one- and two-wavefront tiles, with trajectory lengths that leave a ragged
+    first chunk: every output element against the oracle, and the fused form against gather + loss."""
+    torch, binding = env
+    name, kw, storage = case
+    wl = shape_workload(workloads.WORKLOADS[name], storage=storage, **kw)
+    say(f"case fused large ragged {name} {kw} {storage}")
+    _fused_case(torch, binding, wl, wl.num_slots, wl.B, 0, seed=9, label=f"fused large {name} {kw}")
 
 
 def test_slot_indices_in_host_memory(env):
