@@ -26,6 +26,10 @@ sys.path.insert(0, ROOT)
 import workloads  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
+# HBM bytes per launch of the fused loss kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the
+# same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md).  Tied to the
+# kernel as profiled: to be set to None whenever the kernel changes until the counters are taken again.
+MEASURED_TRAFFIC_BYTES = {"C5": 1.0515e9}
 
 
 def algorithmic_bytes_per_step(wl) -> int:
@@ -264,7 +268,7 @@ def main() -> int:
                    "algorithmic_bytes_per_step": algorithmic_bytes_per_step(wl),
                    "loss5": [float(v) for v in loss]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel_ms": kernel_ms, "kernel": "fused loss kernel + its one-workgroup reduction"},
     }
     if not args.no_cpu_baseline:
