@@ -17,15 +17,17 @@ ATOL, RTOL = 1e-6, 1e-5       # fp32 results against the fp64 oracle: |x - y| <=
 
 
 def say(msg: str) -> None:
-    """Name the case before its GPU step: on stdout, and in a file that survives output capture."""
+    """Name the case before its GPU step: on stdout, and (if IMPACT_TEST_PROGRESS_LOG names a file) in a
+    file that survives output capture."""
     print(msg, flush=True)
     sys.stdout.flush()
-    try:
-        if os.path.isdir("gpurun_out"):
-            with open(os.path.join("gpurun_out", "gpu_test_progress.log"), "a") as f:
+    path = os.environ.get("IMPACT_TEST_PROGRESS_LOG")
+    if path:
+        try:
+            with open(path, "a") as f:
                 f.write(msg + "\n")
-    except OSError:
-        pass
+        except OSError:
+            pass
 
 
 def to_device(x, torch, device="cuda"):
