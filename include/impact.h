@@ -133,6 +133,17 @@ impact_status_t impact_buffer_destroy(impact_buffer_t *buf);
 /* Number of live slots (inserted and not yet traversed K times), or a negative status. */
 int32_t impact_buffer_num_live(impact_buffer_t *buf);
 
+/* The ring's bookkeeping (which slots are live, how often each was traversed, the
+ * two cursors: Section 3.2) as a flat host record, so that a learner can be
+ * stopped and resumed; the slots' contents live in the caller's device storage
+ * and are the caller's to save.  state_bytes: size of the record.  export: write it
+ * to host_dst (at least state_bytes).  import: replace the bookkeeping of `buf` by
+ * a record exported from a buffer with the same descriptor; INVALID_ARG (and no
+ * change) if the record is malformed or belongs to a different descriptor. */
+size_t impact_buffer_state_bytes(impact_buffer_t *buf);
+impact_status_t impact_buffer_export_state(impact_buffer_t *buf, void *host_dst, size_t bytes);
+impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *host_src, size_t bytes);
+
 /* Host bookkeeping half of an insert: choose n empty slots in ring order from the
  * write cursor (never a live one, Section 3.2), mark them live with a traversal
  * count of 0 and report them in out_slots (host, n entries).  No device work:

@@ -34,6 +34,7 @@ IMPACT_FLAG_FORCE_GENERIC = 1
 EXPORTS = [
     "impact_version", "impact_status_string",
     "impact_buffer_storage_bytes", "impact_buffer_create", "impact_buffer_destroy", "impact_buffer_num_live",
+    "impact_buffer_state_bytes", "impact_buffer_export_state", "impact_buffer_import_state",
     "impact_buffer_reserve", "impact_buffer_insert", "impact_buffer_put_target", "impact_buffer_sample",
     "impact_buffer_gather", "impact_loss_workspace_bytes", "impact_loss_fwd_bwd",
     "impact_loss_fwd_bwd_from_buffer",
@@ -91,6 +92,12 @@ def load() -> ctypes.CDLL:
     L.impact_buffer_destroy.argtypes = [vp]
     L.impact_buffer_num_live.restype = i32
     L.impact_buffer_num_live.argtypes = [vp]
+    L.impact_buffer_state_bytes.restype = sz
+    L.impact_buffer_state_bytes.argtypes = [vp]
+    L.impact_buffer_export_state.restype = ctypes.c_int
+    L.impact_buffer_export_state.argtypes = [vp, vp, sz]
+    L.impact_buffer_import_state.restype = ctypes.c_int
+    L.impact_buffer_import_state.argtypes = [vp, vp, sz]
     L.impact_buffer_reserve.restype = ctypes.c_int
     L.impact_buffer_reserve.argtypes = [vp, i32, vp]
     L.impact_buffer_insert.restype = ctypes.c_int
@@ -209,6 +216,21 @@ class Buffer:
 
 def impact_buffer_num_live(buf: Buffer) -> int:
     return int(load().impact_buffer_num_live(buf.handle))
+
+
+def impact_buffer_export_state(buf: Buffer) -> np.ndarray:
+    """The ring's bookkeeping as a byte array (the slots' contents stay in the caller's device storage)."""
+    L = load()
+    state = np.empty(int(L.impact_buffer_state_bytes(buf.handle)), dtype=np.uint8)
+    _check(L.impact_buffer_export_state(buf.handle, state.ctypes.data_as(ctypes.c_void_p), state.size),
+           "impact_buffer_export_state")
+    return state
+
+
+def impact_buffer_import_state(buf: Buffer, state: np.ndarray) -> None:
+    state = np.ascontiguousarray(state, dtype=np.uint8)
+    _check(load().impact_buffer_import_state(buf.handle, state.ctypes.data_as(ctypes.c_void_p), state.size),
+           "impact_buffer_import_state")
 
 
 def impact_buffer_reserve(buf: Buffer, n: int) -> np.ndarray:

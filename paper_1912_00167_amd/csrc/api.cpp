@@ -140,6 +140,56 @@ int32_t impact_buffer_num_live(impact_buffer_t *buf)
     return buf->live;
 }
 
+namespace {
+struct RingStateHeader {
+    uint32_t magic, version;
+    int32_t dist, T, A, num_slots, K, storage;
+    int32_t w, r, live, reserved;
+};
+constexpr uint32_t kStateMagic = 0x504d4952u, kStateVersion = 1;   // "RIMP"
+}  // namespace
+
+size_t impact_buffer_state_bytes(impact_buffer_t *buf)
+{
+    return buf ? sizeof(RingStateHeader) + (size_t)buf->desc.num_slots * sizeof(int32_t) : 0;
+}
+
+impact_status_t impact_buffer_export_state(impact_buffer_t *buf, void *host_dst, size_t bytes)
+{
+    if (!buf || !host_dst || bytes < impact_buffer_state_bytes(buf)) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(buf->mu);
+    const impact_buffer_desc_t &d = buf->desc;
+    const RingStateHeader h{kStateMagic, kStateVersion, d.dist, d.T, d.A, d.num_slots, d.K, d.storage,
+                            buf->w, buf->r, buf->live, 0};
+    std::memcpy(host_dst, &h, sizeof h);
+    std::memcpy(static_cast<char *>(host_dst) + sizeof h, buf->count.data(), buf->count.size() * sizeof(int32_t));
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *host_src, size_t bytes)
+{
+    if (!buf || !host_src || bytes < impact_buffer_state_bytes(buf)) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(buf->mu);
+    const impact_buffer_desc_t &d = buf->desc;
+    RingStateHeader h;
+    std::memcpy(&h, host_src, sizeof h);
+    if (h.magic != kStateMagic || h.version != kStateVersion || h.dist != d.dist || h.T != d.T || h.A != d.A ||
+        h.num_slots != d.num_slots || h.K != d.K || h.storage != d.storage)
+        return IMPACT_ERR_INVALID_ARG;
+    if (h.w < 0 || h.w >= d.num_slots || h.r < 0 || h.r >= d.num_slots) return IMPACT_ERR_INVALID_ARG;
+    std::vector<int32_t> count(d.num_slots);
+    std::memcpy(count.data(), static_cast<const char *>(host_src) + sizeof h, count.size() * sizeof(int32_t));
+    int32_t live = 0;
+    for (int32_t c : count) {
+        if (c < -1 || c >= d.K) return IMPACT_ERR_INVALID_ARG;
+        live += c >= 0;
+    }
+    if (live != h.live) return IMPACT_ERR_INVALID_ARG;
+    buf->count.swap(count);
+    buf->w = h.w; buf->r = h.r; buf->live = live;
+    return IMPACT_OK;
+}
+
 impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *out_slots)
 {
     if (!buf || n < 0 || (n > 0 && !out_slots)) return IMPACT_ERR_INVALID_ARG;

@@ -157,6 +157,69 @@ def test_ring_bookkeeping_is_bit_exact_with_the_oracle(lib, N, K):
         _lib_state_walk(lib, N, K, seed)
 
 
+def _walk(lib, h, ring, rng, N, steps):
+    for _ in range(steps):
+        n = int(rng.integers(0, N + 1))
+        out = np.empty(max(n, 1), np.int32)
+        if rng.random() < 0.5:
+            rc = lib.impact_buffer_reserve(h, n, out.ctypes.data_as(ctypes.c_void_p))
+            try:
+                assert out[:n].tolist() == ring.insert(n) and rc == 0
+            except BufferFull:
+                assert rc == B.IMPACT_ERR_BUFFER_FULL
+        else:
+            c = np.empty(max(n, 1), np.int32)
+            rc = lib.impact_buffer_sample(h, n, out.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p))
+            try:
+                ws, wc = ring.sample(n)
+                assert rc == 0 and out[:n].tolist() == ws and c[:n].tolist() == wc
+            except NotEnoughLive:
+                assert rc == B.IMPACT_ERR_NOT_ENOUGH_LIVE
+
+
+@pytest.mark.parametrize("N,K", [(5, 2), (64, 3)])
+def test_ring_state_survives_export_and_import(lib, N, K):
+    """Stop and resume: a ring restored from an exported record continues exactly as the oracle's ring does."""
+    rng = np.random.default_rng(N)
+    rc, h, _ = _create(lib, N=N, K=K)
+    assert rc == 0
+    ring = RingOracle(N, K)
+    _walk(lib, h, ring, rng, N, 120)
+    nbytes = lib.impact_buffer_state_bytes(h)
+    assert nbytes == 48 + 4 * N
+    state = np.zeros(nbytes, np.uint8)
+    vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    assert lib.impact_buffer_export_state(h, vp(state), nbytes - 1) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_export_state(h, vp(state), nbytes) == 0
+    lib.impact_buffer_destroy(h)
+    rc, h2, _ = _create(lib, N=N, K=K)
+    assert rc == 0 and lib.impact_buffer_num_live(h2) == 0
+    # malformed records change nothing
+    for damage in ("magic", "count", "live", "cursor", "short"):
+        bad = state.copy()
+        words = bad.view(np.int32)
+        if damage == "magic":
+            words[0] ^= 1
+        elif damage == "count":
+            words[12] = K
+        elif damage == "live":
+            words[10] += 1
+        elif damage == "cursor":
+            words[8] = N
+        size = nbytes - 4 if damage == "short" else nbytes
+        assert lib.impact_buffer_import_state(h2, vp(bad), size) == B.IMPACT_ERR_INVALID_ARG, damage
+        assert lib.impact_buffer_num_live(h2) == 0
+    # a record from a ring of another shape is refused
+    rc, h3, _ = _create(lib, N=N + 1, K=K)
+    assert lib.impact_buffer_import_state(h3, vp(state), nbytes) == B.IMPACT_ERR_INVALID_ARG
+    lib.impact_buffer_destroy(h3)
+    assert lib.impact_buffer_import_state(h2, vp(state), nbytes) == 0
+    assert lib.impact_buffer_num_live(h2) == ring.num_live()
+    _walk(lib, h2, ring, rng, N, 120)
+    assert lib.impact_buffer_num_live(h2) == ring.num_live()
+    lib.impact_buffer_destroy(h2)
+
+
 def test_ring_at_full_workload_size_matches_oracle(lib):
     # the largest ring of the workloads: 65536 slots, K = 4, batches of 16384
     N, K, Bn = 65536, 4, 16384
