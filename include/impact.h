@@ -71,7 +71,9 @@ typedef struct {
  *   eps                     PPO clip parameter (Appendix E, last bullet); +inf disables the clip
  *   vf_coeff, ent_coeff, kl_coeff   weights of the value, entropy and KL(pi_target || pi_theta)
  *                           terms (Algorithm 1, Appendix B)
- *   flags                   bit 0: use the shape-generic kernels even when a specialised one exists */
+ *   flags                   bit 0: use the shape-generic kernels even when a specialised one exists
+ *                           bit 1: surrogate ratio pi_theta / pi_worker (R_2 of Section 4.1's ablation)
+ *                                  instead of the target-worker clipped one; rho_clip is then unused */
 typedef struct {
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;
@@ -81,6 +83,7 @@ typedef struct {
 } impact_loss_config_t;
 
 #define IMPACT_FLAG_FORCE_GENERIC 1u
+#define IMPACT_FLAG_RATIO_WORKER 2u
 
 /* The buffer-resident part of a batch (what a worker sent plus the target
  * network's evaluation appended at k = 0, Algorithm 1).  All device pointers.

@@ -35,7 +35,11 @@ def build(force: bool = False) -> str:
 
 class _Cfg(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in
-                ("gamma", "lam", "rho_bar", "c_bar", "rho_clip", "eps", "vf_coeff", "ent_coeff", "kl_coeff")]
+                ("gamma", "lam", "rho_bar", "c_bar", "rho_clip", "eps", "vf_coeff", "ent_coeff", "kl_coeff")] + \
+               [("ratio_mode", ctypes.c_int)]
+
+
+RATIO_TARGET_CLIP, RATIO_WORKER = 0, 1      # Section 4.1: R_3 (R_1 when rho_clip = inf) / R_2
 
 
 _lib = None
@@ -65,6 +69,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = ctypes.c_double
             f.argtypes = [ctypes.c_double] * 4
+        L.oracle_ratio_worker.restype = ctypes.c_double
+        L.oracle_ratio_worker.argtypes = [ctypes.c_double] * 2
         L.oracle_surrogate.restype = ctypes.c_double
         L.oracle_surrogate.argtypes = [ctypes.c_double] * 3
         L.oracle_surrogate_active.restype = ctypes.c_int
@@ -85,13 +91,13 @@ def _ptr(a: Optional[np.ndarray]):
 
 
 def make_config(gamma=0.99, lam=1.0, rho_bar=1.0, c_bar=1.0, rho_clip=2.0, eps=0.2,
-                vf_coeff=1.0, ent_coeff=0.01, kl_coeff=0.0) -> _Cfg:
-    return _Cfg(gamma, lam, rho_bar, c_bar, rho_clip, eps, vf_coeff, ent_coeff, kl_coeff)
+                vf_coeff=1.0, ent_coeff=0.01, kl_coeff=0.0, ratio_mode=RATIO_TARGET_CLIP) -> _Cfg:
+    return _Cfg(gamma, lam, rho_bar, c_bar, rho_clip, eps, vf_coeff, ent_coeff, kl_coeff, int(ratio_mode))
 
 
 def config_from_hyper(h) -> _Cfg:
     return make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, h.eps,
-                       h.vf_coeff, h.ent_coeff, h.kl_coeff)
+                       h.vf_coeff, h.ent_coeff, h.kl_coeff, getattr(h, "ratio_mode", RATIO_TARGET_CLIP))
 
 
 # --- small per-step functions (used by the pin tests) -------------------------
@@ -136,6 +142,10 @@ def gauss_kl(p_target, p_theta) -> float:
 
 def ratio(lp_theta, lp_target, lp_worker, rho_clip) -> float:
     return lib().oracle_ratio(lp_theta, lp_target, lp_worker, rho_clip)
+
+
+def ratio_worker(lp_theta, lp_worker) -> float:
+    return lib().oracle_ratio_worker(lp_theta, lp_worker)
 
 
 def ratio_twin(lp_theta, lp_target, lp_worker, rho_clip) -> float:

@@ -33,7 +33,13 @@ typedef struct {
     double rho_clip;                      /* target-worker clipping rho, Section 3.1; may be +inf */
     double eps;                           /* PPO clip, Section 2.1 / Appendix E; may be +inf */
     double vf_coeff, ent_coeff, kl_coeff; /* Appendix B tables */
+    int ratio_mode;                       /* which of Section 4.1's ratios the surrogate uses, see below */
 } oracle_config;
+
+/* Section 4.1 compares three surrogate ratios.  R_3 (target-worker clipping) is the method's own and
+ * contains R_1 = pi_theta / pi_target as the case rho_clip = +inf; R_2 = pi_theta / pi_worker is the
+ * ablation that drops the target network from the ratio (the V-trace weights keep it). */
+enum { ORACLE_RATIO_TARGET_CLIP = 0, ORACLE_RATIO_WORKER = 1 };
 
 enum { ORACLE_CATEGORICAL = 0, ORACLE_GAUSSIAN = 1 };
 
@@ -199,6 +205,12 @@ double oracle_ratio_twin(double logp_theta, double logp_target, double logp_work
     return m * exp(logp_theta - logp_worker);
 }
 
+/* R_2 of Section 4.1. */
+double oracle_ratio_worker(double logp_theta, double logp_worker)
+{
+    return exp(logp_theta - logp_worker);
+}
+
 static double clip(double x, double lo, double hi)
 {
     return x < lo ? lo : (x > hi ? hi : x);
@@ -272,7 +284,8 @@ int oracle_loss_given_targets(int dist, int T, int B, int A,
                 H = oracle_gauss_entropy(zl, A);
                 KL = oracle_gauss_kl(zt, zl, A);
             }
-            double R = oracle_ratio(lp_l, lp_t, lp_w, cfg->rho_clip);
+            double R = cfg->ratio_mode == ORACLE_RATIO_WORKER ? oracle_ratio_worker(lp_l, lp_w)
+                                                              : oracle_ratio(lp_l, lp_t, lp_w, cfg->rho_clip);
             double surr = oracle_surrogate(R, adv[s], cfg->eps);
             int active = oracle_surrogate_active(R, adv[s], cfg->eps);
             double dv = values[s] - vs[s];

@@ -30,6 +30,7 @@ IMPACT_DIAG_GAUSSIAN = 1
 IMPACT_F32 = 0
 IMPACT_BF16 = 1
 IMPACT_FLAG_FORCE_GENERIC = 1
+IMPACT_FLAG_RATIO_WORKER = 2
 
 EXPORTS = [
     "impact_version", "impact_status_string",
@@ -164,6 +165,8 @@ def make_config(gamma=0.99, lam=1.0, rho_bar=1.0, c_bar=1.0, rho_clip=2.0, eps=0
 
 
 def config_from_hyper(h, flags: int = 0) -> impact_loss_config_t:
+    if getattr(h, "ratio_mode", 0) == 1:
+        flags |= IMPACT_FLAG_RATIO_WORKER
     return make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, h.eps, h.vf_coeff, h.ent_coeff,
                        h.kl_coeff, flags)
 

@@ -363,6 +363,7 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
     a.slots = dev_slots; a.num_slots = num_slots;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
     a.rho_clip = cfg->rho_clip;
+    a.ratio_worker = (cfg->flags & IMPACT_FLAG_RATIO_WORKER) ? 1 : 0;
     a.clip_lo = std::isinf(cfg->eps) ? -(double)INFINITY : 1.0 - (double)cfg->eps;
     a.clip_hi = std::isinf(cfg->eps) ? (double)INFINITY : 1.0 + (double)cfg->eps;
     a.vf_coeff = cfg->vf_coeff; a.ent_coeff = cfg->ent_coeff; a.kl_coeff = cfg->kl_coeff;

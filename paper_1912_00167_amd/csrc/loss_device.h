@@ -337,6 +337,7 @@ __device__ __forceinline__ ScanInputs scan_inputs(const LossArgs &a, double w, f
 // R = R1 * w * rho_clip (the first form of J_AIS).  rho_clip = +inf never takes the second branch.
 __device__ __forceinline__ double surrogate_ratio(const LossArgs &a, double R1, double w)
 {
+    if (a.ratio_worker) return R1 * w;     // pi_theta / pi_worker: Section 4.1's R_2
     return (w * (double)a.rho_clip >= 1.0) ? R1 : R1 * w * (double)a.rho_clip;
 }
 

@@ -99,7 +99,7 @@ def check_against_oracle(wl, x, got, hyper=None, label=""):
             kw = dict(dist=wl.dist, learner=xi["learner"], target=xi["target"], worker=xi["worker"],
                       actions=xi["actions"], values=xi["values"], vs=want["vs"])
             open_cfg = oracle.make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, math.inf, h.vf_coeff,
-                                          h.ent_coeff, h.kl_coeff)
+                                          h.ent_coeff, h.kl_coeff, getattr(h, "ratio_mode", 0))
             g_on = oracle.loss_given_targets(adv=want["adv"], cfg=open_cfg, **kw)["grad_dist"] * M
             g_off = oracle.loss_given_targets(adv=np.zeros_like(want["adv"]), cfg=cfg, **kw)["grad_dist"] * M
             for g_alt in (g_on, g_off):

@@ -59,6 +59,7 @@ HYPERS = [
     dict(lam=0.995), dict(lam=0.9, gamma=0.9), dict(rho_clip=math.inf), dict(eps=math.inf),
     dict(kl_coeff=0.7, ent_coeff=0.05), dict(rho_bar=1.5, c_bar=0.7), dict(rho_bar=0.0), dict(c_bar=0.0),
     dict(vf_coeff=0.5, ent_coeff=0.0, kl_coeff=0.0), dict(eps=0.0), dict(rho_clip=1.0),
+    dict(ratio_mode=1), dict(ratio_mode=1, kl_coeff=0.5, eps=0.1),      # the ablation's ratio pi_theta / pi_worker
 ]
 
 

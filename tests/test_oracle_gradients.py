@@ -25,7 +25,24 @@ CFGS = [
     dict(gamma=0.99, lam=1.0, rho_bar=1.0, c_bar=1.0, rho_clip=2.0, eps=0.2, vf_coeff=1.0, ent_coeff=0.01, kl_coeff=0.0),
     dict(gamma=0.95, lam=0.9, rho_bar=1.3, c_bar=0.8, rho_clip=math.inf, eps=0.4, vf_coeff=0.5, ent_coeff=0.05, kl_coeff=1.0),
     dict(gamma=0.9, lam=0.995, rho_bar=1.0, c_bar=1.0, rho_clip=1.5, eps=math.inf, vf_coeff=2.0, ent_coeff=0.0, kl_coeff=0.3),
+    # the ablation's ratio pi_theta / pi_worker
+    dict(gamma=0.99, lam=1.0, rho_bar=1.0, c_bar=1.0, rho_clip=2.0, eps=0.3, vf_coeff=1.0, ent_coeff=0.01, kl_coeff=0.5, ratio_mode=1),
 ]
+
+
+def test_worker_ratio_mode_equals_the_method_when_target_is_the_worker():
+    """With pi_target = pi_worker the target-clipped ratio is pi_theta / pi_worker for every rho_clip >= 1
+    and all importance weights are 1: the two modes must give the same step, output by output."""
+    for dist in ("categorical", "gaussian"):
+        x = _tiny(dist, 5)
+        outs = []
+        for mode, rho in ((0, 2.0), (0, 1.0), (1, 2.0)):
+            cfg = oracle.make_config(gamma=0.97, lam=0.9, rho_clip=rho, eps=0.25, kl_coeff=0.4, ratio_mode=mode)
+            outs.append(oracle.impact_loss(dist, x["learner"], x["worker"], x["worker"], x["actions"], x["rewards"],
+                                           x["dones"], x["values"], x["bootstrap"], cfg))
+        for o in outs[1:]:
+            for k in ("loss5", "grad_dist", "grad_values", "vs", "adv", "ratio"):
+                np.testing.assert_allclose(o[k], outs[0][k], rtol=1e-13, atol=1e-15, err_msg=f"{dist} {k}")
 
 
 @pytest.mark.parametrize("dist", ["categorical", "gaussian"])

@@ -38,6 +38,19 @@ def test_ratio_bounds_and_limits():
     assert oracle.ratio(math.log(0.75), math.log(0.75), math.log(0.5), 2.0) == pytest.approx(1.0, rel=1e-14)
 
 
+def test_worker_ratio_of_the_ablation():
+    """R_2 = pi_theta / pi_worker (Section 4.1): 1 when learner = worker; equal to the target-clipped
+    ratio for every rho_clip >= 1 when target = worker; R_2 = R_1 * pi_target / pi_worker in general."""
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        lp_l, lp_t, lp_w = rng.normal(size=3) * 2
+        assert oracle.ratio_worker(lp_w, lp_w) == 1.0
+        for rho in (1.0, 2.0, math.inf):
+            assert math.isclose(oracle.ratio_worker(lp_l, lp_w), oracle.ratio(lp_l, lp_w, lp_w, rho), rel_tol=1e-15)
+        assert math.isclose(oracle.ratio_worker(lp_l, lp_w), oracle.ratio(lp_l, lp_t, lp_w, math.inf) * math.exp(lp_t - lp_w),
+                            rel_tol=1e-13)
+
+
 def test_ppo_clip_cases():
     eps = 0.2
     assert oracle.surrogate(1.5, 1.0, eps) == pytest.approx(1.2)     # positive advantage, capped

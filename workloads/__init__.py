@@ -43,6 +43,7 @@ class LossHyper:
     vf_coeff: float = 1.0
     ent_coeff: float = 0.01
     kl_coeff: float = 0.0
+    ratio_mode: int = 0      # 0: target-worker clipping (R_3 of Section 4.1; R_1 when rho_clip = inf); 1: pi_theta / pi_worker (R_2)
 
 
 @dataclass(frozen=True)
