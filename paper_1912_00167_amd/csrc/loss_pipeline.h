@@ -71,12 +71,30 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         slot_row0[tid] = s * a.T;
     }
     __syncthreads();
-    if (PRE) {
-        for (int i = tid; i < NB * a.T; i += 64 * NW) {
+    if constexpr (PRE) {
+        // all loads first, then the LDS stores: one exposed memory latency instead of one per element
+        constexpr int NPRE = NB * T_PRELOAD / 64;
+        static_assert(NW == 1, "one wavefront preloads its own tile");
+        ST rv[NPRE];
+        uint8_t dv[NPRE];
+        int av[NPRE], at[NPRE];
+#pragma unroll
+        for (int q = 0; q < NPRE; ++q) {
+            const int i = min(lane + 64 * q, NB * a.T - 1);
             const int j = i / a.T, t = i - j * a.T;
-            pre_r[j * T_PRELOAD + t] = ((const ST *)a.rewards)[slot_row0[j] + t];
-            pre_d[j * T_PRELOAD + t] = a.dones[slot_row0[j] + t];
-            if (ACT == 0) pre_a[j * T_PRELOAD + t] = ((const int *)a.actions)[slot_row0[j] + t];
+            const int from = slot_row0[j] + t;
+            at[q] = j * T_PRELOAD + t;
+            rv[q] = ((const ST *)a.rewards)[from];
+            dv[q] = a.dones[from];
+            av[q] = ACT == 0 ? ((const int *)a.actions)[from] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < NPRE; ++q) {
+            if (lane + 64 * q < NB * a.T) {
+                pre_r[at[q]] = rv[q];
+                pre_d[at[q]] = dv[q];
+                if (ACT == 0) pre_a[at[q]] = av[q];
+            }
         }
         __syncthreads();
     }
