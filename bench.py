@@ -13,6 +13,7 @@ the CPU oracle's rate on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -176,10 +177,13 @@ def table(torch, binding, names, repeats: int = 5) -> None:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=16)
+    # Defaults long enough to be past the clock transient after idle: for the first ~12 ms of sustained
+    # load launches take up to 20 % longer than in the steady state that follows (kernel trace in profiles/).
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--series", metavar="FILE", help="also write the per-step kernel durations (ms, one per line) to FILE")
     ap.add_argument("--table", action="store_true",
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
     args = ap.parse_args()
@@ -208,48 +212,76 @@ def main() -> int:
     cfg = binding.config_from_hyper(wl.hyper)
     stream = torch.cuda.current_stream()
 
-    depth = 4                                      # page-locked buffers for the slot indices, read by the kernel in place
+    # Page-locked buffers for the slot indices, read by the kernel in place; the host may run this many
+    # steps ahead of the device.
+    depth = 16
     pinned = [torch.empty(B, dtype=torch.int32).pin_memory() for _ in range(depth)]
     pinned_np = [p.numpy() for p in pinned]
     counts_np = np.empty(B, dtype=np.int32)
-    copied = [None] * depth
+    # One pair of HIP events per staging buffer, around the launch on the stream it goes to; a pair is
+    # read and recorded again when its buffer comes round (a fresh pair per step would leave hundreds of
+    # unread events behind, and recording then slows down).
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(depth)]
+    in_flight = [False] * depth
     state = dict(step=0)
+    kernel_times = []
+    host_marks = []                                # host clock before and after each step's records and launch
 
-    def one_step(ev_pair=None):
+    def retire(j, keep):
+        if in_flight[j]:
+            pairs[j][1].synchronize()              # the kernel has read pinned[j]: the staging buffer is free again
+            if keep:
+                kernel_times.append(pairs[j][0].elapsed_time(pairs[j][1]))
+            in_flight[j] = False
+
+    def one_step(timed):
         i = state["step"]
         j = i % depth
-        if copied[j] is not None:
-            copied[j].synchronize()                # the staging buffer is free again
+        retire(j, timed)
         if binding.impact_buffer_num_live(buf) < B:
             binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))   # workers' refill: bookkeeping only, the data is in place
         binding.impact_buffer_sample(buf, B, pinned_np[j], counts_np)
         q = int(pinned_np[j][0]) // B              # ring order: batch q holds slots [qB, (q+1)B)
-        if ev_pair is not None:
-            ev_pair[0].record(stream)
+        host_marks.append(time.perf_counter())
+        pairs[j][0].record(stream)
         binding.impact_loss_fwd_bwd_from_buffer(buf, pinned[j], learner[q % n_batches], values[q % n_batches],
                                                 boot[q % n_batches], cfg, out=outs[i % 2], workspace=workspace,
                                                 stream=stream)
-        if ev_pair is not None:
-            ev_pair[1].record(stream)
-        ev = torch.cuda.Event()
-        ev.record(stream)
-        copied[j] = ev                             # the kernel has read pinned[j] once this has passed
+        pairs[j][1].record(stream)
+        host_marks.append(time.perf_counter())
+        in_flight[j] = True
         state["step"] = i + 1
 
+    # The interpreter's cyclic collector, set off by the small objects every call allocates, takes about
+    # 30 ms per full pass over torch's object graph: more than a hundred steps.  It stays off while steps run.
+    gc.collect()
+    gc.disable()
     for _ in range(args.warmup):
-        one_step()
+        one_step(False)
+    for j in range(depth):
+        retire(j, False)
     torch.cuda.synchronize()
 
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
-        one_step(pairs[k])
+        one_step(True)
+    issued = time.perf_counter() - t0              # host side done; the device may still be working
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    for j in range(depth):
+        retire(j, True)
+    gc.enable()
+    assert len(kernel_times) == args.steps
+    if args.series:
+        with open(args.series, "w") as f:
+            marks = host_marks[-2 * args.steps:]
+            for k, x in enumerate(kernel_times):     # kernel ms, host ms in the launch, host ms since the previous launch
+                since = (marks[2 * k] - marks[2 * k - 1]) * 1e3 if k else 0.0
+                f.write(f"{x:.4f} {(marks[2 * k + 1] - marks[2 * k]) * 1e3:.4f} {since:.4f}\n")
 
     loss = outs[(state["step"] - 1) % 2]["loss5"].cpu().numpy()
     assert np.all(np.isfinite(loss)), f"non-finite loss {loss}"
-    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    kernel_ms = float(np.mean(kernel_times))
     steps_per_call = T * B
     ms_per_step = wall * 1e3 / args.steps
     bytes_per_call = algorithmic_bytes_per_step(wl) * steps_per_call
@@ -266,10 +298,11 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: T={T} B={B} A={wl.A} {wl.dist}, {wl.storage} buffer fields, "
                                f"ring {wl.num_slots} slots K={wl.K}, fused gather+loss+grad",
                    "algorithmic_bytes_per_step": algorithmic_bytes_per_step(wl),
+                   "host_issue_ms_per_step": issued * 1e3 / args.steps,
                    "loss5": [float(v) for v in loss]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "kernel_ms": kernel_ms, "kernel": "fused loss kernel + its one-workgroup reduction"},
+                     "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, max(8, min(B, 4096)))

@@ -122,7 +122,8 @@ const char *impact_status_string(impact_status_t);
 
 /* Bytes of device memory a buffer of this shape needs (0 if the descriptor is
  * invalid).  Layout: one plane per field, slot-major, each plane starting on a
- * 256-byte boundary and followed by at least 16 bytes of padding. */
+ * 256-byte boundary and followed by at least 16 bytes of padding, then 256
+ * bytes of bookkeeping for the fused loss kernel (a completion counter). */
 size_t impact_buffer_storage_bytes(const impact_buffer_desc_t *desc);
 
 /* Create the host-side handle over caller-owned device storage of at least
@@ -222,7 +223,11 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * across the bus once per tile and which must stay unchanged until the kernel
  * has run; pageable host memory is refused with IMPACT_ERR_INVALID_ARG;
  * out-of-range indices are clamped and turn the losses into NaN).
- * dist, T, A and the batch dtype come from the buffer's descriptor. */
+ * dist, T, A and the batch dtype come from the buffer's descriptor.
+ * One launch: the workgroup that finishes last also sums the loss terms, using
+ * a counter in the buffer's storage that the first call on a handle clears (in
+ * stream order).  Calls on one handle must therefore not overlap on the device:
+ * issue them on one stream, or order them with events. */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
                                                 const float *learner_dist, const float *values,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,

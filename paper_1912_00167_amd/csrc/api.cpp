@@ -30,7 +30,7 @@ bool desc_ok(const impact_buffer_desc_t *d)
 }
 
 struct Planes {
-    size_t worker, target, actions, rewards, dones, total;
+    size_t worker, target, actions, rewards, dones, sync, total;
 };
 
 Planes plane_layout(const impact_buffer_desc_t &d)
@@ -46,6 +46,7 @@ Planes plane_layout(const impact_buffer_desc_t &d)
     off = align_up(off + (d.dist == IMPACT_CATEGORICAL ? steps * 4 : steps * d.A * es) + kPlanePad, kPlaneAlign);
     p.rewards = off; off = align_up(off + steps * es + kPlanePad, kPlaneAlign);
     p.dones = off; off = align_up(off + steps + kPlanePad, kPlaneAlign);
+    p.sync = off; off += kPlaneAlign;      // completion counter of the fused loss kernel
     p.total = off;
     return p;
 }
@@ -60,6 +61,7 @@ struct impact_buffer {
     char *storage;
     std::vector<int32_t> count;   // -1 empty, else traversals so far (0 .. K-1)
     int32_t w, r, live;
+    bool sync_zeroed = false;     // the completion counter in the storage has been cleared
     std::mutex mu;
 
     int W() const { return desc.dist == IMPACT_CATEGORICAL ? desc.A : 2 * desc.A; }
@@ -69,12 +71,15 @@ struct impact_buffer {
     void reserve(int32_t n, int32_t *out)
     {
         const int32_t N = desc.num_slots;
+        int32_t *const cnt = count.data();
+        int32_t at = w;
         for (int32_t i = 0; i < n; ++i) {
-            while (count[w] >= 0) w = (w + 1 == N) ? 0 : w + 1;
-            count[w] = 0;
-            out[i] = w;
-            w = (w + 1 == N) ? 0 : w + 1;
+            while (cnt[at] >= 0) at = (at + 1 == N) ? 0 : at + 1;
+            cnt[at] = 0;
+            out[i] = at;
+            at = (at + 1 == N) ? 0 : at + 1;
         }
+        w = at;
         live += n;
     }
 };
@@ -274,18 +279,23 @@ impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *o
     std::lock_guard<std::mutex> g(buf->mu);
     if (buf->live < B) return IMPACT_ERR_NOT_ENOUGH_LIVE;
     const int32_t N = buf->desc.num_slots, K = buf->desc.K;
-    int32_t r = buf->r;
+    // (locals: the stores through the output pointers could alias the handle's fields)
+    int32_t *const cnt = buf->count.data();
+    int32_t r = buf->r, live = buf->live;
     for (int32_t i = 0; i < B; ++i) {
-        while (buf->count[r] < 0) r = (r + 1 == N) ? 0 : r + 1;
+        while (cnt[r] < 0) r = (r + 1 == N) ? 0 : r + 1;
+        int32_t k = cnt[r];
         out_slots[i] = r;
-        out_counts[i] = buf->count[r];
-        if (++buf->count[r] == K) {
-            buf->count[r] = -1;
-            --buf->live;
+        out_counts[i] = k;
+        if (++k == K) {
+            k = -1;
+            --live;
         }
+        cnt[r] = k;
         r = (r + 1 == N) ? 0 : r + 1;
     }
     buf->r = r;
+    buf->live = live;
     return IMPACT_OK;
 }
 
@@ -336,7 +346,7 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
                                 const int32_t *dev_slots, const float *learner,
                                 const float *values, const float *bootstrap, const impact_batch_t &batch,
                                 const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
-                                size_t workspace_bytes, hipStream_t s)
+                                size_t workspace_bytes, unsigned *done_count, hipStream_t s)
 {
     if (dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) return IMPACT_ERR_INVALID_ARG;
     if (dtype != IMPACT_F32 && dtype != IMPACT_BF16) return IMPACT_ERR_INVALID_ARG;
@@ -372,6 +382,7 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
     a.grad_dist = out->grad_learner_dist; a.grad_values = out->grad_values;
     a.vs = out->vs; a.adv = out->adv;
     a.partials = static_cast<float *>(workspace);
+    a.done_count = done_count; a.loss5 = out->loss5;
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
@@ -392,8 +403,10 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
                                               : launch_loss_gauss_static(dtype, slot_major, a, s);
     }
     if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
-    ReduceArgs r{a.partials, num_tiles(B), 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
-    launch_reduce(r, s);
+    if (!done_count) {
+        ReduceArgs r{a.partials, num_tiles(B), 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
+        launch_reduce(r, s);
+    }
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
 }
 
@@ -405,7 +418,7 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
 {
     if (!batch) return IMPACT_ERR_INVALID_ARG;
     return run_loss(dist, batch_dtype, false, T, B, A, 0, nullptr, learner_dist, values, bootstrap, *batch, cfg,
-                    out, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                    out, workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream));
 }
 
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
@@ -433,8 +446,20 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
     batch.actions = base + buf->planes.actions;
     batch.rewards = base + buf->planes.rewards;
     batch.dones = reinterpret_cast<const uint8_t *>(base + buf->planes.dones);
+    // The storage holds a completion counter with which the kernel's last workgroup finishes the loss
+    // terms itself (no second launch).  The kernel leaves it at zero; before the first use it is cleared
+    // here, by a kernel in stream order (a fill that a caller's graph capture records like any other launch).
+    unsigned *done_count = reinterpret_cast<unsigned *>(buf->storage + buf->planes.sync);
+    {
+        std::lock_guard<std::mutex> g(buf->mu);
+        if (!buf->sync_zeroed) {
+            launch_zero_words(done_count, 1, static_cast<hipStream_t>(stream));
+            buf->sync_zeroed = true;
+        }
+    }
     return run_loss(d.dist, d.storage, true, d.T, B, d.A, d.num_slots, dev_slots, learner_dist, values,
-                    bootstrap, batch, cfg, out, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+                    bootstrap, batch, cfg, out, workspace, workspace_bytes, done_count,
+                    static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -144,4 +144,14 @@ void launch_gather_plane(const GatherArgs &a, hipStream_t s)
     }
 }
 
+__global__ void zero_words(unsigned *p, int n)
+{
+    for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;
+}
+
+void launch_zero_words(unsigned *p, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_words, dim3(1), dim3(64), 0, s, p, n);
+}
+
 }  // namespace impact

@@ -47,6 +47,10 @@ struct LossArgs {
     float *vs;                // [T][B] or null
     float *adv;               // [T][B] or null
     float *partials;          // [num_tiles][PARTIAL_STRIDE]
+    // completion counter for the in-kernel final reduction (zero between launches), or null: then the
+    // caller launches the reduction; loss5 is only written by the kernel in the first case
+    unsigned *done_count;
+    float *loss5;
 };
 
 struct ReduceArgs {
@@ -65,6 +69,7 @@ bool launch_loss_cat_static(int dtype, bool slot_major, const LossArgs &a, hipSt
 bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_reduce(const ReduceArgs &r, hipStream_t s);
+void launch_zero_words(unsigned *p, int n, hipStream_t s);
 
 // Buffer data movement.  A "run" is cnt consecutive slots starting at slot0 that take
 // trajectories i0 .. i0+cnt-1 of a time-major source with n trajectories.

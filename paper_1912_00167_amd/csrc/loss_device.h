@@ -377,9 +377,56 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-// Sum the per-thread loss terms over the workgroup and store them for the final reduction.
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// The five loss terms from the tiles' partial sums, by one wavefront and in an order that depends on
+// nothing but the number of tiles: lane l adds tiles l, l + 64, ... in fp64, then the lanes combine.
+// An invalid index anywhere in the batch (flagged in the fifth partial) turns all five into NaN.
+__device__ __forceinline__ void reduce_tiles(const float *partials, int num_tiles, double inv_M, float vf_coeff,
+                                             float ent_coeff, float kl_coeff, float *loss5, int lane)
+{
+    double v[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    // several tiles' loads in flight per lane; the additions keep the order of the tiles
+    constexpr int U = 8;
+    for (int i0 = lane; i0 < num_tiles; i0 += 64 * U) {
+        float4 q[U];
+        float q4[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = min(i0 + 64 * u, num_tiles - 1);
+            q[u] = *(const float4 *)(partials + (size_t)i * PARTIAL_STRIDE);
+            q4[u] = partials[(size_t)i * PARTIAL_STRIDE + 4];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + 64 * u < num_tiles) {
+                v[0] += (double)q[u].x; v[1] += (double)q[u].y; v[2] += (double)q[u].z; v[3] += (double)q[u].w;
+                v[4] += (double)q4[u];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 5; ++j) v[j] = wave_sum(v[j]);
+    if (lane == 0) {
+        const double pg = -v[0] * inv_M, vf = v[1] * inv_M, h = v[2] * inv_M, kl = v[3] * inv_M;
+        const double total = pg + (double)vf_coeff * vf - (double)ent_coeff * h + (double)kl_coeff * kl;
+        const float out[5] = {(float)total, (float)pg, (float)vf, (float)h, (float)kl};
+        const bool bad = v[4] > 0.0;
+#pragma unroll
+        for (int j = 0; j < 5; ++j) loss5[j] = bad ? __builtin_nanf("") : out[j];
+    }
+}
+
+// Sum the per-thread loss terms over the workgroup and store them for the final reduction.  With a
+// completion counter (zero before the launch) the workgroup that finishes last does that reduction
+// itself and leaves the counter at zero again; without one a separate launch follows.
 template <int NW = NWAVES>
-__device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], float *partials, int tile, int tid,
+__device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], const LossArgs &a, int tile, int tid,
                                                float s, float v, float h, float k, float bad)
 {
     const int lane = tid & 63, wave = tid >> 6;
@@ -388,12 +435,33 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], flo
         red[wave][0] = s; red[wave][1] = v; red[wave][2] = h; red[wave][3] = k; red[wave][4] = bad;
     }
     __syncthreads();
-    if (tid < 5) {
-        float t = 0.f;
+    if (wave != 0) return;
+    unsigned before = 0;
+    if (lane == 0) {
+        float *mine = a.partials + (size_t)tile * PARTIAL_STRIDE;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) t += red[w][tid];
-        partials[(size_t)tile * PARTIAL_STRIDE + tid] = t;
+        for (int j = 0; j < 5; ++j) {
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) t += red[w][j];
+            __hip_atomic_store(mine + j, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (a.done_count) {
+            // My sums must be out before my count.  A release fence would do it, but it also writes the
+            // whole cache back, gradients and all, once per workgroup; the sums are written through as
+            // device-scope stores instead, and the count waits for their acknowledgement.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            before = __hip_atomic_fetch_add(a.done_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
+    if (!a.done_count) return;
+    before = __shfl(before, 0, 64);
+    if (before != gridDim.x - 1) return;
+    // Every other tile's sums were acknowledged before its count.  Copies of those lines that this die's
+    // cache may hold from an earlier launch are dropped before they are read (acquire: invalidate only).
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    reduce_tiles(a.partials, (int)gridDim.x, a.inv_M, a.vf_coeff, a.ent_coeff, a.kl_coeff, a.loss5, lane);
+    if (lane == 0) *a.done_count = 0;
 }
 
 }  // namespace impact

@@ -159,7 +159,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             sum_k += (float)KL;
         }
     }
-    store_partials(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    store_partials(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
@@ -176,39 +176,16 @@ void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a
 #undef IMPACT_LAUNCH
 }
 
-// ---- final reduction of the per-workgroup partial sums: one workgroup, fixed order ----------
+// ---- final reduction of the per-workgroup partial sums as a launch of its own: one wavefront ----------
 
-__global__ __launch_bounds__(256) void reduce_partials(const ReduceArgs r)
+__global__ __launch_bounds__(64) void reduce_partials(const ReduceArgs r)
 {
-    __shared__ double acc[5][256];
-    const int tid = threadIdx.x;
-    double v[5] = {0, 0, 0, 0, 0};
-    for (int i = tid; i < r.num_tiles; i += 256)
-#pragma unroll
-        for (int j = 0; j < 5; ++j) v[j] += (double)r.partials[(size_t)i * PARTIAL_STRIDE + j];
-#pragma unroll
-    for (int j = 0; j < 5; ++j) acc[j][tid] = v[j];
-    __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if (tid < off)
-#pragma unroll
-            for (int j = 0; j < 5; ++j) acc[j][tid] += acc[j][tid + off];
-        __syncthreads();
-    }
-    if (tid == 0) {
-        const double pg = -acc[0][0] * r.inv_M, vf = acc[1][0] * r.inv_M;
-        const double h = acc[2][0] * r.inv_M, kl = acc[3][0] * r.inv_M;
-        double total = pg + r.vf_coeff * vf - r.ent_coeff * h + r.kl_coeff * kl;
-        float out[5] = {(float)total, (float)pg, (float)vf, (float)h, (float)kl};
-        const bool bad = acc[4][0] > 0.0;
-#pragma unroll
-        for (int j = 0; j < 5; ++j) r.loss5[j] = bad ? __builtin_nanf("") : out[j];
-    }
+    reduce_tiles(r.partials, r.num_tiles, r.inv_M, r.vf_coeff, r.ent_coeff, r.kl_coeff, r.loss5, threadIdx.x);
 }
 
 void launch_reduce(const ReduceArgs &r, hipStream_t s)
 {
-    hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, s, r);
+    hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(64), 0, s, r);
 }
 
 }  // namespace impact

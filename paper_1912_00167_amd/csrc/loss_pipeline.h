@@ -64,13 +64,38 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[wave], *r_tg = r_tg_all[wave];
 
     float bad = 0.f;
+    // the slot indices travel while the table is computed
+    int my_slot = 0;
+    if (SLOT && tid < NB) my_slot = a.slots[b0 + tid];
     exp64_table_init(exp_tbl, tid, 64 * NW);
     if (SLOT && tid < NB) {
-        int s = a.slots[b0 + tid];
+        int s = my_slot;
         if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
         slot_row0[tid] = s * a.T;
     }
     __syncthreads();
+    // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
+    // have the same geometry and share their lane offsets).  The plans are made for full chunks; the
+    // tail chunk, the only one that can be ragged, is fetched first, here, with plans of its own, so
+    // that its loads travel during the rest of the set-up.
+    ChunkLoader<ST, ACTR, RWP, SLOT> ld_act;
+    ChunkLoader<ST, W, RWP, SLOT> ld_dist;
+    ChunkLoader<float, W, RWP, false> ld_lrn;
+    auto fetch_buffer_side = [&](int c) {
+        const int t_base = c * TCH + wave * RWP;
+        if (ACT > 0) ld_act.issue(ld_act.chunk_base(a.actions, a.B, t_base, b0), r_act, lane);
+        ld_dist.issue(ld_dist.chunk_base(a.worker, a.B, t_base, b0), r_wk, lane);
+        ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
+    };
+    const int nchunk = (a.T + TCH - 1) / TCH;
+    const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
+    if (tail_rows > 0) {
+        ld_lrn.plan(a.B, tail_rows, slot_row0, lane);
+        ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
+        if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_row0, lane);
+        ld_dist.plan(a.B, tail_rows, slot_row0, lane);
+        fetch_buffer_side(nchunk - 1);
+    }
     if constexpr (PRE) {
         // all loads first, then the LDS stores: one exposed memory latency instead of one per element
         constexpr int NPRE = NB * T_PRELOAD / 64;
@@ -102,26 +127,13 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
-    // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
-    // have the same geometry and share their lane offsets).  The plans are made for full chunks; the
-    // tail chunk, the only one that can be ragged, is fetched first with plans of its own.
-    ChunkLoader<ST, ACTR, RWP, SLOT> ld_act;
-    ChunkLoader<ST, W, RWP, SLOT> ld_dist;
-    ChunkLoader<float, W, RWP, false> ld_lrn;
     ChunkStorer<W, RWP> st_grad;
-    auto fetch_buffer_side = [&](int c) {
-        const int t_base = c * TCH + wave * RWP;
-        if (ACT > 0) ld_act.issue(ld_act.chunk_base(a.actions, a.B, t_base, b0), r_act, lane);
-        ld_dist.issue(ld_dist.chunk_base(a.worker, a.B, t_base, b0), r_wk, lane);
-        ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
-    };
     auto fetch_learner = [&](int c, float *region) {
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, c * TCH + wave * RWP, b0), region, lane);
     };
 
     double carry = 0.0;
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
-    const int nchunk = (a.T + TCH - 1) / TCH;
     // The per-step scalars of a chunk are loaded one chunk ahead as well, into registers: a load issued
     // at the start of a chunk would have to wait for the previous chunk's gradient stores, since
     // outstanding loads and stores of a wavefront retire in issue order.
@@ -162,15 +174,6 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     };
     float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)
     {
-        const int t_base = (nchunk - 1) * TCH + wave * RWP;
-        const int rows = min(RWP, a.T - t_base);
-        if (rows > 0) {
-            if (ACT > 0) ld_act.plan(a.B, rows, slot_row0, lane);
-            ld_dist.plan(a.B, rows, slot_row0, lane);
-            ld_lrn.plan(a.B, rows, slot_row0, lane);
-            fetch_buffer_side(nchunk - 1);
-            fetch_learner(nchunk - 1, r_ln0_all[wave]);
-        }
         fetch_scalars_tail(nchunk - 1);
         if (ACT > 0) ld_act.plan(a.B, RWP, slot_row0, lane);
         ld_dist.plan(a.B, RWP, slot_row0, lane);
@@ -293,7 +296,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         chunk(P1{}, std::false_type{}, c);
         if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
     }
-    store_partials<NW>(red, a.partials, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    store_partials<NW>(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
 

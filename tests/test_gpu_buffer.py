@@ -184,6 +184,29 @@ def test_loss_from_buffer(env, ci, flags):
     _fused_case(torch, binding, wl, n_fill, Bn, flags, seed=ci, label=f"fused {name} {kw} flags={flags}")
 
 
+def test_fused_calls_in_a_row_on_one_handle(env):
+    """The last workgroup to finish sums the loss terms with a counter kept in the buffer's storage, which
+    every call must leave at zero: calls of different sizes (many tiles, one tile, a ragged batch on the
+    generic kernels) follow each other on one handle, each checked against the oracle."""
+    torch, binding = env
+    wl = shape_workload(workloads.C5, B=512, num_slots=1024)
+    say("case fused calls in a row")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, 1024, stream=11)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    cfg = binding.config_from_hyper(wl.hyper)
+    rng = np.random.default_rng(5)
+    for Bn in (512, 8, 264, 19, 512, 1024):
+        slots = rng.permutation(1024)[:Bn].astype(np.int32)
+        xb = workloads.take_trajectories(x, slots)
+        learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot, cfg)
+        torch.cuda.synchronize()
+        check_against_oracle(replace(wl, B=Bn), xb, {k: v.cpu().numpy() for k, v in out.items()},
+                             label=f"call with B={Bn}")
+    buf.close()
+
+
 def test_fused_full_size_c5(env):
     """The headline configuration as the benchmark launches it: a full ring of 65536 bf16 slots, 16384
     sampled trajectories of 128 steps, D = 17; every output element against the oracle.  (The ring holds
