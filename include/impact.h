@@ -122,8 +122,10 @@ const char *impact_status_string(impact_status_t);
 
 /* Bytes of device memory a buffer of this shape needs (0 if the descriptor is
  * invalid).  Layout: one plane per field, slot-major, each plane starting on a
- * 256-byte boundary and followed by at least 16 bytes of padding, then 256
- * bytes of bookkeeping for the fused loss kernel (a completion counter). */
+ * 256-byte boundary and followed by at least 16 bytes of padding; in the
+ * distribution and action planes a slot's trajectory is padded to a multiple
+ * of 16 bytes, so that the fused kernels can move whole vectors whatever T is;
+ * then 256 bytes of bookkeeping for the fused loss kernel (a completion counter). */
 size_t impact_buffer_storage_bytes(const impact_buffer_desc_t *desc);
 
 /* Create the host-side handle over caller-owned device storage of at least

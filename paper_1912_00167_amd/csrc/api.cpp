@@ -29,23 +29,30 @@ bool desc_ok(const impact_buffer_desc_t *d)
     return true;
 }
 
+// Offsets of the planes in the storage, and the distance in bytes from one slot's trajectory to the
+// next in each.  The distribution and action planes pad a trajectory to a multiple of 16 bytes, so that
+// every slot starts on a vector boundary whatever T is; rewards and flags are read element-wise.
 struct Planes {
     size_t worker, target, actions, rewards, dones, sync, total;
+    size_t stride_dist, stride_act, stride_rew, stride_done;
 };
 
 Planes plane_layout(const impact_buffer_desc_t &d)
 {
     const size_t es = d.storage == IMPACT_F32 ? 4 : 2;
     const size_t W = d.dist == IMPACT_CATEGORICAL ? (size_t)d.A : 2 * (size_t)d.A;
-    const size_t steps = (size_t)d.num_slots * d.T;
+    const size_t N = (size_t)d.num_slots, T = (size_t)d.T;
     Planes p;
+    p.stride_dist = align_up(T * W * es, 16);
+    p.stride_act = align_up(d.dist == IMPACT_CATEGORICAL ? T * 4 : T * d.A * es, 16);
+    p.stride_rew = T * es;
+    p.stride_done = T;
     size_t off = 0;
-    p.worker = off; off = align_up(off + steps * W * es + kPlanePad, kPlaneAlign);
-    p.target = off; off = align_up(off + steps * W * es + kPlanePad, kPlaneAlign);
-    p.actions = off;
-    off = align_up(off + (d.dist == IMPACT_CATEGORICAL ? steps * 4 : steps * d.A * es) + kPlanePad, kPlaneAlign);
-    p.rewards = off; off = align_up(off + steps * es + kPlanePad, kPlaneAlign);
-    p.dones = off; off = align_up(off + steps + kPlanePad, kPlaneAlign);
+    p.worker = off; off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
+    p.target = off; off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
+    p.actions = off; off = align_up(off + N * p.stride_act + kPlanePad, kPlaneAlign);
+    p.rewards = off; off = align_up(off + N * p.stride_rew + kPlanePad, kPlaneAlign);
+    p.dones = off; off = align_up(off + N * p.stride_done + kPlanePad, kPlaneAlign);
     p.sync = off; off += kPlaneAlign;      // completion counter of the fused loss kernel
     p.total = off;
     return p;
@@ -205,14 +212,14 @@ impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *
 }
 
 // Enqueue the copies of one field for a list of slots, one launch per run of consecutive slots.
-static void scatter_field(PlaneKind kind, const void *src, void *dst, int T, int n, int Wd, const int32_t *slots,
-                          hipStream_t s)
+static void scatter_field(PlaneKind kind, const void *src, void *dst, size_t slot_stride, int T, int n, int Wd,
+                          const int32_t *slots, hipStream_t s)
 {
     int i = 0;
     while (i < n) {
         int j = i + 1;
         while (j < n && slots[j] == slots[j - 1] + 1) ++j;
-        PlaneCopyArgs a{src, dst, T, n, Wd, i, slots[i], j - i};
+        PlaneCopyArgs a{src, dst, T, n, Wd, i, slots[i], j - i, slot_stride};
         launch_insert_plane(kind, a, s);
         i = j;
     }
@@ -235,15 +242,17 @@ impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impa
     const PlaneKind fk = d.storage == IMPACT_F32 ? PLANE_F32_TO_F32 : PLANE_F32_TO_BF16;
     char *base = buf->storage;
     (void)hipGetLastError();
-    scatter_field(fk, src->worker_dist, base + buf->planes.worker, d.T, n, buf->W(), out_slots, s);
+    const Planes &pl = buf->planes;
+    const size_t es = (size_t)buf->es();           // strides below: in elements of the plane's type
+    scatter_field(fk, src->worker_dist, base + pl.worker, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
     if (src->target_dist)
-        scatter_field(fk, src->target_dist, base + buf->planes.target, d.T, n, buf->W(), out_slots, s);
+        scatter_field(fk, src->target_dist, base + pl.target, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
     if (d.dist == IMPACT_CATEGORICAL)
-        scatter_field(PLANE_I32, src->actions, base + buf->planes.actions, d.T, n, 1, out_slots, s);
+        scatter_field(PLANE_I32, src->actions, base + pl.actions, pl.stride_act / 4, d.T, n, 1, out_slots, s);
     else
-        scatter_field(fk, src->actions, base + buf->planes.actions, d.T, n, d.A, out_slots, s);
-    scatter_field(fk, src->rewards, base + buf->planes.rewards, d.T, n, 1, out_slots, s);
-    scatter_field(PLANE_U8, src->dones, base + buf->planes.dones, d.T, n, 1, out_slots, s);
+        scatter_field(fk, src->actions, base + pl.actions, pl.stride_act / es, d.T, n, d.A, out_slots, s);
+    scatter_field(fk, src->rewards, base + pl.rewards, pl.stride_rew / es, d.T, n, 1, out_slots, s);
+    scatter_field(PLANE_U8, src->dones, base + pl.dones, pl.stride_done, d.T, n, 1, out_slots, s);
     if (hipGetLastError() != hipSuccess) {
         // undo the bookkeeping: the slots just reserved become empty again
         for (int32_t i = 0; i < n; ++i) buf->count[out_slots[i]] = -1;
@@ -266,8 +275,8 @@ impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const 
     const impact_buffer_desc_t &d = buf->desc;
     const PlaneKind fk = d.storage == IMPACT_F32 ? PLANE_F32_TO_F32 : PLANE_F32_TO_BF16;
     (void)hipGetLastError();
-    scatter_field(fk, target_dist, buf->storage + buf->planes.target, d.T, n, buf->W(), slots,
-                  static_cast<hipStream_t>(stream));
+    scatter_field(fk, target_dist, buf->storage + buf->planes.target, buf->planes.stride_dist / (size_t)buf->es(), d.T,
+                  n, buf->W(), slots, static_cast<hipStream_t>(stream));
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
 }
 
@@ -310,17 +319,19 @@ impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int3
     const char *base = buf->storage;
     const int es = buf->es();
     (void)hipGetLastError();
-    auto go = [&](size_t plane, const void *out, int Wd, int eb) {
+    auto go = [&](size_t plane, size_t stride_bytes, const void *out, int Wd, int eb) {
         if (!out) return;
-        GatherArgs a{base + plane, const_cast<void *>(out), dev_slots, d.T, B, Wd, d.num_slots, eb};
+        GatherArgs a{base + plane, const_cast<void *>(out), dev_slots, d.T, B, Wd, d.num_slots, eb,
+                     stride_bytes / (size_t)eb};
         launch_gather_plane(a, s);
     };
-    go(buf->planes.worker, dst->worker_dist, buf->W(), es);
-    go(buf->planes.target, dst->target_dist, buf->W(), es);
-    if (d.dist == IMPACT_CATEGORICAL) go(buf->planes.actions, dst->actions, 1, 4);
-    else go(buf->planes.actions, dst->actions, d.A, es);
-    go(buf->planes.rewards, dst->rewards, 1, es);
-    go(buf->planes.dones, dst->dones, 1, 1);
+    const Planes &pl = buf->planes;
+    go(pl.worker, pl.stride_dist, dst->worker_dist, buf->W(), es);
+    go(pl.target, pl.stride_dist, dst->target_dist, buf->W(), es);
+    if (d.dist == IMPACT_CATEGORICAL) go(pl.actions, pl.stride_act, dst->actions, 1, 4);
+    else go(pl.actions, pl.stride_act, dst->actions, d.A, es);
+    go(pl.rewards, pl.stride_rew, dst->rewards, 1, es);
+    go(pl.dones, pl.stride_done, dst->dones, 1, 1);
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
 }
 
@@ -342,12 +353,13 @@ static bool config_ok(const impact_loss_config_t *c)
     return true;
 }
 
-static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int B, int A, int num_slots,
+static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T, int B, int A, int num_slots,
                                 const int32_t *dev_slots, const float *learner,
                                 const float *values, const float *bootstrap, const impact_batch_t &batch,
                                 const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
                                 size_t workspace_bytes, unsigned *done_count, hipStream_t s)
 {
+    const bool slot_major = planes != nullptr;     // the batch fields are the buffer's planes, read in place
     if (dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) return IMPACT_ERR_INVALID_ARG;
     if (dtype != IMPACT_F32 && dtype != IMPACT_BF16) return IMPACT_ERR_INVALID_ARG;
     if (T < 1 || B < 1 || A < 1 || A > (1 << 20)) return IMPACT_ERR_INVALID_ARG;
@@ -386,15 +398,15 @@ static impact_status_t run_loss(int dist, int dtype, bool slot_major, int T, int
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
-    const int es = dtype == IMPACT_F32 ? 4 : 2;
     bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
-    if (slot_major && ((double)num_slots * T >= 2147483648.0 || (double)num_slots * T * W * es >= 4294967296.0)) fast = false;
-    if (fast && slot_major) {
-        // every slot's trajectory must start on a 16-byte boundary in each staged plane
-        if (((size_t)T * W * es) % 16) fast = false;
-        if (dist == IMPACT_DIAG_GAUSSIAN && ((size_t)T * A * es) % 16) fast = false;
+    if (slot_major) {
+        if ((double)num_slots * T >= 2147483648.0 || (double)num_slots * (double)planes->stride_dist >= 4294967296.0 ||
+            (double)num_slots * (double)planes->stride_act >= 4294967296.0)
+            fast = false;
+        a.stride_dist = planes->stride_dist;
+        a.stride_act = planes->stride_act;
     }
     (void)hipGetLastError();
     bool launched = false;
@@ -417,7 +429,7 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
                                     impact_stream_t stream)
 {
     if (!batch) return IMPACT_ERR_INVALID_ARG;
-    return run_loss(dist, batch_dtype, false, T, B, A, 0, nullptr, learner_dist, values, bootstrap, *batch, cfg,
+    return run_loss(dist, batch_dtype, nullptr, T, B, A, 0, nullptr, learner_dist, values, bootstrap, *batch, cfg,
                     out, workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream));
 }
 
@@ -457,7 +469,7 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
             buf->sync_zeroed = true;
         }
     }
-    return run_loss(d.dist, d.storage, true, d.T, B, d.A, d.num_slots, dev_slots, learner_dist, values,
+    return run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, learner_dist, values,
                     bootstrap, batch, cfg, out, workspace, workspace_bytes, done_count,
                     static_cast<hipStream_t>(stream));
 }

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void insert_plane(const PlaneCopyArgs a)
         const size_t rem = e - (size_t)s * per_slot;
         const int t = (int)(rem / a.Wd), k = (int)(rem - (size_t)t * a.Wd);
         const S v = ((const S *)a.src)[((size_t)t * a.n + a.i0 + s) * a.Wd + k];
-        ((D *)a.dst)[(size_t)(a.slot0 + s) * per_slot + rem] = convert<S, D>(v);
+        ((D *)a.dst)[(size_t)(a.slot0 + s) * a.slot_stride + rem] = convert<S, D>(v);
     }
 }
 
@@ -54,7 +54,7 @@ constexpr int GATHER_NB = 8;
 constexpr int GATHER_TILE_BYTES = 16384;
 
 template <typename Word>
-__global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr, int RT)
+__global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr, int RT, size_t slot_words)
 {
     __shared__ __align__(16) unsigned char tile_bytes[GATHER_TILE_BYTES];
     __shared__ int slot_of[GATHER_NB];
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr,
     const int stride = RT * wpr;                   // words between trajectories in the tile
     const bool vec_in = (stride % VW) == 0 && (piece % VW) == 0;
     for (int j = wave; j < nb; j += 4) {
-        const Word *src = (const Word *)a.src + ((size_t)slot_of[j] * a.T + t0) * wpr;
+        const Word *src = (const Word *)a.src + (size_t)slot_of[j] * slot_words + (size_t)t0 * wpr;
         if (vec_in && ((size_t)src % 16) == 0) {
             for (int i = lane; i < piece / VW; i += 64) ((uint4 *)(tile + j * stride))[i] = ((const uint4 *)src)[i];
         } else {
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void gather_elements(const GatherArgs a)
         const size_t rem = e - (size_t)t * row;
         const int b = (int)(rem / a.Wd), k = (int)(rem - (size_t)b * a.Wd);
         const int slot = min(max(a.slots[b], 0), a.num_slots - 1);
-        ((E *)a.dst)[e] = ((const E *)a.src)[((size_t)slot * a.T + t) * a.Wd + k];
+        ((E *)a.dst)[e] = ((const E *)a.src)[(size_t)slot * a.slot_stride + (size_t)t * a.Wd + k];
     }
 }
 
@@ -133,14 +133,15 @@ void launch_gather_plane(const GatherArgs &a, hipStream_t s)
     }
     const int WB = rec % 4 == 0 ? 4 : rec % 2 == 0 ? 2 : 1;
     const int wpr = (int)(rec / WB);
+    const size_t slot_words = a.slot_stride * a.elem_bytes / WB;   // (a stride is T records, or a multiple of 16 bytes)
     int RT = max(1, (int)(GATHER_TILE_BYTES / (GATHER_NB * rec)));
     if (RT >= 16) RT &= ~15;                       // whole 16-byte vectors per trajectory piece, whatever the record size
     RT = min(RT, a.T);
     const dim3 grid((a.B + GATHER_NB - 1) / GATHER_NB, (a.T + RT - 1) / RT), block(256);
     switch (WB) {
-    case 4: hipLaunchKernelGGL((gather_tiles<uint32_t>), grid, block, 0, s, a, wpr, RT); break;
-    case 2: hipLaunchKernelGGL((gather_tiles<uint16_t>), grid, block, 0, s, a, wpr, RT); break;
-    default: hipLaunchKernelGGL((gather_tiles<uint8_t>), grid, block, 0, s, a, wpr, RT); break;
+    case 4: hipLaunchKernelGGL((gather_tiles<uint32_t>), grid, block, 0, s, a, wpr, RT, slot_words); break;
+    case 2: hipLaunchKernelGGL((gather_tiles<uint16_t>), grid, block, 0, s, a, wpr, RT, slot_words); break;
+    default: hipLaunchKernelGGL((gather_tiles<uint8_t>), grid, block, 0, s, a, wpr, RT, slot_words); break;
     }
 }
 

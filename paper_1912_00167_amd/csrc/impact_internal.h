@@ -34,6 +34,9 @@ struct LossArgs {
     const uint8_t *dones;
     const int32_t *slots;     // device [B]; slot-major only
     int num_slots;
+    // slot-major only: bytes from one slot's trajectory to the next in the distribution planes and in
+    // the action plane (multiples of 16; rewards and flags lie T elements apart)
+    size_t stride_dist, stride_act;
     // hyper-parameters, pre-digested on the host
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;           // target-worker clipping rho; may be +inf
@@ -75,19 +78,21 @@ void launch_zero_words(unsigned *p, int n, hipStream_t s);
 // trajectories i0 .. i0+cnt-1 of a time-major source with n trajectories.
 struct PlaneCopyArgs {
     const void *src;     // time-major [T][n][Wd]
-    void *dst;           // slot-major [N][T][Wd]
+    void *dst;           // slot-major [N][T][Wd], slots slot_stride elements apart (>= T * Wd)
     int T, n, Wd;
     int i0, slot0, cnt;
+    size_t slot_stride;
 };
 enum PlaneKind { PLANE_F32_TO_F32, PLANE_F32_TO_BF16, PLANE_I32, PLANE_U8 };
 void launch_insert_plane(PlaneKind kind, const PlaneCopyArgs &a, hipStream_t s);
 
 struct GatherArgs {
-    const void *src;     // slot-major plane [N][T][Wd]
+    const void *src;     // slot-major plane [N][T][Wd], slots slot_stride elements apart
     void *dst;           // time-major [T][B][Wd]
     const int32_t *slots;
     int T, B, Wd, num_slots;
     int elem_bytes;      // 1, 2 or 4
+    size_t slot_stride;
 };
 void launch_gather_plane(const GatherArgs &a, hipStream_t s);
 

@@ -231,7 +231,8 @@ struct ChunkLoader {
 
     // rows: valid time rows (1..RWP); vectors of the missing rows re-read valid ones, so that every
     // load stays inside the tensor
-    __device__ __forceinline__ void plan(int B, int rows, const int *slot_row0, int lane)
+    // slot_byte0: where each of the tile's trajectories starts in the plane (slot-major only)
+    __device__ __forceinline__ void plan(int B, int rows, const unsigned *slot_byte0, int lane)
     {
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
@@ -239,7 +240,7 @@ struct ChunkLoader {
             if (SLOT) {
                 const int last_vec = (rows * Wd * ES - 1) / VB;
                 const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
-                offset[it] = (unsigned)slot_row0[bl] * (unsigned)(Wd * ES) + (unsigned)(min(v, last_vec) * VB);
+                offset[it] = slot_byte0[bl] + (unsigned)(min(v, last_vec) * VB);
             } else {
                 const int r = i / SEGV, v = i - r * SEGV;
                 offset[it] = (unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * ES)) + (unsigned)v * 16u;

@@ -73,9 +73,12 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         float m_l = 0.f, m_t = 0.f;
         double S_l = 1.0, S_t = 1.0;
         const float *zl = a.learner + s_tm * W;
-        const ST *zt = (const ST *)a.target + s_buf * W;
-        const ST *zw = (const ST *)a.worker + s_buf * W;
-        const ST *av = (const ST *)a.actions + s_buf * A;   // Gaussian actions
+        // in the buffer's planes a slot's trajectory starts at a multiple of the plane's stride
+        const size_t dist_at = SLOT ? (size_t)slot * a.stride_dist + (size_t)t * W * sizeof(ST) : s_tm * W * sizeof(ST);
+        const ST *zt = (const ST *)((const char *)a.target + dist_at);
+        const ST *zw = (const ST *)((const char *)a.worker + dist_at);
+        const char *act_slot = (const char *)a.actions + (SLOT ? (size_t)slot * a.stride_act : 0);
+        const ST *av = (const ST *)act_slot + (SLOT ? (size_t)t : s_tm) * A;   // Gaussian actions
 
         if (valid) {
             V = a.values[s_tm];
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             const bool done = a.dones[s_buf] != 0;
             double w, R1;
             if (DIST == IMPACT_CATEGORICAL) {
-                act = ((const int *)a.actions)[s_buf];
+                act = ((const int *)act_slot)[SLOT ? (size_t)t : s_tm];
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
                 float m_w;
                 double S_w;

@@ -44,7 +44,10 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     __shared__ __align__(16) float r_ln1_all[NLN == 2 ? NW : 1][NLN == 2 ? SPW * W : 4];
     __shared__ double sd[2][TCH * NB];
     __shared__ double sg[2][TCH * NB];
+    // where the tile's trajectories start in the buffer: in steps (rewards, flags), and in bytes of the
+    // distribution planes and of the action plane, whose slots are padded to 16 bytes
     __shared__ int slot_row0[NB];
+    __shared__ unsigned slot_dist0[NB], slot_act0[NB];
     __shared__ float red[NW][PARTIAL_STRIDE];
     __shared__ double exp_tbl[EXP_TABLE_SIZE];
     // A wavefront that walks its trajectories alone (NW == 1) reads their rewards and termination flags
@@ -72,6 +75,8 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         int s = my_slot;
         if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
         slot_row0[tid] = s * a.T;
+        slot_dist0[tid] = (unsigned)s * (unsigned)a.stride_dist;
+        slot_act0[tid] = (unsigned)s * (unsigned)a.stride_act;
     }
     __syncthreads();
     // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
@@ -90,10 +95,10 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     const int nchunk = (a.T + TCH - 1) / TCH;
     const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
     if (tail_rows > 0) {
-        ld_lrn.plan(a.B, tail_rows, slot_row0, lane);
+        ld_lrn.plan(a.B, tail_rows, nullptr, lane);
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
-        if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_row0, lane);
-        ld_dist.plan(a.B, tail_rows, slot_row0, lane);
+        if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane);
+        ld_dist.plan(a.B, tail_rows, slot_dist0, lane);
         fetch_buffer_side(nchunk - 1);
     }
     if constexpr (PRE) {
@@ -111,7 +116,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
             at[q] = j * T_PRELOAD + t;
             rv[q] = ((const ST *)a.rewards)[from];
             dv[q] = a.dones[from];
-            av[q] = ACT == 0 ? ((const int *)a.actions)[from] : 0;
+            av[q] = ACT == 0 ? *(const int *)((const char *)a.actions + slot_act0[j] + 4u * (unsigned)t) : 0;
         }
 #pragma unroll
         for (int q = 0; q < NPRE; ++q) {
@@ -124,6 +129,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         __syncthreads();
     }
     const int my_row0 = SLOT ? slot_row0[bl] : 0;
+    const unsigned my_act0 = SLOT ? slot_act0[bl] : 0u;
     const int own_step = SLOT ? (bl * RWP + rl) : step;   // position of my step in a staged buffer-side tensor
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
@@ -153,7 +159,8 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         if (!PRE) {
             nx_r = ((const ST *)a.rewards)[s_buf];
             nx_done = a.dones[s_buf];
-            if (ACT == 0) nx_act = ((const int *)a.actions)[s_buf];
+            if (ACT == 0) nx_act = SLOT ? *(const int *)((const char *)a.actions + my_act0 + 4u * (unsigned)tc)
+                                        : ((const int *)a.actions)[s_tm];
         }
     };
     // full chunks: wave-uniform chunk address plus constant lane offsets, as for the tensors above
@@ -169,15 +176,16 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
             nx_Vnext = *(const float *)(vbase + (step_tm + (unsigned)a.B) * 4u);       // row t + 1 exists: not the tail
             nx_r = *(const ST *)(uniform_ptr((const ST *)a.rewards + first_buf) + step_buf * (unsigned)sizeof(ST));
             nx_done = *(const uint8_t *)(uniform_ptr(a.dones + first_buf) + step_buf);
-            if (ACT == 0) nx_act = *(const int *)(uniform_ptr((const int *)a.actions + first_buf) + step_buf * 4u);
+            if (ACT == 0)
+                nx_act = *(const int *)(uniform_ptr((const int *)a.actions + first_buf) + (SLOT ? my_act0 + 4u * (unsigned)rl : step_tm * 4u));
         }
     };
     float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)
     {
         fetch_scalars_tail(nchunk - 1);
-        if (ACT > 0) ld_act.plan(a.B, RWP, slot_row0, lane);
-        ld_dist.plan(a.B, RWP, slot_row0, lane);
-        ld_lrn.plan(a.B, RWP, slot_row0, lane);
+        if (ACT > 0) ld_act.plan(a.B, RWP, slot_act0, lane);
+        ld_dist.plan(a.B, RWP, slot_dist0, lane);
+        ld_lrn.plan(a.B, RWP, nullptr, lane);
         st_grad.plan(a.B, lane);
     }
     wait_dma_done();

@@ -49,16 +49,18 @@ def _create(lib, dist=0, T=4, A=3, N=8, K=2, storage=0, ptr=FAKE_DEV, nbytes=Non
 
 
 def test_storage_bytes_cover_all_planes(lib):
+    up = lambda x, a: (x + a - 1) // a * a
     for dist, storage in ((0, 0), (0, 1), (1, 0), (1, 1)):
-        T, A, N = 7, 5, 11
-        d = B.impact_buffer_desc_t(dist, T, A, N, 2, storage)
-        es = 4 if storage == 0 else 2
-        W = A if dist == 0 else 2 * A
-        payload = N * T * (2 * W * es + (4 if dist == 0 else A * es) + es + 1)
-        got = lib.impact_buffer_storage_bytes(ctypes.byref(d))
-        # five planes, each padded and aligned, and one 256-byte block of kernel bookkeeping
-        assert payload + 5 * 16 + 256 <= got <= payload + 5 * (16 + 256) + 256
-        assert got % 256 == 0
+        for T, A, N in ((7, 5, 11), (50, 18, 64), (128, 17, 8)):
+            d = B.impact_buffer_desc_t(dist, T, A, N, 2, storage)
+            es = 4 if storage == 0 else 2
+            W = A if dist == 0 else 2 * A
+            # distribution and action planes: every slot padded to 16 bytes; rewards and flags packed;
+            # each plane followed by >= 16 bytes and aligned to 256; one 256-byte block of kernel bookkeeping
+            planes = [N * up(T * W * es, 16)] * 2 + [N * up(T * 4 if dist == 0 else T * A * es, 16), N * T * es, N * T]
+            want = sum(up(p + 16, 256) for p in planes) + 256
+            got = lib.impact_buffer_storage_bytes(ctypes.byref(d))
+            assert got == want, (dist, storage, T, A, N)
 
 
 def test_invalid_descriptors_and_arguments(lib):

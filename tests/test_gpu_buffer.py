@@ -169,6 +169,12 @@ FUSED = [
     ("C3", dict(B=128, num_slots=256), 256, 128),
     ("C5", dict(B=64, num_slots=128), 128, 64),                       # bf16 storage, D = 17
     ("C4", dict(B=64, num_slots=128, storage="bf16"), 128, 64),       # bf16 storage, categorical
+    # trajectory lengths whose bytes per slot are no multiple of 16: the planes pad each slot
+    ("C4", dict(T=50, B=64, num_slots=128, storage="bf16"), 128, 64),  # A = 18 bf16: 1800 bytes per slot
+    ("C2", dict(T=7, B=64, A=9, num_slots=128), 128, 64),             # A = 9 fp32: 252 bytes; actions 28
+    ("C3", dict(T=13, B=64, A=3, num_slots=128, storage="bf16"), 128, 64),   # D = 3 bf16: 156 and 78 bytes
+    ("C5", dict(T=50, B=64, num_slots=128), 128, 64),                 # D = 17 bf16: 3400 and 1700 bytes
+    ("C5", dict(T=33, B=64, num_slots=128, storage="f32"), 128, 64),  # D = 17 fp32: 4488 and 2244 bytes
     ("C2", dict(T=37, B=21, A=7, num_slots=40), 40, 21),              # generic kernels, ragged
     ("C5", dict(T=45, B=19, A=4, num_slots=32), 32, 19),              # generic kernels, bf16, ragged
 ]
