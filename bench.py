@@ -125,7 +125,7 @@ def table(torch, binding, names, repeats: int = 5) -> None:
     """Three lines per workload, as markdown on stdout: the loss on a pre-gathered time-major batch, the
     gather alone, and the fused gather + loss.  HIP events around back-to-back calls, median of repeats."""
     def timed(call, n_calls):
-        for i in range(max(3, n_calls // 5)):
+        for i in range(max(10, n_calls)):            # past the clock transient that follows idle
             call(i)
         torch.cuda.synchronize()
         us = []
@@ -153,13 +153,22 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         cfg = binding.config_from_hyper(wl.hyper)
         gathered = [binding.impact_buffer_gather(buf, slots[q]) for q in range(min(nq, 2))]
         dst = binding.alloc_batch(buf, B)
-        n_calls = 100 if T * B < 500_000 else 20
+        n_calls = 100
         t_tm = timed(lambda i: binding.impact_loss_fwd_bwd(wl.dist, learner[i % len(gathered)], values[i % len(gathered)],
                                                            boot[i % len(gathered)], gathered[i % len(gathered)], cfg,
                                                            out=out, workspace=ws), n_calls)
         t_g = timed(lambda i: binding.impact_buffer_gather(buf, slots[i % nq], dst), n_calls)
         t_f = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
                                                                       boot[i % nq], cfg, out=out, workspace=ws), n_calls)
+        # host bookkeeping of one sample call (ring walk, counts), timed on its own
+        s_np, c_np = np.empty(B, np.int32), np.empty(B, np.int32)
+        t0 = time.perf_counter()
+        n_samples = 200
+        for _ in range(n_samples):
+            if binding.impact_buffer_num_live(buf) < B:
+                binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
+            binding.impact_buffer_sample(buf, B, s_np, c_np)
+        t_s = (time.perf_counter() - t0) * 1e6 / n_samples
         clip, trunc = branch_fractions(wl)
         es = 4 if wl.storage == "f32" else 2
         resident = (2 * W * es + (4 if wl.dist == workloads.CATEGORICAL else wl.A * es) + es + 1)   # buffer bytes per step
@@ -170,6 +179,7 @@ def table(torch, binding, names, repeats: int = 5) -> None:
             gbs = bps * steps / us / 1e3
             print(f"| {wl.name} | {line} | {us:.1f} | {steps / us * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | "
                   f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
+        print(f"| {wl.name} | sample (host bookkeeping, incl. refill) | {t_s:.1f} | {steps / t_s * 1e6:.3e} | - | - | - | - |", flush=True)
         buf.close()
         del learner, values, boot, gathered, dst, out
 

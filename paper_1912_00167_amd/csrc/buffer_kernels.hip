@@ -33,10 +33,84 @@ __global__ __launch_bounds__(256) void insert_plane(const PlaneCopyArgs a)
     }
 }
 
+// The same copy for records of 16 bytes and more, as a transpose through LDS: a workgroup takes a tile
+// of INSERT_NB trajectories x RT rows.  In: each wavefront reads whole rows of the source (the tile's
+// INSERT_NB records of a time step lie one after the other).  Out: each wavefront writes whole
+// trajectories' pieces (RT records, contiguous in the plane), converted, 16 bytes per lane.
+constexpr int INSERT_NB = 8;
+constexpr int INSERT_TILE_BYTES = 32768;
+
+template <typename S, typename D>
+__global__ __launch_bounds__(256) void insert_tiles(const PlaneCopyArgs a, int RT)
+{
+    __shared__ __align__(16) S tile[INSERT_TILE_BYTES / sizeof(S)];
+    constexpr int VW = 16 / (int)sizeof(D);        // destination elements per 16-byte vector
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s0 = blockIdx.x * INSERT_NB, t0 = blockIdx.y * RT;
+    const int nb = min(INSERT_NB, a.cnt - s0), rows = min(RT, a.T - t0);
+    const int row_elems = nb * a.Wd;               // of the tile, in the source
+    const int row_pitch = INSERT_NB * a.Wd;        // in LDS
+    // several loads in flight per thread before the first LDS store (the loop bounds are run-time values,
+    // which would otherwise leave one load latency exposed per element)
+    constexpr int U = 8;
+    const S *src0 = (const S *)a.src + ((size_t)t0 * a.n + a.i0 + s0) * a.Wd;
+    const size_t src_pitch = (size_t)a.n * a.Wd;
+    const int total = rows * row_elems;
+    const float inv_row = 1.0f / (float)row_elems;
+    for (int f0 = tid; f0 < total; f0 += 256 * U) {
+        S v[U];
+        int at[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int f = min(f0 + 256 * u, total - 1);
+            const int r = (int)(((float)f + 0.5f) * inv_row), i = f - r * row_elems;
+            at[u] = r * row_pitch + i;
+            v[u] = src0[(size_t)r * src_pitch + i];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (f0 + 256 * u < total) tile[at[u]] = v[u];
+    }
+    __syncthreads();
+    const int piece = rows * a.Wd;                 // destination elements per trajectory
+    const float inv_wd = 1.0f / (float)a.Wd;
+    auto from_tile = [&](int j, int e) {           // element e of trajectory j's piece (e < 8192: exact in float)
+        const int r = (int)(((float)e + 0.5f) * inv_wd), k = e - r * a.Wd;
+        return convert<S, D>(tile[r * row_pitch + j * a.Wd + k]);
+    };
+    for (int j = wave; j < nb; j += 4) {
+        D *dst = (D *)a.dst + (size_t)(a.slot0 + s0 + j) * a.slot_stride + (size_t)t0 * a.Wd;
+        const int nvec = (((size_t)dst % 16) == 0) ? piece / VW : 0;
+        for (int v = lane; v < nvec; v += 64) {
+            D w[VW];
+#pragma unroll
+            for (int q = 0; q < VW; ++q) w[q] = from_tile(j, v * VW + q);
+            ((uint4 *)dst)[v] = *(const uint4 *)w;
+        }
+        for (int e = nvec * VW + lane; e < piece; e += 64) dst[e] = from_tile(j, e);
+    }
+}
+
+template <typename S, typename D>
+static bool launch_insert_tiles(const PlaneCopyArgs &a, hipStream_t s)
+{
+    const size_t rec = (size_t)a.Wd * sizeof(S);              // bytes of one source record
+    if (rec < 16 || a.cnt < INSERT_NB || a.T > 65535 * 8) return false;
+    int RT = (int)(INSERT_TILE_BYTES / (INSERT_NB * rec)) & ~7;   // whole 16-byte vectors per piece, whatever Wd
+    if (RT < 8) return false;
+    RT = min(RT, (a.T + 7) & ~7);
+    const dim3 grid((a.cnt + INSERT_NB - 1) / INSERT_NB, (a.T + RT - 1) / RT);
+    if (grid.y > 65535) return false;
+    hipLaunchKernelGGL((insert_tiles<S, D>), grid, dim3(256), 0, s, a, RT);
+    return true;
+}
+
 void launch_insert_plane(PlaneKind kind, const PlaneCopyArgs &a, hipStream_t s)
 {
     const size_t total = (size_t)a.T * a.Wd * a.cnt;
     if (total == 0) return;
+    if (kind == PLANE_F32_TO_F32 && launch_insert_tiles<float, float>(a, s)) return;
+    if (kind == PLANE_F32_TO_BF16 && launch_insert_tiles<float, bf16_t>(a, s)) return;
     const unsigned blocks = (unsigned)min((size_t)65536, (total + 255) / 256);
     switch (kind) {
     case PLANE_F32_TO_F32: hipLaunchKernelGGL((insert_plane<float, float>), dim3(blocks), dim3(256), 0, s, a); break;
