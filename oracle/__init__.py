@@ -190,20 +190,30 @@ def _actions(dist_code: int, actions) -> np.ndarray:
     return _f64(actions)
 
 
+def _opt64(x):
+    return None if x is None else _f64(x)
+
+
 def vtrace_targets(dist, target, worker, actions, rewards, dones, values, bootstrap, cfg: _Cfg,
-                   twin: bool = False, n_threads: int = 1):
+                   twin: bool = False, n_threads: int = 1, cached_logp=None):
+    """cached_logp: [T][B][2] = (log pi_worker(a), log pi_target(a)); target and worker are then not read
+    (pass None, with the action dimension A as `actions`' last axis or via the cached array's shape)."""
     d = _dist_code(dist)
-    target, worker = _f64(target), _f64(worker)
-    T, B, W = target.shape
-    A = W if d == CATEGORICAL else W // 2
+    target, worker, cached = _opt64(target), _opt64(worker), _opt64(cached_logp)
     act = _actions(d, actions)
+    if cached is not None:
+        T, B = cached.shape[:2]
+        A = 1 if d == CATEGORICAL else act.shape[-1]
+    else:
+        T, B, W = target.shape
+        A = W if d == CATEGORICAL else W // 2
     r, v, bs = _f64(rewards), _f64(values), _f64(bootstrap)
     dn = np.ascontiguousarray(np.asarray(dones, dtype=np.uint8))
     vs, adv = np.empty((T, B)), np.empty((T, B))
     f = lib().oracle_vtrace_targets
     f.restype = ctypes.c_int
     rc = f(ctypes.c_int(d), ctypes.c_int(T), ctypes.c_int(B), ctypes.c_int(A), _ptr(target), _ptr(worker),
-           _ptr(act), _ptr(r), _ptr(dn), _ptr(v), _ptr(bs), ctypes.byref(cfg),
+           _ptr(cached), _ptr(act), _ptr(r), _ptr(dn), _ptr(v), _ptr(bs), ctypes.byref(cfg),
            ctypes.c_int(int(twin)), ctypes.c_int(n_threads), _ptr(vs), _ptr(adv))
     if rc:
         raise RuntimeError(f"oracle_vtrace_targets failed: {rc}")
@@ -211,9 +221,9 @@ def vtrace_targets(dist, target, worker, actions, rewards, dones, values, bootst
 
 
 def loss_given_targets(dist, learner, target, worker, actions, values, vs, adv, cfg: _Cfg,
-                       want_grads: bool = True, n_threads: int = 1) -> Dict[str, np.ndarray]:
+                       want_grads: bool = True, n_threads: int = 1, cached_logp=None) -> Dict[str, np.ndarray]:
     d = _dist_code(dist)
-    learner, target, worker = _f64(learner), _f64(target), _f64(worker)
+    learner, target, worker, cached = _f64(learner), _opt64(target), _opt64(worker), _opt64(cached_logp)
     T, B, W = learner.shape
     A = W if d == CATEGORICAL else W // 2
     act = _actions(d, actions)
@@ -224,18 +234,37 @@ def loss_given_targets(dist, learner, target, worker, actions, values, vs, adv, 
     f = lib().oracle_loss_given_targets
     f.restype = ctypes.c_int
     rc = f(ctypes.c_int(d), ctypes.c_int(T), ctypes.c_int(B), ctypes.c_int(A), _ptr(learner), _ptr(target),
-           _ptr(worker), _ptr(act), _ptr(v), _ptr(vs), _ptr(adv), ctypes.byref(cfg), ctypes.c_int(n_threads),
+           _ptr(worker), _ptr(cached), _ptr(act), _ptr(v), _ptr(vs), _ptr(adv), ctypes.byref(cfg), ctypes.c_int(n_threads),
            _ptr(gd), _ptr(gv), _ptr(loss5), _ptr(R), _ptr(lp3))
     if rc:
         raise RuntimeError(f"oracle_loss_given_targets failed: {rc}")
     return dict(grad_dist=gd, grad_values=gv, loss5=loss5, ratio=R, logp3=lp3)
 
 
-def impact_loss(dist, learner, target, worker, actions, rewards, dones, values, bootstrap, cfg: _Cfg,
-                n_threads: int = 1) -> Dict[str, np.ndarray]:
-    """The whole step on fp64 copies of the inputs.  Returns grads, vs, adv, loss5, ratio, logp3."""
+def behaviour_logp(dist, target, worker, actions) -> np.ndarray:
+    """[T][B][2] fp64: (log pi_worker(a), log pi_target(a)) -- what a caching buffer keeps per step."""
     d = _dist_code(dist)
-    learner, target, worker = _f64(learner), _f64(target), _f64(worker)
+    target, worker = _f64(target), _f64(worker)
+    T, B, W = target.shape
+    A = W if d == CATEGORICAL else W // 2
+    act = _actions(d, actions)
+    out = np.empty((T, B, 2))
+    f = lib().oracle_behaviour_logp
+    f.restype = ctypes.c_int
+    rc = f(ctypes.c_int(d), ctypes.c_int(T), ctypes.c_int(B), ctypes.c_int(A), _ptr(target), _ptr(worker), _ptr(act),
+           _ptr(out))
+    if rc:
+        raise RuntimeError(f"oracle_behaviour_logp failed: {rc}")
+    return out
+
+
+def impact_loss(dist, learner, target, worker, actions, rewards, dones, values, bootstrap, cfg: _Cfg,
+                n_threads: int = 1, cached_logp=None) -> Dict[str, np.ndarray]:
+    """The whole step on fp64 copies of the inputs.  Returns grads, vs, adv, loss5, ratio, logp3.
+    With cached_logp ([T][B][2]) the worker's distribution is not read (None allowed) and the target's
+    only for the KL term (None allowed when kl_coeff = 0)."""
+    d = _dist_code(dist)
+    learner, target, worker, cached = _f64(learner), _opt64(target), _opt64(worker), _opt64(cached_logp)
     T, B, W = learner.shape
     A = W if d == CATEGORICAL else W // 2
     act = _actions(d, actions)
@@ -247,7 +276,7 @@ def impact_loss(dist, learner, target, worker, actions, rewards, dones, values, 
     f = lib().oracle_impact_loss
     f.restype = ctypes.c_int
     rc = f(ctypes.c_int(d), ctypes.c_int(T), ctypes.c_int(B), ctypes.c_int(A), _ptr(learner), _ptr(target),
-           _ptr(worker), _ptr(act), _ptr(r), _ptr(dn), _ptr(v), _ptr(bs), ctypes.byref(cfg),
+           _ptr(worker), _ptr(cached), _ptr(act), _ptr(r), _ptr(dn), _ptr(v), _ptr(bs), ctypes.byref(cfg),
            ctypes.c_int(n_threads), _ptr(gd), _ptr(gv), _ptr(vs), _ptr(adv), _ptr(loss5), _ptr(R), _ptr(lp3))
     if rc:
         raise RuntimeError(f"oracle_impact_loss failed: {rc}")

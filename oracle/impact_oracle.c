@@ -241,9 +241,16 @@ int oracle_surrogate_active(double R, double adv, double eps)
 /*       + kl_coeff mean KL(pi_target || pi_theta)                             */
 /* loss5 = {L, -mean s, mean 1/2 (V-vs)^2, mean H, mean KL}.                   */
 /* Optional outputs may be NULL.                                              */
+/* cached_logp, if given, is [T][B][2] = {log pi_worker(a), log pi_target(a)}  */
+/* as stored when the trajectory entered the buffer: V-trace weights and the   */
+/* denominator of R depend on the buffer's data alone (Sections 3.1, 3.2), so  */
+/* the two numbers can stand in for the distributions.  `worker` is then not   */
+/* read; `target` is read for the KL term only and may be NULL if kl_coeff = 0 */
+/* (KL is then reported as 0).                                                */
 /* ------------------------------------------------------------------------- */
 int oracle_loss_given_targets(int dist, int T, int B, int A,
                               const double *learner, const double *target, const double *worker,
+                              const double *cached_logp,
                               const void *actions, const double *values,
                               const double *vs, const double *adv,
                               const oracle_config *cfg, int n_threads,
@@ -253,6 +260,8 @@ int oracle_loss_given_targets(int dist, int T, int B, int A,
     const int W = (dist == ORACLE_CATEGORICAL) ? A : 2 * A;
     const double M = (double)T * (double)B;
     int status = 0;
+    if (!cached_logp && (!target || !worker)) return -3;
+    if (cached_logp && !target && cfg->kl_coeff != 0.0) return -3;
     /* per-trajectory sums of {s, 1/2 (V-vs)^2, H, KL}; added up in trajectory order afterwards */
     double *part = (double *)calloc((size_t)(B > 0 ? B : 1) * 4, sizeof(double));
     if (!part) return -1;
@@ -266,23 +275,24 @@ int oracle_loss_given_targets(int dist, int T, int B, int A,
         int bad = (!p || !pt) ? -1 : 0;
         for (int t = 0; t < T && !bad; ++t) {
             size_t s = (size_t)t * B + b;
-            const double *zl = learner + s * W, *zt = target + s * W, *zw = worker + s * W;
+            const double *zl = learner + s * W;
+            const double *zt = target ? target + s * W : NULL, *zw = cached_logp ? NULL : worker + s * W;
             double lp_l, lp_t, lp_w, H, KL;
             if (dist == ORACLE_CATEGORICAL) {
                 int a = ((const int32_t *)actions)[s];
                 if (a < 0 || a >= A) { bad = -2; break; }
                 lp_l = oracle_cat_logp(zl, A, a);
-                lp_t = oracle_cat_logp(zt, A, a);
-                lp_w = oracle_cat_logp(zw, A, a);
+                lp_t = cached_logp ? cached_logp[2 * s + 1] : oracle_cat_logp(zt, A, a);
+                lp_w = cached_logp ? cached_logp[2 * s] : oracle_cat_logp(zw, A, a);
                 H = oracle_cat_entropy(zl, A);
-                KL = oracle_cat_kl(zt, zl, A);
+                KL = zt ? oracle_cat_kl(zt, zl, A) : 0.0;
             } else {
                 const double *act = (const double *)actions + s * A;
                 lp_l = oracle_gauss_logp(zl, A, act);
-                lp_t = oracle_gauss_logp(zt, A, act);
-                lp_w = oracle_gauss_logp(zw, A, act);
+                lp_t = cached_logp ? cached_logp[2 * s + 1] : oracle_gauss_logp(zt, A, act);
+                lp_w = cached_logp ? cached_logp[2 * s] : oracle_gauss_logp(zw, A, act);
                 H = oracle_gauss_entropy(zl, A);
-                KL = oracle_gauss_kl(zt, zl, A);
+                KL = zt ? oracle_gauss_kl(zt, zl, A) : 0.0;
             }
             double R = cfg->ratio_mode == ORACLE_RATIO_WORKER ? oracle_ratio_worker(lp_l, lp_w)
                                                               : oracle_ratio(lp_l, lp_t, lp_w, cfg->rho_clip);
@@ -303,26 +313,29 @@ int oracle_loss_given_targets(int dist, int T, int B, int A,
             double *gd = grad_dist + s * W;
             if (dist == ORACLE_CATEGORICAL) {
                 int a = ((const int32_t *)actions)[s];
-                double lse_l = oracle_cat_logsumexp(zl, A), lse_t = oracle_cat_logsumexp(zt, A);
-                for (int k = 0; k < A; ++k) { p[k] = exp(zl[k] - lse_l); pt[k] = exp(zt[k] - lse_t); }
+                double lse_l = oracle_cat_logsumexp(zl, A), lse_t = zt ? oracle_cat_logsumexp(zt, A) : 0.0;
+                for (int k = 0; k < A; ++k) { p[k] = exp(zl[k] - lse_l); pt[k] = zt ? exp(zt[k] - lse_t) : 0.0; }
                 for (int k = 0; k < A; ++k) {
                     double dlogp = ((k == a) ? 1.0 : 0.0) - p[k];          /* d logp(a) / d z_k */
                     double dH = -p[k] * ((zl[k] - lse_l) + H);              /* d H / d z_k */
-                    double dKL = p[k] - pt[k];                              /* d KL / d z_k */
+                    double dKL = zt ? p[k] - pt[k] : 0.0;                   /* d KL / d z_k */
                     gd[k] = g * dlogp - cfg->ent_coeff / M * dH + cfg->kl_coeff / M * dKL;
                 }
             } else {
                 const double *act = (const double *)actions + s * A;
                 for (int d = 0; d < A; ++d) {
-                    double sl = exp(zl[A + d]), st = exp(zt[A + d]);
+                    double sl = exp(zl[A + d]);
                     double diff = act[d] - zl[d];
                     double zed = diff / sl;
-                    double dm = zl[d] - zt[d];
                     double dlogp_dmu = diff / (sl * sl);
                     double dlogp_dls = zed * zed - 1.0;
                     double dH_dls = 1.0;
-                    double dKL_dmu = dm / (sl * sl);
-                    double dKL_dls = 1.0 - (st * st + dm * dm) / (sl * sl);
+                    double dKL_dmu = 0.0, dKL_dls = 0.0;
+                    if (zt) {
+                        double st = exp(zt[A + d]), dm = zl[d] - zt[d];
+                        dKL_dmu = dm / (sl * sl);
+                        dKL_dls = 1.0 - (st * st + dm * dm) / (sl * sl);
+                    }
                     gd[d] = g * dlogp_dmu + cfg->kl_coeff / M * dKL_dmu;
                     gd[A + d] = g * dlogp_dls - cfg->ent_coeff / M * dH_dls + cfg->kl_coeff / M * dKL_dls;
                 }
@@ -356,7 +369,8 @@ int oracle_loss_given_targets(int dist, int T, int B, int A,
 /* the scan; the loss sums stay sequential.                                   */
 /* ------------------------------------------------------------------------- */
 int oracle_vtrace_targets(int dist, int T, int B, int A,
-                          const double *target, const double *worker, const void *actions,
+                          const double *target, const double *worker, const double *cached_logp,
+                          const void *actions,
                           const double *rewards, const uint8_t *dones,
                           const double *values, const double *bootstrap,
                           const oracle_config *cfg, int use_sum_twin, int n_threads,
@@ -383,7 +397,10 @@ int oracle_vtrace_targets(int dist, int T, int B, int A,
         double *lpt = buf, *lpw = buf + T, *r = buf + 2 * T, *v = buf + 3 * T, *o_vs = buf + 4 * T, *o_adv = buf + 5 * T;
         for (int t = 0; t < T; ++t) {
             size_t s = (size_t)t * B + b;
-            if (dist == ORACLE_CATEGORICAL) {
+            if (cached_logp) {
+                lpw[t] = cached_logp[2 * s];
+                lpt[t] = cached_logp[2 * s + 1];
+            } else if (dist == ORACLE_CATEGORICAL) {
                 int a = ((const int32_t *)actions)[s];
                 if (a < 0 || a >= A) { bad_action = 1; a = 0; }
                 lpt[t] = oracle_cat_logp(target + s * W, A, a);
@@ -414,18 +431,40 @@ int oracle_vtrace_targets(int dist, int T, int B, int A,
     return status;
 }
 
+/* What the buffer stores per step in place of the worker's distribution when it caches log-probabilities:
+ * out[t][b] = {log pi_worker(a_tb), log pi_target(a_tb)}, the action being the one stored. */
+int oracle_behaviour_logp(int dist, int T, int B, int A, const double *target, const double *worker,
+                          const void *actions, double *out)
+{
+    const int W = (dist == ORACLE_CATEGORICAL) ? A : 2 * A;
+    for (size_t s = 0; s < (size_t)T * B; ++s) {
+        if (dist == ORACLE_CATEGORICAL) {
+            int a = ((const int32_t *)actions)[s];
+            if (a < 0 || a >= A) return -2;
+            out[2 * s] = oracle_cat_logp(worker + s * W, A, a);
+            out[2 * s + 1] = oracle_cat_logp(target + s * W, A, a);
+        } else {
+            const double *act = (const double *)actions + s * A;
+            out[2 * s] = oracle_gauss_logp(worker + s * W, A, act);
+            out[2 * s + 1] = oracle_gauss_logp(target + s * W, A, act);
+        }
+    }
+    return 0;
+}
+
 int oracle_impact_loss(int dist, int T, int B, int A,
                        const double *learner, const double *target, const double *worker,
+                       const double *cached_logp,
                        const void *actions, const double *rewards, const uint8_t *dones,
                        const double *values, const double *bootstrap,
                        const oracle_config *cfg, int n_threads,
                        double *grad_dist, double *grad_values, double *vs, double *adv,
                        double *loss5, double *ratio_out, double *logp3_out)
 {
-    int rc = oracle_vtrace_targets(dist, T, B, A, target, worker, actions, rewards, dones,
+    int rc = oracle_vtrace_targets(dist, T, B, A, target, worker, cached_logp, actions, rewards, dones,
                                    values, bootstrap, cfg, 0, n_threads, vs, adv);
     if (rc) return rc;
-    return oracle_loss_given_targets(dist, T, B, A, learner, target, worker, actions, values,
+    return oracle_loss_given_targets(dist, T, B, A, learner, target, worker, cached_logp, actions, values,
                                      vs, adv, cfg, n_threads, grad_dist, grad_values, loss5, ratio_out, logp3_out);
 }
 
