@@ -61,7 +61,18 @@ typedef struct {
     int32_t num_slots;  /* N, >= 1 */
     int32_t K;          /* replay limit, >= 1 */
     int32_t storage;    /* impact_dtype_t of the float fields kept in the buffer */
+    uint32_t flags;     /* IMPACT_BUFFER_* below; 0 = keep both distributions */
 } impact_buffer_desc_t;
+
+/* The V-trace weights pi_target/pi_worker (Section 3.1, with Section 2.2) and the denominator of
+ * the surrogate ratio, max(pi_target, pi_worker / rho) (J_AIS, Section 3.1), depend on the buffer's
+ * own data only, through two numbers per step: log pi_worker(a) and log pi_target(a).
+ *   IMPACT_BUFFER_CACHE_LOGP      keep those two (fp64, computed when the worker's and the target's
+ *                                 distributions are handed over) and not the worker's distribution
+ *   IMPACT_BUFFER_NO_TARGET_DIST  with CACHE_LOGP: do not keep the target's distribution either;
+ *                                 the loss then has no KL term (kl_coeff must be 0) */
+#define IMPACT_BUFFER_CACHE_LOGP 1u
+#define IMPACT_BUFFER_NO_TARGET_DIST 2u
 
 /* Hyper-parameters of the loss.
  *   gamma, lambda           discount and GAE-lambda of the V-trace advantage (Section 3.1)
@@ -91,6 +102,9 @@ typedef struct {
  *   actions                   int32 [T][B] (categorical) or float [T][B][D] (Gaussian)
  *   rewards                   [T][B]
  *   dones                     uint8 [T][B]; 1 = the transition at t ended the episode
+ *   logp                      double [T][B][2] = {log pi_worker(a), log pi_target(a)}, or NULL.
+ *                             Where given it replaces worker_dist (then unused, may be NULL), and
+ *                             target_dist is needed for the KL term only (NULL allowed if kl_coeff = 0).
  * Float fields have the dtype named next to the struct in each call. */
 typedef struct {
     const void *worker_dist;
@@ -98,6 +112,7 @@ typedef struct {
     const void *actions;
     const void *rewards;
     const uint8_t *dones;
+    const double *logp;
 } impact_batch_t;
 
 /* Outputs of the loss, all device, all fp32, written in full by each call.
@@ -163,13 +178,16 @@ impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *
  *   out_slots  host, n entries: the slots chosen, in ring order from the write cursor,
  *              skipping live slots (a live trajectory is never overwritten, Section 3.2)
  * Values are converted to the storage dtype (bf16: round-to-nearest-even).
+ * A buffer that caches log-probabilities computes them here, in fp64, from the fp32
+ * distributions as given and the action as stored (src->logp is not read).
  * All-or-nothing: BUFFER_FULL if fewer than n slots are empty.  n = 0 is a no-op. */
 impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impact_batch_t *src_f32,
                                      int32_t *out_slots, impact_stream_t stream);
 
 /* "If k = 0, evaluate B on target, append target output to B" (Algorithm 1):
  * write fp32 target-network outputs [T][n][W] (device) into the target_dist
- * plane of the n slots listed in the host array `slots` (each in [0, num_slots)). */
+ * plane of the n slots listed in the host array `slots` (each in [0, num_slots));
+ * a buffer that caches log-probabilities also computes log pi_target(a) from them. */
 impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const int32_t *slots,
                                          const float *target_dist, impact_stream_t stream);
 
@@ -185,7 +203,9 @@ impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *o
  * buffer's storage dtype (a byte copy, no conversion).  dev_slots: device int32
  * [B], each in [0, num_slots) -- an out-of-range index is clamped into range,
  * never dereferenced out of bounds.  dst pointers are device outputs; a NULL
- * field is skipped. */
+ * field is skipped, and so is a field the buffer does not keep (worker_dist, and
+ * possibly target_dist, of a buffer that caches log-probabilities; logp of one
+ * that does not). */
 impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
                                      const impact_batch_t *dst, impact_stream_t stream);
 

@@ -31,6 +31,8 @@ IMPACT_F32 = 0
 IMPACT_BF16 = 1
 IMPACT_FLAG_FORCE_GENERIC = 1
 IMPACT_FLAG_RATIO_WORKER = 2
+IMPACT_BUFFER_CACHE_LOGP = 1
+IMPACT_BUFFER_NO_TARGET_DIST = 2
 
 EXPORTS = [
     "impact_version", "impact_status_string",
@@ -50,7 +52,8 @@ class ImpactError(RuntimeError):
 
 class impact_buffer_desc_t(ctypes.Structure):
     _fields_ = [("dist", ctypes.c_int32), ("T", ctypes.c_int32), ("A", ctypes.c_int32),
-                ("num_slots", ctypes.c_int32), ("K", ctypes.c_int32), ("storage", ctypes.c_int32)]
+                ("num_slots", ctypes.c_int32), ("K", ctypes.c_int32), ("storage", ctypes.c_int32),
+                ("flags", ctypes.c_uint32)]
 
 
 class impact_loss_config_t(ctypes.Structure):
@@ -62,7 +65,7 @@ class impact_loss_config_t(ctypes.Structure):
 
 class impact_batch_t(ctypes.Structure):
     _fields_ = [("worker_dist", ctypes.c_void_p), ("target_dist", ctypes.c_void_p), ("actions", ctypes.c_void_p),
-                ("rewards", ctypes.c_void_p), ("dones", ctypes.c_void_p)]
+                ("rewards", ctypes.c_void_p), ("dones", ctypes.c_void_p), ("logp", ctypes.c_void_p)]
 
 
 class impact_loss_out_t(ctypes.Structure):
@@ -172,27 +175,31 @@ def config_from_hyper(h, flags: int = 0) -> impact_loss_config_t:
 
 
 def _batch_struct(batch: Dict[str, torch.Tensor], need_target: bool = True) -> impact_batch_t:
-    tgt = batch.get("target")
-    if need_target and tgt is None:
+    """worker/target may be missing where cached log-probabilities ("logp", fp64 [T][B][2]) stand in for them."""
+    tgt, lp = batch.get("target"), batch.get("logp")
+    if need_target and tgt is None and lp is None:
         raise ValueError("batch needs a target tensor")
-    return impact_batch_t(_ptr(batch["worker"]), _ptr(tgt), _ptr(batch["actions"]), _ptr(batch["rewards"]),
-                          _ptr(batch["dones"]))
+    if lp is not None and lp.dtype != torch.float64:
+        raise ValueError("cached log-probabilities are fp64")
+    return impact_batch_t(_ptr(batch.get("worker")), _ptr(tgt), _ptr(batch["actions"]), _ptr(batch["rewards"]),
+                          _ptr(batch["dones"]), _ptr(lp))
 
 
 # ------------------------------------------------------------------------------------------
 # circular buffer
 # ------------------------------------------------------------------------------------------
 
-def impact_buffer_storage_bytes(dist, T: int, A: int, num_slots: int, K: int, storage) -> int:
-    d = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage))
+def impact_buffer_storage_bytes(dist, T: int, A: int, num_slots: int, K: int, storage, flags: int = 0) -> int:
+    d = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage), flags)
     return int(load().impact_buffer_storage_bytes(ctypes.byref(d)))
 
 
 class Buffer:
     """Owner of a buffer handle and of the torch allocation behind it."""
 
-    def __init__(self, dist, T: int, A: int, num_slots: int, K: int, storage="f32", device="cuda"):
-        self.desc = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage))
+    def __init__(self, dist, T: int, A: int, num_slots: int, K: int, storage="f32", device="cuda", flags: int = 0):
+        self.desc = impact_buffer_desc_t(dist_code(dist), T, A, num_slots, K, dtype_code(storage), flags)
+        self.flags = flags
         nbytes = int(load().impact_buffer_storage_bytes(ctypes.byref(self.desc)))
         if nbytes == 0:
             raise ImpactError(IMPACT_ERR_INVALID_ARG, "impact_buffer_storage_bytes")
@@ -274,10 +281,15 @@ def alloc_batch(buf: Buffer, B: int) -> Dict[str, torch.Tensor]:
     fd, dev, T = buf.float_dtype, buf.device, buf.T
     acts = (torch.empty((T, B), dtype=torch.int32, device=dev) if buf.dist == IMPACT_CATEGORICAL
             else torch.empty((T, B, buf.A), dtype=fd, device=dev))
-    return dict(worker=torch.empty((T, B, buf.W), dtype=fd, device=dev),
-                target=torch.empty((T, B, buf.W), dtype=fd, device=dev), actions=acts,
-                rewards=torch.empty((T, B), dtype=fd, device=dev),
-                dones=torch.empty((T, B), dtype=torch.uint8, device=dev))
+    out = dict(actions=acts, rewards=torch.empty((T, B), dtype=fd, device=dev),
+               dones=torch.empty((T, B), dtype=torch.uint8, device=dev))
+    if buf.flags & IMPACT_BUFFER_CACHE_LOGP:
+        out["logp"] = torch.empty((T, B, 2), dtype=torch.float64, device=dev)
+    else:
+        out["worker"] = torch.empty((T, B, buf.W), dtype=fd, device=dev)
+    if not buf.flags & IMPACT_BUFFER_NO_TARGET_DIST:
+        out["target"] = torch.empty((T, B, buf.W), dtype=fd, device=dev)
+    return out
 
 
 def impact_buffer_gather(buf: Buffer, dev_slots: torch.Tensor, dst: Optional[Dict[str, torch.Tensor]] = None,
@@ -326,7 +338,7 @@ def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, boots
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(d, T, B, A), dtype=torch.uint8, device=learner.device)
     b, o = _batch_struct(batch), _out_struct(out)
-    _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["worker"].dtype), T, B, A, _ptr(learner), _ptr(values),
+    _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
                                       _ptr(bootstrap), ctypes.byref(b), ctypes.byref(cfg), ctypes.byref(o),
                                       _ptr(workspace), workspace.numel(), _stream(stream)), "impact_loss_fwd_bwd")
     return out

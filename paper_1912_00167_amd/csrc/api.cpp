@@ -26,15 +26,20 @@ bool desc_ok(const impact_buffer_desc_t *d)
     // keep every element index of a plane below 2^40 and W within int range
     if ((double)d->num_slots * d->T * (2.0 * d->A) > 1.0e12) return false;
     if (d->A > (1 << 20)) return false;
+    if (d->flags & ~(IMPACT_BUFFER_CACHE_LOGP | IMPACT_BUFFER_NO_TARGET_DIST)) return false;
+    if ((d->flags & IMPACT_BUFFER_NO_TARGET_DIST) && !(d->flags & IMPACT_BUFFER_CACHE_LOGP)) return false;
     return true;
 }
 
 // Offsets of the planes in the storage, and the distance in bytes from one slot's trajectory to the
 // next in each.  The distribution and action planes pad a trajectory to a multiple of 16 bytes, so that
 // every slot starts on a vector boundary whatever T is; rewards and flags are read element-wise.
+// A buffer that caches log-probabilities has a plane logp[slot][T][2] of doubles and no worker plane
+// (and, if so asked, no target plane).
 struct Planes {
-    size_t worker, target, actions, rewards, dones, sync, total;
-    size_t stride_dist, stride_act, stride_rew, stride_done;
+    size_t worker, target, actions, rewards, dones, logp, sync, total;
+    size_t stride_dist, stride_act, stride_rew, stride_done, stride_lp;
+    bool has_worker, has_target, has_logp;
 };
 
 Planes plane_layout(const impact_buffer_desc_t &d)
@@ -47,9 +52,14 @@ Planes plane_layout(const impact_buffer_desc_t &d)
     p.stride_act = align_up(d.dist == IMPACT_CATEGORICAL ? T * 4 : T * d.A * es, 16);
     p.stride_rew = T * es;
     p.stride_done = T;
+    p.stride_lp = T * 2 * sizeof(double);
+    p.has_logp = (d.flags & IMPACT_BUFFER_CACHE_LOGP) != 0;
+    p.has_worker = !p.has_logp;
+    p.has_target = !(d.flags & IMPACT_BUFFER_NO_TARGET_DIST);
     size_t off = 0;
-    p.worker = off; off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
-    p.target = off; off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
+    p.worker = off; if (p.has_worker) off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
+    p.target = off; if (p.has_target) off = align_up(off + N * p.stride_dist + kPlanePad, kPlaneAlign);
+    p.logp = off; if (p.has_logp) off = align_up(off + N * p.stride_lp + kPlanePad, kPlaneAlign);
     p.actions = off; off = align_up(off + N * p.stride_act + kPlanePad, kPlaneAlign);
     p.rewards = off; off = align_up(off + N * p.stride_rew + kPlanePad, kPlaneAlign);
     p.dones = off; off = align_up(off + N * p.stride_done + kPlanePad, kPlaneAlign);
@@ -156,7 +166,8 @@ namespace {
 struct RingStateHeader {
     uint32_t magic, version;
     int32_t dist, T, A, num_slots, K, storage;
-    int32_t w, r, live, reserved;
+    int32_t w, r, live;
+    uint32_t flags;
 };
 constexpr uint32_t kStateMagic = 0x504d4952u, kStateVersion = 1;   // "RIMP"
 }  // namespace
@@ -172,7 +183,7 @@ impact_status_t impact_buffer_export_state(impact_buffer_t *buf, void *host_dst,
     std::lock_guard<std::mutex> lock(buf->mu);
     const impact_buffer_desc_t &d = buf->desc;
     const RingStateHeader h{kStateMagic, kStateVersion, d.dist, d.T, d.A, d.num_slots, d.K, d.storage,
-                            buf->w, buf->r, buf->live, 0};
+                            buf->w, buf->r, buf->live, d.flags};
     std::memcpy(host_dst, &h, sizeof h);
     std::memcpy(static_cast<char *>(host_dst) + sizeof h, buf->count.data(), buf->count.size() * sizeof(int32_t));
     return IMPACT_OK;
@@ -186,7 +197,7 @@ impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *hos
     RingStateHeader h;
     std::memcpy(&h, host_src, sizeof h);
     if (h.magic != kStateMagic || h.version != kStateVersion || h.dist != d.dist || h.T != d.T || h.A != d.A ||
-        h.num_slots != d.num_slots || h.K != d.K || h.storage != d.storage)
+        h.num_slots != d.num_slots || h.K != d.K || h.storage != d.storage || h.flags != d.flags)
         return IMPACT_ERR_INVALID_ARG;
     if (h.w < 0 || h.w >= d.num_slots || h.r < 0 || h.r >= d.num_slots) return IMPACT_ERR_INVALID_ARG;
     std::vector<int32_t> count(d.num_slots);
@@ -225,6 +236,24 @@ static void scatter_field(PlaneKind kind, const void *src, void *dst, size_t slo
     }
 }
 
+// log pi(a) of one policy (which: 0 worker, 1 target) for the trajectories of a time-major fp32 tensor,
+// into the log-probability plane of the slots they went to; one launch per run of consecutive slots.
+static void cache_logp_field(impact_buffer *buf, int which, const float *dist_f32, int n, const int32_t *slots,
+                             hipStream_t s)
+{
+    const impact_buffer_desc_t &d = buf->desc;
+    int i = 0;
+    while (i < n) {
+        int j = i + 1;
+        while (j < n && slots[j] == slots[j - 1] + 1) ++j;
+        LogpArgs a{dist_f32, buf->storage + buf->planes.actions, reinterpret_cast<double *>(buf->storage + buf->planes.logp),
+                   d.dist, d.storage, d.T, n, d.A, i, slots[i], j - i, which, buf->planes.stride_act,
+                   buf->planes.stride_lp};
+        launch_cache_logp(a, s);
+        i = j;
+    }
+}
+
 impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impact_batch_t *src, int32_t *out_slots,
                                      impact_stream_t stream)
 {
@@ -244,13 +273,19 @@ impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impa
     (void)hipGetLastError();
     const Planes &pl = buf->planes;
     const size_t es = (size_t)buf->es();           // strides below: in elements of the plane's type
-    scatter_field(fk, src->worker_dist, base + pl.worker, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
-    if (src->target_dist)
+    if (pl.has_worker)
+        scatter_field(fk, src->worker_dist, base + pl.worker, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
+    if (src->target_dist && pl.has_target)
         scatter_field(fk, src->target_dist, base + pl.target, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
     if (d.dist == IMPACT_CATEGORICAL)
         scatter_field(PLANE_I32, src->actions, base + pl.actions, pl.stride_act / 4, d.T, n, 1, out_slots, s);
     else
         scatter_field(fk, src->actions, base + pl.actions, pl.stride_act / es, d.T, n, d.A, out_slots, s);
+    if (pl.has_logp) {
+        // after the actions: the log-probabilities are those of the action as stored
+        cache_logp_field(buf, 0, static_cast<const float *>(src->worker_dist), n, out_slots, s);
+        if (src->target_dist) cache_logp_field(buf, 1, static_cast<const float *>(src->target_dist), n, out_slots, s);
+    }
     scatter_field(fk, src->rewards, base + pl.rewards, pl.stride_rew / es, d.T, n, 1, out_slots, s);
     scatter_field(PLANE_U8, src->dones, base + pl.dones, pl.stride_done, d.T, n, 1, out_slots, s);
     if (hipGetLastError() != hipSuccess) {
@@ -275,8 +310,10 @@ impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const 
     const impact_buffer_desc_t &d = buf->desc;
     const PlaneKind fk = d.storage == IMPACT_F32 ? PLANE_F32_TO_F32 : PLANE_F32_TO_BF16;
     (void)hipGetLastError();
-    scatter_field(fk, target_dist, buf->storage + buf->planes.target, buf->planes.stride_dist / (size_t)buf->es(), d.T,
-                  n, buf->W(), slots, static_cast<hipStream_t>(stream));
+    if (buf->planes.has_target)
+        scatter_field(fk, target_dist, buf->storage + buf->planes.target, buf->planes.stride_dist / (size_t)buf->es(),
+                      d.T, n, buf->W(), slots, static_cast<hipStream_t>(stream));
+    if (buf->planes.has_logp) cache_logp_field(buf, 1, target_dist, n, slots, static_cast<hipStream_t>(stream));
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
 }
 
@@ -326,8 +363,9 @@ impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int3
         launch_gather_plane(a, s);
     };
     const Planes &pl = buf->planes;
-    go(pl.worker, pl.stride_dist, dst->worker_dist, buf->W(), es);
-    go(pl.target, pl.stride_dist, dst->target_dist, buf->W(), es);
+    if (pl.has_worker) go(pl.worker, pl.stride_dist, dst->worker_dist, buf->W(), es);
+    if (pl.has_target) go(pl.target, pl.stride_dist, dst->target_dist, buf->W(), es);
+    if (pl.has_logp) go(pl.logp, pl.stride_lp, dst->logp, 4, 4);      // a pair of doubles, copied as four words
     if (d.dist == IMPACT_CATEGORICAL) go(pl.actions, pl.stride_act, dst->actions, 1, 4);
     else go(pl.actions, pl.stride_act, dst->actions, d.A, es);
     go(pl.rewards, pl.stride_rew, dst->rewards, 1, es);
@@ -364,15 +402,18 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     if (dtype != IMPACT_F32 && dtype != IMPACT_BF16) return IMPACT_ERR_INVALID_ARG;
     if (T < 1 || B < 1 || A < 1 || A > (1 << 20)) return IMPACT_ERR_INVALID_ARG;
     if (!config_ok(cfg) || !out) return IMPACT_ERR_INVALID_ARG;
-    if (!learner || !values || !bootstrap || !batch.worker_dist || !batch.target_dist || !batch.actions ||
-        !batch.rewards || !batch.dones)
+    if (!learner || !values || !bootstrap || !batch.actions || !batch.rewards || !batch.dones)
         return IMPACT_ERR_INVALID_ARG;
+    // cached log-probabilities stand in for the worker's distribution, and for the target's outside the KL term
+    const bool cached = batch.logp != nullptr;
+    if (!cached && (!batch.worker_dist || !batch.target_dist)) return IMPACT_ERR_INVALID_ARG;
+    if (cached && !batch.target_dist && cfg && cfg->kl_coeff != 0.f) return IMPACT_ERR_INVALID_ARG;
     if (!out->grad_learner_dist || !out->grad_values || !out->loss5 || !workspace) return IMPACT_ERR_INVALID_ARG;
     if (workspace_bytes < impact_loss_workspace_bytes(dist, T, B, A)) return IMPACT_ERR_INVALID_ARG;
-    const void *ptrs[] = {learner, values, bootstrap, batch.worker_dist, batch.target_dist, batch.actions,
-                          batch.rewards, out->grad_learner_dist, out->grad_values, workspace};
+    const void *ptrs[] = {learner, values, bootstrap, cached ? nullptr : batch.worker_dist, batch.target_dist,
+                          batch.actions, batch.rewards, batch.logp, out->grad_learner_dist, out->grad_values, workspace};
     for (const void *p : ptrs)
-        if (!aligned16(p)) return IMPACT_ERR_INVALID_ARG;
+        if (p && !aligned16(p)) return IMPACT_ERR_INVALID_ARG;
     if ((out->vs && !aligned16(out->vs)) || (out->adv && !aligned16(out->adv))) return IMPACT_ERR_INVALID_ARG;
     if ((double)T * B * (2.0 * A) > 1.0e12) return IMPACT_ERR_INVALID_ARG;
 
@@ -380,7 +421,8 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     std::memset(&a, 0, sizeof(a));
     a.T = T; a.B = B; a.A = A;
     a.learner = learner; a.values = values; a.bootstrap = bootstrap;
-    a.worker = batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
+    a.worker = cached ? nullptr : batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
+    a.logp = batch.logp;
     a.rewards = batch.rewards; a.dones = batch.dones;
     a.slots = dev_slots; a.num_slots = num_slots;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
@@ -399,6 +441,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
     bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
+    if (cached) fast = false;
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
     if (slot_major) {
@@ -407,6 +450,8 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
             fast = false;
         a.stride_dist = planes->stride_dist;
         a.stride_act = planes->stride_act;
+        a.stride_lp = planes->stride_lp;
+        if ((double)num_slots * (double)planes->stride_lp >= 4294967296.0) fast = false;
     }
     (void)hipGetLastError();
     bool launched = false;
@@ -453,8 +498,9 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
     const impact_buffer_desc_t &d = buf->desc;
     const char *base = buf->storage;
     impact_batch_t batch;
-    batch.worker_dist = base + buf->planes.worker;
-    batch.target_dist = base + buf->planes.target;
+    batch.worker_dist = buf->planes.has_worker ? base + buf->planes.worker : nullptr;
+    batch.target_dist = buf->planes.has_target ? base + buf->planes.target : nullptr;
+    batch.logp = buf->planes.has_logp ? reinterpret_cast<const double *>(base + buf->planes.logp) : nullptr;
     batch.actions = base + buf->planes.actions;
     batch.rewards = base + buf->planes.rewards;
     batch.dones = reinterpret_cast<const uint8_t *>(base + buf->planes.dones);

@@ -219,6 +219,49 @@ void launch_gather_plane(const GatherArgs &a, hipStream_t s)
     }
 }
 
+// One thread per stored step: fp64 with the library's exp and log (this runs once per trajectory, when
+// it enters the buffer or when the target network's outputs are appended).
+template <int DIST, typename ST>
+__global__ __launch_bounds__(256) void cache_logp(const LogpArgs a)
+{
+    const int W = DIST == IMPACT_CATEGORICAL ? a.A : 2 * a.A;
+    const size_t total = (size_t)a.cnt * a.T;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const int s = (int)(e / a.T), t = (int)(e - (size_t)s * a.T);
+        const float *z = a.dist_f32 + ((size_t)t * a.n + a.i0 + s) * W;
+        const char *act_slot = (const char *)a.actions_plane + (size_t)(a.slot0 + s) * a.stride_act;
+        double lp;
+        if (DIST == IMPACT_CATEGORICAL) {
+            const int act = min(max(((const int *)act_slot)[t], 0), a.A - 1);   // (the loss flags an index out of range)
+            float m = z[0];
+            for (int k = 1; k < a.A; ++k) m = fmaxf(m, z[k]);
+            double S = 0.0;
+            for (int k = 0; k < a.A; ++k) S += exp((double)z[k] - (double)m);
+            lp = ((double)z[act] - (double)m) - log(S);
+        } else {
+            const ST *act = (const ST *)act_slot + (size_t)t * a.A;
+            lp = -a.A * (double)kHalfLog2Pi;
+            for (int d = 0; d < a.A; ++d) {
+                const double ls = (double)z[a.A + d];
+                const double diff = (double)widen(act[d]) - (double)z[d];
+                lp += -0.5 * diff * diff * exp(-2.0 * ls) - ls;
+            }
+        }
+        double *slot_lp = (double *)((char *)a.logp_plane + (size_t)(a.slot0 + s) * a.stride_lp);
+        slot_lp[2 * t + a.which] = lp;
+    }
+}
+
+void launch_cache_logp(const LogpArgs &a, hipStream_t s)
+{
+    const size_t total = (size_t)a.cnt * a.T;
+    if (total == 0) return;
+    const dim3 grid((unsigned)min((size_t)65536, (total + 255) / 256)), block(256);
+    if (a.dist == IMPACT_CATEGORICAL) hipLaunchKernelGGL((cache_logp<IMPACT_CATEGORICAL, float>), grid, block, 0, s, a);
+    else if (a.storage == IMPACT_F32) hipLaunchKernelGGL((cache_logp<IMPACT_DIAG_GAUSSIAN, float>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((cache_logp<IMPACT_DIAG_GAUSSIAN, bf16_t>), grid, block, 0, s, a);
+}
+
 __global__ void zero_words(unsigned *p, int n)
 {
     for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0u;

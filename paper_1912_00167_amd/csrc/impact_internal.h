@@ -32,11 +32,14 @@ struct LossArgs {
     const void *actions;
     const void *rewards;
     const uint8_t *dones;
+    // cached log pi_worker(a), log pi_target(a): [T][B][2] or the buffer's plane [slot][T][2], or null.
+    // Where given, `worker` is null, and `target` may be (then the KL coefficient is zero).
+    const double *logp;
     const int32_t *slots;     // device [B]; slot-major only
     int num_slots;
     // slot-major only: bytes from one slot's trajectory to the next in the distribution planes and in
     // the action plane (multiples of 16; rewards and flags lie T elements apart)
-    size_t stride_dist, stride_act;
+    size_t stride_dist, stride_act, stride_lp;
     // hyper-parameters, pre-digested on the host
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;           // target-worker clipping rho; may be +inf
@@ -95,5 +98,17 @@ struct GatherArgs {
     size_t slot_stride;
 };
 void launch_gather_plane(const GatherArgs &a, hipStream_t s);
+
+// log pi(a) of the trajectories i0 .. i0+cnt-1 of a time-major fp32 distribution tensor [T][n][W], for the
+// actions already stored in slots slot0 .. slot0+cnt-1, into column `which` of the plane logp[slot][T][2].
+struct LogpArgs {
+    const float *dist_f32;
+    const void *actions_plane;
+    double *logp_plane;
+    int dist, storage, T, n, A;
+    int i0, slot0, cnt, which;
+    size_t stride_act, stride_lp;    // bytes between slots
+};
+void launch_cache_logp(const LogpArgs &a, hipStream_t s);
 
 }  // namespace impact

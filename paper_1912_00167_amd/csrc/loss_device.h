@@ -16,7 +16,7 @@ typedef uint16_t bf16_t;
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 
-constexpr float kHalfLog2Pi = 0.91893853320467274178f;
+constexpr double kHalfLog2Pi = 0.91893853320467274178;
 
 // e^x through the hardware base-2 exponential: one multiply and one v_exp_f32.  The rounding of
 // x*log2(e) adds a relative error of about |x| * 6e-8 to the 1-ulp result; results below the

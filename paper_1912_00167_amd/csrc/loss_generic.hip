@@ -80,6 +80,11 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         const char *act_slot = (const char *)a.actions + (SLOT ? (size_t)slot * a.stride_act : 0);
         const ST *av = (const ST *)act_slot + (SLOT ? (size_t)t : s_tm) * A;   // Gaussian actions
 
+        // cached log pi_worker(a), log pi_target(a) of this step; the target's distribution may be absent
+        const bool cached = a.logp != nullptr, has_target = a.target != nullptr;
+        const double *lp2 = !cached ? nullptr
+                            : SLOT ? (const double *)((const char *)a.logp + (size_t)slot * a.stride_lp) + 2 * (size_t)t
+                                   : a.logp + 2 * s_tm;
         if (valid) {
             V = a.values[s_tm];
             const float Vn = (t + 1 < a.T) ? a.values[s_tm + a.B] : a.bootstrap[b];
@@ -89,34 +94,50 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             if (DIST == IMPACT_CATEGORICAL) {
                 act = ((const int *)act_slot)[SLOT ? (size_t)t : s_tm];
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
-                float m_w;
-                double S_w;
-                softmax_stats(zw, A, m_w, S_w);
-                softmax_stats(zt, A, m_t, S_t);
+                if (has_target) softmax_stats(zt, A, m_t, S_t);
                 softmax_stats(zl, A, m_l, S_l);
-                const double xw = (double)widen(zw[act]) - (double)m_w;
-                const double xt = (double)widen(zt[act]) - (double)m_t;
                 const double xl = (double)zl[act] - (double)m_l;
-                w = exp(xt - xw) * (S_w / S_t);
-                R1 = exp(xl - xt) * (S_t / S_l);
                 const double logS_l = log(S_l), logS_t = log(S_t);
+                if (cached) {
+                    w = exp(lp2[1] - lp2[0]);
+                    R1 = exp((xl - logS_l) - lp2[1]);
+                } else {
+                    float m_w;
+                    double S_w;
+                    softmax_stats(zw, A, m_w, S_w);
+                    const double xw = (double)widen(zw[act]) - (double)m_w;
+                    const double xt = (double)widen(zt[act]) - (double)m_t;
+                    w = exp(xt - xw) * (S_w / S_t);
+                    R1 = exp(xl - xt) * (S_t / S_l);
+                }
                 for (int k = 0; k < A; ++k) {
                     const double lpl = ((double)zl[k] - (double)m_l) - logS_l;
-                    const double lpt = ((double)widen(zt[k]) - (double)m_t) - logS_t;
                     H -= exp(lpl) * lpl;
-                    KL += exp(lpt) * (lpt - lpl);
+                    if (has_target) {
+                        const double lpt = ((double)widen(zt[k]) - (double)m_t) - logS_t;
+                        KL += exp(lpt) * (lpt - lpl);
+                    }
                 }
             } else {
-                const double lw = gauss_logp(zw, av, A), lt = gauss_logp(zt, av, A), ll = gauss_logp(zl, av, A);
-                w = exp(lt - lw);
-                R1 = exp(ll - lt);
-                for (int d = 0; d < A; ++d) {
-                    const double ls = (double)zl[A + d], lst = (double)widen(zt[A + d]);
-                    const double dm = (double)zl[d] - (double)widen(zt[d]);
-                    H += ls;
-                    KL += (ls - lst) + 0.5 * (exp(2.0 * lst) + dm * dm) * exp(-2.0 * ls) - 0.5;
+                const double ll = gauss_logp(zl, av, A);
+                if (cached) {                      // the cached values carry the -D/2 log 2pi that gauss_logp omits
+                    w = exp(lp2[1] - lp2[0]);
+                    R1 = exp((ll - A * kHalfLog2Pi) - lp2[1]);
+                } else {
+                    const double lw = gauss_logp(zw, av, A), lt = gauss_logp(zt, av, A);
+                    w = exp(lt - lw);
+                    R1 = exp(ll - lt);
                 }
-                H += A * ((double)kHalfLog2Pi + 0.5);
+                for (int d = 0; d < A; ++d) {
+                    const double ls = (double)zl[A + d];
+                    H += ls;
+                    if (has_target) {
+                        const double lst = (double)widen(zt[A + d]);
+                        const double dm = (double)zl[d] - (double)widen(zt[d]);
+                        KL += (ls - lst) + 0.5 * (exp(2.0 * lst) + dm * dm) * exp(-2.0 * ls) - 0.5;
+                    }
+                }
+                H += A * (kHalfLog2Pi + 0.5);
             }
             sc = scan_inputs(a, w, r, done, V, Vn);
             R = surrogate_ratio(a, R1, w);
@@ -138,7 +159,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 for (int k = 0; k < A; ++k) {
                     const double lp = ((double)zl[k] - (double)m_l) - logS_l;
                     const double p = exp(lp);
-                    const double pt = exp(((double)widen(zt[k]) - (double)m_t) - logS_t);
+                    const double pt = has_target ? exp(((double)widen(zt[k]) - (double)m_t) - logS_t) : p;   // no target: no KL term
                     const double base = ce * p * (lp + H) + ck * (p - pt);
                     gd[k] = (float)(g * ((k == act) ? others : -p) + base);
                 }
@@ -147,8 +168,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                     const double mu = (double)zl[d], ls = (double)zl[A + d];
                     const double E = exp(-2.0 * ls);
                     const double diff = (double)widen(av[d]) - mu;
-                    const double dm = mu - (double)widen(zt[d]);
-                    const double q = (exp(2.0 * (double)widen(zt[A + d])) + dm * dm) * E;
+                    const double dm = has_target ? mu - (double)widen(zt[d]) : 0.0;
+                    const double q = has_target ? (exp(2.0 * (double)widen(zt[A + d])) + dm * dm) * E : 1.0;   // no target: no KL term
                     gd[d] = (float)((g * diff + ck * dm) * E);
                     gd[A + d] = (float)(g * (diff * diff * E - 1.0) + ck * (1.0 - q) - ce);
                 }

@@ -59,12 +59,27 @@ def as_passed_to_c(h):
                    eps=f(h.eps), vf_coeff=f(h.vf_coeff), ent_coeff=f(h.ent_coeff), kl_coeff=f(h.kl_coeff))
 
 
-def run_oracle(wl, x, hyper=None, n_threads=8):
+def cached_oracle_inputs(x, xi, wl, cached):
+    """What a buffer that caches log-probabilities holds: log pi_worker(a), log pi_target(a) from the fp32
+    distributions as handed over and the action as stored; no worker distribution; the target's (rounded
+    to the storage dtype) only if it is kept for the KL term.  cached: None, "with_target" or "no_target"."""
+    if cached is None:
+        return xi
+    y = dict(xi)
+    y["logp"] = oracle.behaviour_logp(wl.dist, x["target"], x["worker"], xi["actions"])
+    y["worker"] = None
+    if cached == "no_target":
+        y["target"] = None
+    return y
+
+
+def run_oracle(wl, x, hyper=None, n_threads=8, cached=None):
     h = as_passed_to_c(wl.hyper if hyper is None else hyper)
     cfg = oracle.config_from_hyper(h)
-    xi = oracle_inputs(x, wl.storage)
+    xi = cached_oracle_inputs(x, oracle_inputs(x, wl.storage), wl, cached)
     return oracle.impact_loss(wl.dist, xi["learner"], xi["target"], xi["worker"], xi["actions"], xi["rewards"],
-                              xi["dones"], xi["values"], xi["bootstrap"], cfg, n_threads=n_threads), xi, cfg
+                              xi["dones"], xi["values"], xi["bootstrap"], cfg, n_threads=n_threads,
+                              cached_logp=xi.get("logp")), xi, cfg
 
 
 def max_violation(got, want, scale=1.0):
@@ -74,10 +89,10 @@ def max_violation(got, want, scale=1.0):
     return float(np.max(err / (ATOL + RTOL * np.abs(want)))) if err.size else 0.0
 
 
-def check_against_oracle(wl, x, got, hyper=None, label=""):
+def check_against_oracle(wl, x, got, hyper=None, label="", cached=None):
     """got: dict of numpy arrays from the GPU (grad_dist, grad_values, vs, adv, loss5)."""
     h = as_passed_to_c(wl.hyper if hyper is None else hyper)
-    want, xi, cfg = run_oracle(wl, x, h)
+    want, xi, cfg = run_oracle(wl, x, h, cached=cached)
     M = wl.T * x["learner"].shape[1]
     report = {}
     for k in ("vs", "adv"):
@@ -97,7 +112,7 @@ def check_against_oracle(wl, x, got, hyper=None, label=""):
         near = (np.abs(R - (1 + h.eps)) <= 2e-5 * (1 + h.eps)) | (np.abs(R - (1 - h.eps)) <= 2e-5)
         if near.any():
             kw = dict(dist=wl.dist, learner=xi["learner"], target=xi["target"], worker=xi["worker"],
-                      actions=xi["actions"], values=xi["values"], vs=want["vs"])
+                      actions=xi["actions"], values=xi["values"], vs=want["vs"], cached_logp=xi.get("logp"))
             open_cfg = oracle.make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, math.inf, h.vf_coeff,
                                           h.ent_coeff, h.kl_coeff, getattr(h, "ratio_mode", 0))
             g_on = oracle.loss_given_targets(adv=want["adv"], cfg=open_cfg, **kw)["grad_dist"] * M

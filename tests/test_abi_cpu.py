@@ -34,9 +34,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(B.impact_buffer_desc_t) == 24
+    assert ctypes.sizeof(B.impact_buffer_desc_t) == 28
     assert ctypes.sizeof(B.impact_loss_config_t) == 40
-    assert ctypes.sizeof(B.impact_batch_t) == 5 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(B.impact_batch_t) == 6 * ctypes.sizeof(ctypes.c_void_p)
     assert ctypes.sizeof(B.impact_loss_out_t) == 5 * ctypes.sizeof(ctypes.c_void_p)
 
 
@@ -61,6 +61,26 @@ def test_storage_bytes_cover_all_planes(lib):
             want = sum(up(p + 16, 256) for p in planes) + 256
             got = lib.impact_buffer_storage_bytes(ctypes.byref(d))
             assert got == want, (dist, storage, T, A, N)
+
+
+def test_storage_of_a_buffer_that_caches_log_probabilities(lib):
+    up = lambda x, a: (x + a - 1) // a * a
+    T, A, N = 50, 18, 64
+    for dist, storage in ((0, 0), (1, 1)):
+        es = 4 if storage == 0 else 2
+        W = A if dist == 0 else 2 * A
+        act = N * up(T * 4 if dist == 0 else T * A * es, 16)
+        common = [act, N * T * es, N * T, N * T * 16]           # actions, rewards, flags, two doubles per step
+        for flags, extra in ((B.IMPACT_BUFFER_CACHE_LOGP, [N * up(T * W * es, 16)]),
+                             (B.IMPACT_BUFFER_CACHE_LOGP | B.IMPACT_BUFFER_NO_TARGET_DIST, [])):
+            d = B.impact_buffer_desc_t(dist, T, A, N, 2, storage, flags)
+            want = sum(up(p + 16, 256) for p in common + extra) + 256
+            assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == want, (dist, storage, flags)
+    # dropping the target's distribution makes sense only when its log-probabilities are cached
+    d = B.impact_buffer_desc_t(0, T, A, N, 2, 0, B.IMPACT_BUFFER_NO_TARGET_DIST)
+    assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == 0
+    d = B.impact_buffer_desc_t(0, T, A, N, 2, 0, 8)
+    assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == 0
 
 
 def test_invalid_descriptors_and_arguments(lib):
