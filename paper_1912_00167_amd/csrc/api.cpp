@@ -441,7 +441,6 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
     bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
-    if (cached) fast = false;
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
     if (slot_major) {
@@ -456,8 +455,12 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     (void)hipGetLastError();
     bool launched = false;
     if (fast) {
-        launched = dist == IMPACT_CATEGORICAL ? launch_loss_cat_static(dtype, slot_major, a, s)
-                                              : launch_loss_gauss_static(dtype, slot_major, a, s);
+        if (cached)
+            launched = dist == IMPACT_CATEGORICAL ? launch_loss_cat_cached(dtype, slot_major, a, s)
+                                                  : launch_loss_gauss_cached(dtype, slot_major, a, s);
+        else
+            launched = dist == IMPACT_CATEGORICAL ? launch_loss_cat_static(dtype, slot_major, a, s)
+                                                  : launch_loss_gauss_static(dtype, slot_major, a, s);
     }
     if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
     if (!done_count) {

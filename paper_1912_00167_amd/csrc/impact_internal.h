@@ -73,6 +73,9 @@ inline int num_tiles(int B) { return (B + NB - 1) / NB; }
 // Return false when no specialised kernel exists for (A, alignment): the caller then uses the generic one.
 bool launch_loss_cat_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+// ... on cached log-probabilities (a.logp; with the KL term if a.target is there)
+bool launch_loss_cat_cached(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+bool launch_loss_gauss_cached(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_reduce(const ReduceArgs &r, hipStream_t s);
 void launch_zero_words(unsigned *p, int n, hipStream_t s);

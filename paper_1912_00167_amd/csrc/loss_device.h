@@ -18,6 +18,11 @@ __device__ __forceinline__ float widen(bf16_t x) { return __uint_as_float(((uint
 
 constexpr double kHalfLog2Pi = 0.91893853320467274178;
 
+// Where a policy class takes the behaviour side from: the worker's and the target's distributions, or the
+// buffer's cached pair log pi_worker(a), log pi_target(a) without / with the target's distribution (which
+// the KL term needs).
+constexpr int POLICY_FULL = 0, POLICY_CACHED = 1, POLICY_CACHED_TARGET = 2;
+
 // e^x through the hardware base-2 exponential: one multiply and one v_exp_f32.  The rounding of
 // x*log2(e) adds a relative error of about |x| * 6e-8 to the 1-ulp result; results below the
 // normal range flush to zero.  Only used where an absolute error of a few 1e-8 in a probability

@@ -30,13 +30,19 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     constexpr int SPW = 64 / P;                    // steps per wavefront
     constexpr int RWP = SPW / NB;                  // time rows per wavefront
     constexpr int TCH = NW * RWP;              // time rows per chunk
-    // per-wavefront staging regions: actions, worker, target (storage dtype), learner / gradients (fp32)
+    // The behaviour side: the worker's and the target's distributions, or the cached pair
+    // log pi_worker(a), log pi_target(a) with the target's distribution only where the KL term needs it.
+    constexpr bool CACHED = Policy::CACHED, TGT = Policy::TGT;
+    // per-wavefront staging regions: actions, worker, target (storage dtype), cached pair (fp64),
+    // learner / gradients (fp32)
     __shared__ __align__(16) ST r_act_all[ACT > 0 ? NW : 1][ACT > 0 ? SPW * ACT : 8];
-    __shared__ __align__(16) ST r_wk_all[NW][SPW * W];
-    __shared__ __align__(16) ST r_tg_all[NW][SPW * W];
+    __shared__ __align__(16) ST r_wk_all[CACHED ? 1 : NW][CACHED ? 8 : SPW * W];
+    __shared__ __align__(16) ST r_tg_all[TGT ? NW : 1][TGT ? SPW * W : 8];
+    __shared__ __align__(16) double r_lp_all[CACHED ? NW : 1][CACHED ? SPW * 2 : 2];
     // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
     // while this chunk's gradients are still being produced in the other one
-    constexpr int LDS_ONE = NW * SPW * ((ACT + 2 * W) * (int)sizeof(ST) + W * 4) + 4 * TCH * NB * 8 + 1024;
+    constexpr int BEHAVIOUR_BYTES = (ACT + (CACHED ? 0 : W) + (TGT ? W : 0)) * (int)sizeof(ST) + (CACHED ? 16 : 0);
+    constexpr int LDS_ONE = NW * SPW * (BEHAVIOUR_BYTES + W * 4) + 4 * TCH * NB * 8 + 1024;
     constexpr int NLN = (LDS_ONE + NW * SPW * W * 4 <= 64 * 1024) ? 2 : 1;
     // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
     // tell a read of one region from an asynchronous load still in flight into the other)
@@ -47,7 +53,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     // where the tile's trajectories start in the buffer: in steps (rewards, flags), and in bytes of the
     // distribution planes and of the action plane, whose slots are padded to 16 bytes
     __shared__ int slot_row0[NB];
-    __shared__ unsigned slot_dist0[NB], slot_act0[NB];
+    __shared__ unsigned slot_dist0[NB], slot_act0[NB], slot_lp0[NB];
     __shared__ float red[NW][PARTIAL_STRIDE];
     __shared__ double exp_tbl[EXP_TABLE_SIZE];
     // A wavefront that walks its trajectories alone (NW == 1) reads their rewards and termination flags
@@ -64,7 +70,8 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     const bool lead = part == 0;                   // the lane that stores the step's scalars
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
     const int b0 = tile * NB, b = b0 + bl;
-    ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[wave], *r_tg = r_tg_all[wave];
+    ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[CACHED ? 0 : wave], *r_tg = r_tg_all[TGT ? wave : 0];
+    double *r_lp = r_lp_all[CACHED ? wave : 0];
 
     float bad = 0.f;
     // the slot indices travel while the table is computed
@@ -77,6 +84,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         slot_row0[tid] = s * a.T;
         slot_dist0[tid] = (unsigned)s * (unsigned)a.stride_dist;
         slot_act0[tid] = (unsigned)s * (unsigned)a.stride_act;
+        slot_lp0[tid] = (unsigned)s * (unsigned)a.stride_lp;
     }
     __syncthreads();
     // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
@@ -85,12 +93,14 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     // that its loads travel during the rest of the set-up.
     ChunkLoader<ST, ACTR, RWP, SLOT> ld_act;
     ChunkLoader<ST, W, RWP, SLOT> ld_dist;
+    ChunkLoader<double, 2, RWP, SLOT> ld_lp;
     ChunkLoader<float, W, RWP, false> ld_lrn;
     auto fetch_buffer_side = [&](int c) {
         const int t_base = c * TCH + wave * RWP;
         if (ACT > 0) ld_act.issue(ld_act.chunk_base(a.actions, a.B, t_base, b0), r_act, lane);
-        ld_dist.issue(ld_dist.chunk_base(a.worker, a.B, t_base, b0), r_wk, lane);
-        ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
+        if (!CACHED) ld_dist.issue(ld_dist.chunk_base(a.worker, a.B, t_base, b0), r_wk, lane);
+        if (TGT) ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
+        if (CACHED) ld_lp.issue(ld_lp.chunk_base(a.logp, a.B, t_base, b0), r_lp, lane);
     };
     const int nchunk = (a.T + TCH - 1) / TCH;
     const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
@@ -99,6 +109,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
         if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane);
         ld_dist.plan(a.B, tail_rows, slot_dist0, lane);
+        if (CACHED) ld_lp.plan(a.B, tail_rows, slot_lp0, lane);
         fetch_buffer_side(nchunk - 1);
     }
     if constexpr (PRE) {
@@ -185,6 +196,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         fetch_scalars_tail(nchunk - 1);
         if (ACT > 0) ld_act.plan(a.B, RWP, slot_act0, lane);
         ld_dist.plan(a.B, RWP, slot_dist0, lane);
+        if (CACHED) ld_lp.plan(a.B, RWP, slot_lp0, lane);
         ld_lrn.plan(a.B, RWP, nullptr, lane);
         st_grad.plan(a.B, lane);
     }
@@ -236,8 +248,8 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         if (rows > 0) {
             const float Vn = (t + 1 < a.T) ? Vnext : Vboot;
             wave_lds_sync();
-            w = Policy::behaviour(kept, r_act + own_step * ACTR, action, r_wk + own_step * W, r_tg + own_step * W, part,
-                                  exp_tbl, bad);
+            w = Policy::behaviour(kept, r_act + own_step * ACTR, action, r_wk + (CACHED ? 0 : own_step * W),
+                                  r_tg + (TGT ? own_step * W : 0), r_lp + (CACHED ? own_step * 2 : 0), part, exp_tbl, bad);
             sc = scan_inputs(a, w, r, done, V, Vn);
         }
         // ---- scan: adv_t ----
