@@ -33,17 +33,17 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 MEASURED_TRAFFIC_BYTES = {"C5": 1.0491e9, "C4": 2.670e8}
 
 
-def algorithmic_bytes_per_step(wl) -> int:
-    """Each input read once, each output written once (single pass), per (t, b) step."""
+def algorithmic_bytes_per_step(wl, cached=None) -> int:
+    """Each input read once, each output written once (single pass), per (t, b) step.
+    cached: None (both distributions in the batch), or "with_target" / "no_target": the buffer keeps
+    log pi_worker(a), log pi_target(a) as two doubles in place of the worker's distribution (and of the
+    target's, which only the KL term needs)."""
     es = 4 if wl.storage == "f32" else 2
-    if wl.dist == workloads.CATEGORICAL:
-        A = wl.A
-        reads = 4 * A + 2 * A * es + 4 + es + 1 + 4      # learner, target+worker, action, reward, done, value
-        writes = 4 * A + 12                              # grad logits, grad value, vs, adv
-    else:
-        D = wl.A
-        reads = 8 * D + 4 * D * es + D * es + es + 1 + 4  # learner, target+worker, actions, reward, done, value
-        writes = 8 * D + 12
+    W = wl.A if wl.dist == workloads.CATEGORICAL else 2 * wl.A
+    action = 4 if wl.dist == workloads.CATEGORICAL else wl.A * es
+    behaviour = {None: 2 * W * es, "with_target": 16 + W * es, "no_target": 16}[cached]
+    reads = 4 * W + behaviour + action + es + 1 + 4      # learner, behaviour side, action, reward, done, value
+    writes = 4 * W + 12                                  # gradient of the distribution, of the value, vs, adv
     return reads + writes
 
 
@@ -139,6 +139,8 @@ def table(torch, binding, names, repeats: int = 5) -> None:
             us.append(e0.elapsed_time(e1) * 1e3 / n_calls)
         return float(np.median(us))
 
+    gc.collect()
+    gc.disable()       # a full collection (about 30 ms with torch loaded) would land in one of the timing loops
     print("| workload | line | us/call | steps/s | algorithmic GB/s | % of 8 TB/s | clipped | truncated |")
     print("|---|---|---|---|---|---|---|---|")
     for name in names:
@@ -162,9 +164,10 @@ def table(torch, binding, names, repeats: int = 5) -> None:
                                                                       boot[i % nq], cfg, out=out, workspace=ws), n_calls)
         # host bookkeeping of one sample call (ring walk, counts), timed on its own
         s_np, c_np = np.empty(B, np.int32), np.empty(B, np.int32)
-        t0 = time.perf_counter()
         n_samples = 200
-        for _ in range(n_samples):
+        for k in range(20 + n_samples):
+            if k == 20:                             # after a warm-up
+                t0 = time.perf_counter()
             if binding.impact_buffer_num_live(buf) < B:
                 binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
             binding.impact_buffer_sample(buf, B, s_np, c_np)
@@ -181,7 +184,25 @@ def table(torch, binding, names, repeats: int = 5) -> None:
                   f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
         print(f"| {wl.name} | sample (host bookkeeping, incl. refill) | {t_s:.1f} | {steps / t_s * 1e6:.3e} | - | - | - | - |", flush=True)
         buf.close()
-        del learner, values, boot, gathered, dst, out
+        del gathered, dst
+        # the same step on a buffer that keeps the two log-probabilities per step instead of the worker's
+        # distribution, and the target's distribution only if the workload has a KL term
+        cached = "with_target" if wl.hyper.kl_coeff != 0 else "no_target"
+        flags = binding.IMPACT_BUFFER_CACHE_LOGP | (0 if cached == "with_target" else binding.IMPACT_BUFFER_NO_TARGET_DIST)
+        buf = binding.Buffer(wl.dist, T, wl.A, wl.num_slots, wl.K, wl.storage, flags=flags)
+        del learner, values, boot
+        learner, values, boot = fill_ring(torch, binding, wl, buf, min(B, 4096))
+        t_c = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
+                                                                      boot[i % nq], cfg, out=out, workspace=ws), n_calls)
+        bps = algorithmic_bytes_per_step(wl, cached)
+        gbs = bps * steps / t_c / 1e3
+        what = "kept for the KL term" if cached == "with_target" else "not kept"
+        print(f"| {wl.name} | fused, cached log pi(a) pair ({bps} B/step; target distribution {what}) | {t_c:.1f} | "
+              f"{steps / t_c * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | {clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
+        buf.close()
+        del learner, values, boot, out
+        gc.collect()
+    gc.enable()
 
 
 def main() -> int:
