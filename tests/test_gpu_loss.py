@@ -77,6 +77,22 @@ def test_hyper_parameter_variants(env, dist, hi):
         check_against_oracle(wl, x, got, hyper=h, label=f"{dist} {HYPERS[hi]} flags={flags}")
 
 
+@pytest.mark.parametrize("name", ["C2", "C3"])
+@pytest.mark.parametrize("flags", [0, FORCE_GENERIC], ids=["specialised", "generic"])
+def test_impala_objective_with_the_learner_in_the_targets_place(env, name, flags):
+    """V-trace with learner-over-worker weights and the importance-sampled policy gradient (Section 2.3) come
+    out of the same kernels when the learner's own distribution is handed over as the target's, with no ratio
+    clipping and equal truncation levels."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], B=64, num_slots=64)
+    x = dict(workloads.make_trajectories(wl, 64, stream=17))
+    x["target"] = x["learner"].copy()
+    h = replace(wl.hyper, rho_clip=math.inf, eps=math.inf, rho_bar=1.3, c_bar=1.3, kl_coeff=0.0)
+    say(f"case impala objective {name} flags={flags}")
+    got = gpu_loss(torch, binding, wl, x, hyper=h, flags=flags)
+    check_against_oracle(wl, x, got, hyper=h, label=f"impala objective {name}")
+
+
 def test_optional_outputs_may_be_null(env):
     torch, binding = env
     wl = shape_workload(workloads.C2, B=16)
