@@ -175,6 +175,7 @@ FUSED = [
     ("C3", dict(T=13, B=64, A=3, num_slots=128, storage="bf16"), 128, 64),   # D = 3 bf16: 156 and 78 bytes
     ("C5", dict(T=50, B=64, num_slots=128), 128, 64),                 # D = 17 bf16: 3400 and 1700 bytes
     ("C5", dict(T=33, B=64, num_slots=128, storage="f32"), 128, 64),  # D = 17 fp32: 4488 and 2244 bytes
+    ("C2", dict(T=1000, B=64, A=6, num_slots=64), 64, 64),            # a long trajectory: 32 chunks and more
     ("C2", dict(T=37, B=21, A=7, num_slots=40), 40, 21),              # generic kernels, ragged
     ("C5", dict(T=45, B=19, A=4, num_slots=32), 32, 19),              # generic kernels, bf16, ragged
 ]
@@ -251,7 +252,9 @@ def test_fused_full_size_c5(env):
                                   ("C2", dict(T=24, A=18, B=16384, num_slots=16384), "bf16"),
                                   ("C2", dict(T=13, A=18, B=16384, num_slots=16384), "bf16"),
                                   ("C3", dict(T=50, A=6, B=16384, num_slots=16384), "bf16"),
-                                  ("C4", dict(T=21, A=9, B=8192, num_slots=8192), "f32")])
+                                  ("C4", dict(T=21, A=9, B=8192, num_slots=8192), "f32"),
+                                  # longer than the single-wavefront tiles' preload arrays: two wavefronts per tile
+                                  ("C3", dict(T=130, A=6, B=16384, num_slots=16384), "bf16")])
 def test_fused_large_batch_short_ragged_trajectories(env, case):
     """Batches large enough for one- and two-wavefront tiles, with trajectory lengths that leave a ragged
     first chunk: every output element against the oracle, and the fused form against gather + loss."""
@@ -282,6 +285,48 @@ def test_slot_indices_in_host_memory(env):
         np.testing.assert_array_equal(on_device[k].cpu().numpy(), in_place[k].cpu().numpy(), err_msg=k)
     with pytest.raises(binding.ImpactError):
         binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots.copy()), learner, values, boot, cfg)
+    buf.close()
+
+
+def test_fused_step_replays_in_a_captured_graph(env):
+    """A launch-bound learner loop can capture the step once and replay it: the call records nothing but its
+    kernel launch.  Every replay, with eager work and new inputs in between, must give the eager result."""
+    torch, binding = env
+    wl = shape_workload(workloads.C3, B=64, num_slots=128)
+    say("case fused step in a graph")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, 128, stream=21)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots_np = np.random.default_rng(2).permutation(128)[:64].astype(np.int32)
+    dev_slots = torch.from_numpy(slots_np).cuda()
+    xb = workloads.take_trajectories(x, slots_np)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    cfg = binding.config_from_hyper(wl.hyper)
+    out = binding.alloc_loss_out(wl.T, 64, wl.W)
+    ws = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, wl.T, 64, wl.A), dtype=torch.uint8, device="cuda")
+    step = lambda: binding.impact_loss_fwd_bwd_from_buffer(buf, dev_slots, learner, values, boot, cfg, out=out, workspace=ws)
+    step()                                               # the handle's first call (it clears the counter)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    for rep in range(4):
+        # new inputs in the captured tensors, the eager result for them, then unrelated eager work
+        learner.copy_(torch.from_numpy((xb["learner"] + 0.1 * rep * rng.standard_normal(xb["learner"].shape)).astype(np.float32)))
+        dev_slots.copy_(torch.from_numpy(np.roll(slots_np, rep)))
+        step()
+        torch.cuda.synchronize()
+        eager = {k: v.clone() for k, v in out.items()}
+        for v in out.values():
+            v.fill_(float("nan"))
+        junk = (torch.randn(1 << 16, device="cuda") * 2).sum()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for k in eager:
+            assert torch.equal(out[k], eager[k]), (rep, k)
     buf.close()
 
 
