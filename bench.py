@@ -219,7 +219,7 @@ def main() -> int:
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
 
     import torch

@@ -43,7 +43,7 @@ typedef enum {
     IMPACT_ERR_BUFFER_FULL = -2,     /* insert: fewer empty slots than trajectories offered */
     IMPACT_ERR_NOT_ENOUGH_LIVE = -3, /* sample: fewer live slots than trajectories asked for */
     IMPACT_ERR_HIP = -4,             /* a HIP runtime call or a kernel launch failed */
-    IMPACT_ERR_UNSUPPORTED = -5      /* a valid request this build has no kernel for */
+    IMPACT_ERR_UNSUPPORTED = -5      /* a valid request the library has no kernel for */
 } impact_status_t;
 
 typedef enum { IMPACT_CATEGORICAL = 0, IMPACT_DIAG_GAUSSIAN = 1 } impact_dist_t;
@@ -249,7 +249,9 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * One launch: the workgroup that finishes last also sums the loss terms, using
  * a counter in the buffer's storage that the first call on a handle clears (in
  * stream order).  Calls on one handle must therefore not overlap on the device:
- * issue them on one stream, or order them with events. */
+ * issue them on one stream, or order them with events.  The call enqueues kernel
+ * launches only (no memset, no copy, no allocation), so it can be captured in a
+ * HIP graph and replayed. */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
                                                 const float *learner_dist, const float *values,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,

@@ -2,9 +2,10 @@
 
 The paper fixes: N stored items, each traversable at most K times, after which
 it is discarded and its place taken by a new worker batch.  The order of
-traversal, and what happens when the ring is full or short, are this build's
-readings (parity unpinned): ring order from a read cursor, inserts never
-overwrite a live item, insert and sample are all-or-nothing.
+traversal, and what happens when the ring is full or short, are readings of a
+text that is silent on them: ring order from a read cursor, inserts never
+overwrite a live item, insert and sample are all-or-nothing.  (The bookkeeping
+itself is pinned by a brute-force simulation in the tests.)
 
 Plain Python, one loop per operation; the stored records are numpy arrays in
 slot-major order ``[N, T, ...]``.

@@ -8,7 +8,7 @@
  * do.  One loop per sum, no blocking, no fusion.
  *
  * Conventions used where the paper is silent (each is a reading, not a fact the
- * text confirms -- "parity unpinned" for these choices):
+ * text confirms; the arithmetic under each reading is pinned by the tests):
  *   - the value target is V_t + A_t with lambda inside the single accumulator;
  *   - done[t] = 1 cuts both the bootstrap of the TD error at t and the trace;
  *   - one values[T,B] tensor plus bootstrap[B] feeds the scan (no gradient) and
