@@ -227,7 +227,9 @@ __global__ __launch_bounds__(256) void cache_logp(const LogpArgs a)
     const int W = DIST == IMPACT_CATEGORICAL ? a.A : 2 * a.A;
     const size_t total = (size_t)a.cnt * a.T;
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-        const int s = (int)(e / a.T), t = (int)(e - (size_t)s * a.T);
+        // neighbouring threads take neighbouring trajectories of one time step: their records lie one
+        // after the other in the source tensor, which is where most of the bytes are
+        const int t = (int)(e / a.cnt), s = (int)(e - (size_t)t * a.cnt);
         const float *z = a.dist_f32 + ((size_t)t * a.n + a.i0 + s) * W;
         const char *act_slot = (const char *)a.actions_plane + (size_t)(a.slot0 + s) * a.stride_act;
         double lp;
