@@ -440,7 +440,22 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
-    bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC) && (B % NB == 0);
+    bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC);
+    if (B % NB) {
+        // A ragged last tile: the specialised kernels move 16-byte vectors of time-major row segments, so
+        // every row of such a tensor has to start on a vector boundary and the ragged segment has to be a
+        // whole number of vectors.  (The buffer's planes are slot-major and do not depend on B.)
+        const size_t nbr = (size_t)(B % NB), es = dtype == IMPACT_F32 ? 4 : 2;
+        auto whole_vectors = [&](size_t elems, size_t elem_bytes) {
+            return ((size_t)B * elems * elem_bytes) % 16 == 0 && (nbr * elems * elem_bytes) % 16 == 0;
+        };
+        const size_t Wd = dist == IMPACT_CATEGORICAL ? (size_t)A : 2 * (size_t)A;
+        if (!whole_vectors(Wd, 4)) fast = false;                                  // learner rows, gradient rows
+        if (!slot_major) {
+            if ((batch.target_dist || !cached) && !whole_vectors(Wd, es)) fast = false;
+            if (dist == IMPACT_DIAG_GAUSSIAN && !whole_vectors((size_t)A, es)) fast = false;
+        }
+    }
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
     if (slot_major) {

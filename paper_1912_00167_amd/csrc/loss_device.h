@@ -237,7 +237,9 @@ struct ChunkLoader {
     // rows: valid time rows (1..RWP); vectors of the missing rows re-read valid ones, so that every
     // load stays inside the tensor
     // slot_byte0: where each of the tile's trajectories starts in the plane (slot-major only)
-    __device__ __forceinline__ void plan(int B, int rows, const unsigned *slot_byte0, int lane)
+    // segv: 16-byte vectors of a time-major row segment that belong to the tile (fewer than SEGV in the
+    // ragged last tile of a batch; the others re-read the last valid one)
+    __device__ __forceinline__ void plan(int B, int rows, const unsigned *slot_byte0, int lane, int segv = SEGV)
     {
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
@@ -248,7 +250,7 @@ struct ChunkLoader {
                 offset[it] = slot_byte0[bl] + (unsigned)(min(v, last_vec) * VB);
             } else {
                 const int r = i / SEGV, v = i - r * SEGV;
-                offset[it] = (unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * ES)) + (unsigned)v * 16u;
+                offset[it] = (unsigned)min(r, rows - 1) * ((unsigned)B * (unsigned)(Wd * ES)) + (unsigned)min(v, segv - 1) * 16u;
             }
         }
     }
@@ -303,14 +305,15 @@ struct ChunkStorer {
     // FULL: all RWP rows are valid.  Every store instruction then executes with all lanes enabled, so the
     // number of stores in flight after this call is a compile-time constant; the wait that precedes the
     // next chunk's first use of prefetched data can then leave exactly these stores outstanding.
+    // Otherwise: rows valid rows and segv valid vectors per row segment (the ragged last tile of a batch).
     template <bool FULL>
-    __device__ __forceinline__ void store(char *base, const float *region, int rows, int lane) const
+    __device__ __forceinline__ void store(char *base, const float *region, int rows, int lane, int segv = SEGV) const
     {
         const int r = lane / LPR, v0 = lane % LPR;
         wave_lds_sync();   // every lane has written the values of its own step
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            const bool inside = SEGV % LPR == 0 || it < NIT - 1 || v0 + LPR * it < SEGV;
+            const bool inside = FULL ? true : v0 + LPR * it < segv;
             const uint4 x = *(const uint4 *)((const char *)region + from[it]);
             // written once and not read again by this kernel: a streaming store leaves the L2 to the loads
             if (FULL || (r < rows && inside)) __builtin_nontemporal_store(*(const v4u *)&x, (v4u *)(base + offset[it]));

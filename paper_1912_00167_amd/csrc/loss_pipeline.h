@@ -21,7 +21,8 @@ namespace impact {
 // fill the chip that way, the wavefronts of a compute unit drift apart in phase, and while some are
 // held up issuing loads into a full memory queue the others compute.
 template <class Policy, typename ST, bool SLOT, int NW>
-__global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
+void loss_static(const LossArgs a)
 {
     constexpr int W = Policy::W;                   // elements of a distribution tensor per step
     constexpr int ACT = Policy::ACT;               // elements of the action tensor per step; 0: one int32 index
@@ -69,14 +70,19 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     const int rl = step / NB, bl = step % NB, tl = wave * RWP + rl;
     const bool lead = part == 0;                   // the lane that stores the step's scalars
     const int tile = tile_of_block(blockIdx.x, gridDim.x);
-    const int b0 = tile * NB, b = b0 + bl;
+    // The last tile of a batch may hold fewer than NB trajectories.  Its missing lanes shadow the last real
+    // trajectory (every address stays inside the tensors) and drop their results; the tile takes the
+    // masked copy of the chunk body for all its chunks.
+    const int b0 = tile * NB, nb = min(NB, a.B - b0);
+    const bool mine = bl < nb;
+    const int b = b0 + min(bl, nb - 1);
     ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[CACHED ? 0 : wave], *r_tg = r_tg_all[TGT ? wave : 0];
     double *r_lp = r_lp_all[CACHED ? wave : 0];
 
     float bad = 0.f;
     // the slot indices travel while the table is computed
     int my_slot = 0;
-    if (SLOT && tid < NB) my_slot = a.slots[b0 + tid];
+    if (SLOT && tid < NB) my_slot = a.slots[b0 + min(tid, nb - 1)];
     exp64_table_init(exp_tbl, tid, 64 * NW);
     if (SLOT && tid < NB) {
         int s = my_slot;
@@ -105,11 +111,11 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     const int nchunk = (a.T + TCH - 1) / TCH;
     const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
     if (tail_rows > 0) {
-        ld_lrn.plan(a.B, tail_rows, nullptr, lane);
+        ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * 4 / 16);
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
-        if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane);
-        ld_dist.plan(a.B, tail_rows, slot_dist0, lane);
-        if (CACHED) ld_lp.plan(a.B, tail_rows, slot_lp0, lane);
+        if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
+        ld_dist.plan(a.B, tail_rows, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
+        if (CACHED) ld_lp.plan(a.B, tail_rows, slot_lp0, lane, nb);
         fetch_buffer_side(nchunk - 1);
     }
     if constexpr (PRE) {
@@ -194,10 +200,10 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)
     {
         fetch_scalars_tail(nchunk - 1);
-        if (ACT > 0) ld_act.plan(a.B, RWP, slot_act0, lane);
-        ld_dist.plan(a.B, RWP, slot_dist0, lane);
-        if (CACHED) ld_lp.plan(a.B, RWP, slot_lp0, lane);
-        ld_lrn.plan(a.B, RWP, nullptr, lane);
+        if (ACT > 0) ld_act.plan(a.B, RWP, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
+        ld_dist.plan(a.B, RWP, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
+        if (CACHED) ld_lp.plan(a.B, RWP, slot_lp0, lane, nb);
+        ld_lrn.plan(a.B, RWP, nullptr, lane, nb * W * 4 / 16);
         st_grad.plan(a.B, lane);
     }
     wait_dma_done();
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         const int t_base = c * TCH + wave * RWP;
         const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
-        const bool valid = !TAIL || t < a.T;
+        const bool valid = !TAIL || (t < a.T && mine);
         constexpr int par = Q;
         const size_t s_tm = (size_t)min(t, a.T - 1) * a.B + b;
 
@@ -283,7 +289,8 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
         if (c > 0) {
             fetch_buffer_side(c - 1);
             if (NLN == 2) fetch_learner(c - 1, r_ln_next);
-            fetch_scalars(c - 1);
+            if (TAIL) fetch_scalars_tail(c - 1);       // (clamped addresses: the tile may be ragged)
+            else fetch_scalars(c - 1);
         }
 
         if (rows > 0) {
@@ -291,7 +298,7 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
             double s, H, KL;
             Policy::learner(kept, r_ln + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
             char *gbase = st_grad.chunk_base(a.grad_dist, a.B, t_base, b0);
-            if (TAIL) st_grad.template store<false>(gbase, r_ln, rows, lane);
+            if (TAIL) st_grad.template store<false>(gbase, r_ln, rows, lane, nb * W * 4 / 16);
             else st_grad.template store<true>(gbase, r_ln, rows, lane);
 
             if (valid && lead) {
@@ -311,10 +318,17 @@ __global__ __launch_bounds__(64 * NW) void loss_static(const LossArgs a)
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    chunk(P0{}, std::true_type{}, nchunk - 1);
-    for (int c = nchunk - 2; c >= 0; c -= 2) {
-        chunk(P1{}, std::false_type{}, c);
-        if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
+    if (nb == NB) {
+        chunk(P0{}, std::true_type{}, nchunk - 1);
+        for (int c = nchunk - 2; c >= 0; c -= 2) {
+            chunk(P1{}, std::false_type{}, c);
+            if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
+        }
+    } else {
+        for (int c = nchunk - 1; c >= 0; c -= 2) {
+            chunk(P0{}, std::true_type{}, c);
+            if (c >= 1) chunk(P1{}, std::true_type{}, c - 1);
+        }
     }
     store_partials<NW>(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
