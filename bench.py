@@ -162,6 +162,10 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         t_g = timed(lambda i: binding.impact_buffer_gather(buf, slots[i % nq], dst), n_calls)
         t_f = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
                                                                       boot[i % nq], cfg, out=out, workspace=ws), n_calls)
+        out_p = binding.alloc_loss_out(T, B, W, packed=True)
+        t_p = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
+                                                                      boot[i % nq], cfg, out=out_p, workspace=ws), n_calls)
+        del out_p
         # host bookkeeping of one sample call (ring walk, counts), timed on its own
         s_np, c_np = np.empty(B, np.int32), np.empty(B, np.int32)
         n_samples = 200
@@ -178,7 +182,8 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         steps = T * B
         for line, us, bps in (("loss, time-major batch", t_tm, algorithmic_bytes_per_step(wl)),
                               ("gather alone", t_g, 2 * resident),
-                              ("fused gather + loss", t_f, algorithmic_bytes_per_step(wl))):
+                              ("fused gather + loss", t_f, algorithmic_bytes_per_step(wl)),
+                              ("fused, per-step scalars as packed records", t_p, algorithmic_bytes_per_step(wl))):
             gbs = bps * steps / us / 1e3
             print(f"| {wl.name} | {line} | {us:.1f} | {steps / us * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | "
                   f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
@@ -214,6 +219,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--packed-outputs", action="store_true",
+                    help="per-step scalars as one 16-byte record per step (a layout variant; not the default)")
     ap.add_argument("--series", metavar="FILE", help="also write the per-step kernel durations (ms, one per line) to FILE")
     ap.add_argument("--table", action="store_true",
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
@@ -238,7 +245,7 @@ def main() -> int:
     block = min(B, 4096)
     learner, values, boot = fill_ring(torch, binding, wl, buf, block)
     n_batches = len(learner)                       # distinct batches per pass over the ring
-    outs = [binding.alloc_loss_out(T, B, W) for _ in range(2)]
+    outs = [binding.alloc_loss_out(T, B, W, packed=args.packed_outputs) for _ in range(2)]
     workspace = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, T, B, wl.A), dtype=torch.uint8, device="cuda")
     cfg = binding.config_from_hyper(wl.hyper)
     stream = torch.cuda.current_stream()
@@ -254,7 +261,7 @@ def main() -> int:
     # unread events behind, and recording then slows down).
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(depth)]
     in_flight = [False] * depth
-    state = dict(step=0)
+    state = dict(step=0, outs=outs)
     kernel_times = []
     host_marks = []                                # host clock before and after each step's records and launch
 
@@ -276,7 +283,7 @@ def main() -> int:
         host_marks.append(time.perf_counter())
         pairs[j][0].record(stream)
         binding.impact_loss_fwd_bwd_from_buffer(buf, pinned[j], learner[q % n_batches], values[q % n_batches],
-                                                boot[q % n_batches], cfg, out=outs[i % 2], workspace=workspace,
+                                                boot[q % n_batches], cfg, out=state["outs"][i % 2], workspace=workspace,
                                                 stream=stream)
         pairs[j][1].record(stream)
         host_marks.append(time.perf_counter())
@@ -301,8 +308,29 @@ def main() -> int:
     wall = time.perf_counter() - t0
     for j in range(depth):
         retire(j, True)
-    gc.enable()
     assert len(kernel_times) == args.steps
+    main_times = list(kernel_times)
+
+    # The same step with the per-step scalars written as packed records (a layout variant of the outputs,
+    # not the default): a shorter run on the warm device, reported next to the headline figure.
+    variant = None
+    if not args.packed_outputs:
+        state["outs"] = [binding.alloc_loss_out(T, B, W, packed=True) for _ in range(2)]
+        n_var = min(args.steps, 256)
+        for _ in range(32):
+            one_step(False)
+        for j in range(depth):
+            retire(j, False)
+        del kernel_times[:]
+        for _ in range(n_var):
+            one_step(True)
+        torch.cuda.synchronize()
+        for j in range(depth):
+            retire(j, True)
+        variant = float(np.mean(kernel_times))
+        state["outs"] = outs
+    kernel_times = main_times
+    gc.enable()
     if args.series:
         with open(args.series, "w") as f:
             marks = host_marks[-2 * args.steps:]
@@ -310,7 +338,7 @@ def main() -> int:
                 since = (marks[2 * k] - marks[2 * k - 1]) * 1e3 if k else 0.0
                 f.write(f"{x:.4f} {(marks[2 * k + 1] - marks[2 * k]) * 1e3:.4f} {since:.4f}\n")
 
-    loss = outs[(state["step"] - 1) % 2]["loss5"].cpu().numpy()
+    loss = outs[(args.warmup + args.steps - 1) % 2]["loss5"].cpu().numpy()
     assert np.all(np.isfinite(loss)), f"non-finite loss {loss}"
     kernel_ms = float(np.mean(kernel_times))
     steps_per_call = T * B
@@ -327,14 +355,21 @@ def main() -> int:
         "dtype": "f64" if wl.dist == workloads.GAUSSIAN else "f32+f64",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} B={B} A={wl.A} {wl.dist}, {wl.storage} buffer fields, "
-                               f"ring {wl.num_slots} slots K={wl.K}, fused gather+loss+grad",
+                               f"ring {wl.num_slots} slots K={wl.K}, fused gather+loss+grad"
+                               + (", per-step scalars as packed records" if args.packed_outputs else ""),
                    "algorithmic_bytes_per_step": algorithmic_bytes_per_step(wl),
                    "host_issue_ms_per_step": issued * 1e3 / args.steps,
                    "loss5": [float(v) for v in loss]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if args.packed_outputs else MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)"},
     }
+    if variant is not None:
+        result["variants"] = {"packed_step_outputs": {
+            "kernel_ms": variant, "frac": bytes_per_call / (variant * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "what": "grad_values, vs, adv written as one 16-byte record per step (whole lines per wavefront) "
+                    "instead of three [T][B] tensors; same algorithmic bytes"}}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, max(8, min(B, 4096)))
     print(json.dumps(result))

@@ -119,13 +119,21 @@ typedef struct {
  *   grad_learner_dist  [T][B][W]  dL/d(learner logits) or dL/d(mean | log-std)
  *   grad_values        [T][B]     dL/dV
  *   vs, adv            [T][B]     value targets and advantages; either may be NULL
- *   loss5              [5]        {total, policy, value, mean entropy, mean KL} */
+ *   loss5              [5]        {total, policy, value, mean entropy, mean KL}
+ *   step_outputs       [T][B][4]  or NULL.  If given, the three per-step scalars leave as one
+ *                                 16-byte record {dL/dV, vs, adv, 0} per step and grad_values, vs
+ *                                 and adv are not written (they may be NULL).  The kernels own 8
+ *                                 neighbouring trajectories per wavefront, so a row of records is
+ *                                 a whole 128-byte line per wavefront where the three separate
+ *                                 tensors each receive a 32-byte piece of one; consumers read the
+ *                                 fields as strided views (dL/dV = element 0 of every record). */
 typedef struct {
     float *grad_learner_dist;
     float *grad_values;
     float *vs;
     float *adv;
     float *loss5;
+    float *step_outputs;
 } impact_loss_out_t;
 
 /* Library version, "major.minor". */

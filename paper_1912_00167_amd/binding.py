@@ -70,7 +70,7 @@ class impact_batch_t(ctypes.Structure):
 
 class impact_loss_out_t(ctypes.Structure):
     _fields_ = [("grad_learner_dist", ctypes.c_void_p), ("grad_values", ctypes.c_void_p), ("vs", ctypes.c_void_p),
-                ("adv", ctypes.c_void_p), ("loss5", ctypes.c_void_p)]
+                ("adv", ctypes.c_void_p), ("loss5", ctypes.c_void_p), ("step_outputs", ctypes.c_void_p)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -311,7 +311,15 @@ def impact_loss_workspace_bytes(dist, T: int, B: int, A: int) -> int:
     return int(load().impact_loss_workspace_bytes(dist_code(dist), T, B, A))
 
 
-def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = True) -> Dict[str, torch.Tensor]:
+def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = True,
+                   packed: bool = False) -> Dict[str, torch.Tensor]:
+    """packed: the per-step scalars as one record {dL/dV, vs, adv, 0} per step ("step_outputs", [T][B][4]);
+    grad_values, vs and adv are then strided views of it."""
+    if packed:
+        rec = torch.empty((T, B, 4), dtype=torch.float32, device=device)
+        return dict(grad_dist=torch.empty((T, B, W), dtype=torch.float32, device=device), step_outputs=rec,
+                    grad_values=rec[..., 0], vs=rec[..., 1], adv=rec[..., 2],
+                    loss5=torch.empty(5, dtype=torch.float32, device=device))
     out = dict(grad_dist=torch.empty((T, B, W), dtype=torch.float32, device=device),
                grad_values=torch.empty((T, B), dtype=torch.float32, device=device),
                loss5=torch.empty(5, dtype=torch.float32, device=device))
@@ -322,8 +330,10 @@ def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = T
 
 
 def _out_struct(out: Dict[str, torch.Tensor]) -> impact_loss_out_t:
+    if out.get("step_outputs") is not None:
+        return impact_loss_out_t(_ptr(out["grad_dist"]), None, None, None, _ptr(out["loss5"]), _ptr(out["step_outputs"]))
     return impact_loss_out_t(_ptr(out["grad_dist"]), _ptr(out["grad_values"]), _ptr(out.get("vs")),
-                             _ptr(out.get("adv")), _ptr(out["loss5"]))
+                             _ptr(out.get("adv")), _ptr(out["loss5"]), None)
 
 
 def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, bootstrap: torch.Tensor,

@@ -408,10 +408,12 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     const bool cached = batch.logp != nullptr;
     if (!cached && (!batch.worker_dist || !batch.target_dist)) return IMPACT_ERR_INVALID_ARG;
     if (cached && !batch.target_dist && cfg && cfg->kl_coeff != 0.f) return IMPACT_ERR_INVALID_ARG;
-    if (!out->grad_learner_dist || !out->grad_values || !out->loss5 || !workspace) return IMPACT_ERR_INVALID_ARG;
+    if (!out->grad_learner_dist || !out->loss5 || !workspace) return IMPACT_ERR_INVALID_ARG;
+    if (!out->grad_values && !out->step_outputs) return IMPACT_ERR_INVALID_ARG;
     if (workspace_bytes < impact_loss_workspace_bytes(dist, T, B, A)) return IMPACT_ERR_INVALID_ARG;
     const void *ptrs[] = {learner, values, bootstrap, cached ? nullptr : batch.worker_dist, batch.target_dist,
-                          batch.actions, batch.rewards, batch.logp, out->grad_learner_dist, out->grad_values, workspace};
+                          batch.actions, batch.rewards, batch.logp, out->grad_learner_dist, out->grad_values,
+                          out->step_outputs, workspace};
     for (const void *p : ptrs)
         if (p && !aligned16(p)) return IMPACT_ERR_INVALID_ARG;
     if ((out->vs && !aligned16(out->vs)) || (out->adv && !aligned16(out->adv))) return IMPACT_ERR_INVALID_ARG;
@@ -435,6 +437,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.inv_M = 1.0 / M;
     a.grad_dist = out->grad_learner_dist; a.grad_values = out->grad_values;
     a.vs = out->vs; a.adv = out->adv;
+    a.step_out = reinterpret_cast<float4 *>(out->step_outputs);
     a.partials = static_cast<float *>(workspace);
     a.done_count = done_count; a.loss5 = out->loss5;
 

@@ -52,6 +52,7 @@ struct LossArgs {
     float *grad_values;       // [T][B]
     float *vs;                // [T][B] or null
     float *adv;               // [T][B] or null
+    float4 *step_out;         // [T][B] records {dL/dV, vs, adv, 0} in place of the three tensors above, or null
     float *partials;          // [num_tiles][PARTIAL_STRIDE]
     // completion counter for the in-kernel final reduction (zero between launches), or null: then the
     // caller launches the reduction; loss5 is only written by the kernel in the first case

@@ -174,9 +174,14 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                     gd[A + d] = (float)(g * (diff * diff * E - 1.0) + ck * (1.0 - q) - ce);
                 }
             }
-            a.grad_values[s_tm] = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
-            if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
-            if (a.adv) a.adv[s_tm] = (float)adv;
+            const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
+            if (a.step_out) {
+                a.step_out[s_tm] = make_float4(gV, (float)((double)V + adv), (float)adv, 0.f);
+            } else {
+                a.grad_values[s_tm] = gV;
+                if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
+                if (a.adv) a.adv[s_tm] = (float)adv;
+            }
             sum_s += (float)s;
             sum_v += (float)(0.5 * adv * adv);
             sum_h += (float)H;

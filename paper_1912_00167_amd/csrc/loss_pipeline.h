@@ -269,7 +269,13 @@ void loss_static(const LossArgs a)
         if (valid && lead) {
             const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);        // V - vs = -adv
             const float vs_t = (float)((double)V + adv), adv_t = (float)adv;
-            if (TAIL) {
+            if (a.step_out) {
+                // one 16-byte record per step: a tile's row is then a whole 128-byte line, where the three
+                // separate [T][B] tensors each take a 32-byte piece of one
+                const float4 rec = make_float4(gV, vs_t, adv_t, 0.f);
+                if (TAIL) a.step_out[s_tm] = rec;
+                else *(float4 *)(uniform_ptr(a.step_out + ((size_t)t_base * a.B + b0)) + step_tm * 16u) = rec;
+            } else if (TAIL) {
                 a.grad_values[s_tm] = gV;
                 if (a.vs) a.vs[s_tm] = vs_t;
                 if (a.adv) a.adv[s_tm] = adv_t;

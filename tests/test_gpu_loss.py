@@ -96,6 +96,28 @@ def test_impala_objective_with_the_learner_in_the_targets_place(env, name, flags
     check_against_oracle(wl, x, got, hyper=h, label=f"impala objective {name}")
 
 
+@pytest.mark.parametrize("name,kw", [("C1", {}), ("C3", dict(B=64)), ("C2", dict(T=50, B=10)), ("C2", dict(T=33, B=37, A=5)),
+                                     ("C5", dict(T=40, B=2048))])
+def test_per_step_scalars_as_packed_records(env, name, kw):
+    """grad_values, vs and adv as one record {dL/dV, vs, adv, 0} per step: the same numbers, bit for bit, as in
+    the three separate tensors, and the oracle's within tolerance."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], storage="f32", **kw)
+    x = workloads.make_batch(wl, stream=23)
+    say(f"case packed records {name} {kw}")
+    d = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in x.items()}
+    cfg = binding.config_from_hyper(wl.hyper)
+    plain = binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg)
+    packed = binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg,
+                                         out=binding.alloc_loss_out(wl.T, wl.B, wl.W, packed=True))
+    torch.cuda.synchronize()
+    for k in ("grad_dist", "grad_values", "vs", "adv", "loss5"):
+        assert torch.equal(plain[k], packed[k].contiguous()), k
+    assert torch.all(packed["step_outputs"][..., 3] == 0)
+    got = {k: packed[k].contiguous().cpu().numpy() for k in ("grad_dist", "grad_values", "vs", "adv", "loss5")}
+    check_against_oracle(wl, x, got, label=f"packed records {name}")
+
+
 def test_optional_outputs_may_be_null(env):
     torch, binding = env
     wl = shape_workload(workloads.C2, B=16)
