@@ -275,23 +275,32 @@ struct ChunkLoader {
 };
 
 // LDS region ([row][bl][Wd] floats) -> time-major global tensor [T][B][Wd], 16-byte stores; the same
-// split into a wave-uniform chunk address and constant per-lane offsets.  64 / RWP lanes walk each row.
+// split into a wave-uniform chunk address and constant per-lane offsets.  The lanes walk the chunk's
+// vectors row by row, so that one store instruction covers 1 KB of consecutive addresses of a row
+// (whole 128-byte lines completed by a single instruction) before it moves on to the next row.
 template <int Wd, int RWP>
 struct ChunkStorer {
-    static constexpr int LPR = 64 / RWP;
-    static constexpr int SEGV = NB * Wd * 4 / 16;
-    static constexpr int NIT = (SEGV + LPR - 1) / LPR;             // store instructions per chunk
+    static constexpr int SEGV = NB * Wd * 4 / 16;                  // vectors per row segment
+    static constexpr int TOTAL = RWP * SEGV;                       // vectors per chunk
+    static constexpr int NIT = (TOTAL + 63) / 64;                  // store instructions per chunk
 
     unsigned offset[NIT];      // into the tensor, from the chunk's address
     unsigned from[NIT];        // into the LDS region
 
+    __device__ __forceinline__ static void split(int lane, int it, int &r, int &v)
+    {
+        // lanes past the end of the chunk repeat its last vector
+        const int g = (TOTAL % 64 == 0 || it < NIT - 1) ? lane + 64 * it : min(lane + 64 * it, TOTAL - 1);
+        r = g / SEGV;
+        v = g - r * SEGV;
+    }
+
     __device__ __forceinline__ void plan(int B, int lane)
     {
-        const int r = lane / LPR, v0 = lane % LPR;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            // lanes past the end of a row segment repeat its last vector
-            const int v = (SEGV % LPR == 0 || it < NIT - 1) ? v0 + LPR * it : min(v0 + LPR * it, SEGV - 1);
+            int r, v;
+            split(lane, it, r, v);
             offset[it] = (unsigned)r * ((unsigned)B * (unsigned)(Wd * 4)) + (unsigned)v * 16u;
             from[it] = (unsigned)(r * SEGV + v) * 16u;
         }
@@ -309,14 +318,15 @@ struct ChunkStorer {
     template <bool FULL>
     __device__ __forceinline__ void store(char *base, const float *region, int rows, int lane, int segv = SEGV) const
     {
-        const int r = lane / LPR, v0 = lane % LPR;
         wave_lds_sync();   // every lane has written the values of its own step
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            const bool inside = FULL ? true : v0 + LPR * it < segv;
+            int r, v;
+            split(lane, it, r, v);
+            const bool inside = FULL ? true : (lane + 64 * it < TOTAL && r < rows && v < segv);
             const uint4 x = *(const uint4 *)((const char *)region + from[it]);
             // written once and not read again by this kernel: a streaming store leaves the L2 to the loads
-            if (FULL || (r < rows && inside)) __builtin_nontemporal_store(*(const v4u *)&x, (v4u *)(base + offset[it]));
+            if (inside) __builtin_nontemporal_store(*(const v4u *)&x, (v4u *)(base + offset[it]));
         }
     }
 };
