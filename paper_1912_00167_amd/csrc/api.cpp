@@ -376,7 +376,10 @@ impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int3
 size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A)
 {
     if ((dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) || T < 1 || B < 1 || A < 1) return 0;
-    return align_up((size_t)num_tiles(B) * PARTIAL_STRIDE * sizeof(float), 256);
+    // per-tile partial sums; for small batches per (tile, time segment), plus the segments' scan pairs
+    const size_t tiles = (size_t)num_tiles(B);
+    if (tiles > SEG_MAX_TILES) return align_up(tiles * PARTIAL_STRIDE * sizeof(float), 256);
+    return align_up(tiles * SEG_MAX * PARTIAL_STRIDE * sizeof(float), 256) + (size_t)SEG_MAX * B * 2 * sizeof(double);
 }
 
 static bool config_ok(const impact_loss_config_t *c)
@@ -439,6 +442,10 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.vs = out->vs; a.adv = out->adv;
     a.step_out = reinterpret_cast<float4 *>(out->step_outputs);
     a.partials = static_cast<float *>(workspace);
+    a.num_segs = 1;
+    if (num_tiles(B) <= SEG_MAX_TILES)
+        a.seg_agg = reinterpret_cast<double *>(static_cast<char *>(workspace) +
+                                               align_up((size_t)num_tiles(B) * SEG_MAX * PARTIAL_STRIDE * sizeof(float), 256));
     a.done_count = done_count; a.loss5 = out->loss5;
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
@@ -482,7 +489,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     }
     if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
     if (!done_count) {
-        ReduceArgs r{a.partials, num_tiles(B), 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
+        ReduceArgs r{a.partials, num_tiles(B) * a.num_segs, 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
         launch_reduce(r, s);
     }
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;

@@ -54,6 +54,13 @@ struct LossArgs {
     float *adv;               // [T][B] or null
     float4 *step_out;         // [T][B] records {dL/dV, vs, adv, 0} in place of the three tensors above, or null
     float *partials;          // [num_tiles][PARTIAL_STRIDE]
+    // Long trajectories of a small batch are cut into num_segs time segments of seg_chunks chunks each,
+    // one workgroup per (tile, segment).  The scan is affine in its carry, acc_t = A_t + P_t * carry, so a
+    // first launch (phase 1) only finds every segment's A and P at its first step (seg_agg[seg][b][2]) and a
+    // second launch (phase 2) starts each segment from the carry that the later segments' pairs compose to.
+    // num_segs = 1, phase = 0: the whole trajectory in one workgroup.
+    int num_segs, seg_chunks, phase;
+    double *seg_agg;
     // completion counter for the in-kernel final reduction (zero between launches), or null: then the
     // caller launches the reduction; loss5 is only written by the kernel in the first case
     unsigned *done_count;
@@ -68,15 +75,20 @@ struct ReduceArgs {
     float *loss5;
 };
 
-inline int num_tiles(int B) { return (B + NB - 1) / NB; }
+__host__ __device__ inline int num_tiles(int B) { return (B + NB - 1) / NB; }
+
+// Time segments (see LossArgs): at most SEG_MAX per trajectory, and only for batches of at most
+// SEG_MAX_TILES tiles, which bounds the workspace the pairs and the per-segment partial sums need.
+constexpr int SEG_MAX = 64, SEG_MAX_TILES = 128;
 
 // Launchers (defined in the .hip files).  `slot_major` selects the fused-gather addressing.
 // Return false when no specialised kernel exists for (A, alignment): the caller then uses the generic one.
-bool launch_loss_cat_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
-bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+// They set a.num_segs: the partial sums to reduce are num_tiles * num_segs.
+bool launch_loss_cat_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
+bool launch_loss_gauss_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 // ... on cached log-probabilities (a.logp; with the KL term if a.target is there)
-bool launch_loss_cat_cached(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
-bool launch_loss_gauss_cached(int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
+bool launch_loss_cat_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
+bool launch_loss_gauss_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_reduce(const ReduceArgs &r, hipStream_t s);
 void launch_zero_words(unsigned *p, int n, hipStream_t s);

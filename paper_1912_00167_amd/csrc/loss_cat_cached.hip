@@ -4,7 +4,7 @@
 namespace impact {
 
 template <int MODE>
-static bool launch_mode(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+static bool launch_mode(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
     switch (a.A) {
     case 4: launch_loss_static<CatPolicy<4, 1, MODE>>(dtype, slot_major, a, s); return true;
@@ -15,7 +15,7 @@ static bool launch_mode(int dtype, bool slot_major, const LossArgs &a, hipStream
     }
 }
 
-bool launch_loss_cat_cached(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+bool launch_loss_cat_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
     return a.target ? launch_mode<POLICY_CACHED_TARGET>(dtype, slot_major, a, s)
                     : launch_mode<POLICY_CACHED>(dtype, slot_major, a, s);

@@ -244,7 +244,7 @@ struct ChunkLoader {
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int i = lane + 64 * it;
-            if (SLOT) {
+            if constexpr (SLOT) {
                 const int last_vec = (rows * Wd * ES - 1) / VB;
                 const int bl = min(i / VPT, NB - 1), v = i - (i / VPT) * VPT;
                 offset[it] = slot_byte0[bl] + (unsigned)(min(v, last_vec) * VB);
@@ -372,8 +372,9 @@ __device__ __forceinline__ void surrogate(const LossArgs &a, double R, double ad
 // Backward scan of one chunk of TCH time steps.  sd/sg hold delta and gamma*lambda*c for
 // TCH x NB steps (zero for steps past T); threads tid < NB each run one trajectory and leave
 // the accumulated advantage in sd.  Two workgroup barriers.
+// coeff, if given, is multiplied by the chunk's product of gamma*lambda*c (the carry's coefficient).
 template <int TCH, int NW = NWAVES>
-__device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid)
+__device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double &carry, int tid, double *coeff = nullptr)
 {
     // a single-wavefront workgroup needs no hardware barrier
     if (NW == 1) wave_lds_sync(); else lds_barrier();
@@ -385,6 +386,12 @@ __device__ __forceinline__ void chunk_scan(double *sd, const double *sg, double 
             sd[j * NB + tid] = acc;
         }
         carry = acc;
+        if (coeff) {
+            double p = *coeff;
+#pragma unroll 8
+            for (int j = TCH - 1; j >= 0; --j) p *= sg[j * NB + tid];
+            *coeff = p;
+        }
     }
     if (NW == 1) wave_lds_sync(); else lds_barrier();
 }

@@ -4,7 +4,7 @@
 namespace impact {
 
 // Action dimensions of the MuJoCo tasks the paper trains on (Hopper 3, HalfCheetah 6, Humanoid 17).
-bool launch_loss_gauss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+bool launch_loss_gauss_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
     switch (a.A) {
     case 3: launch_loss_static<GaussPolicy<3, 1>>(dtype, slot_major, a, s); return true;

@@ -69,7 +69,13 @@ void loss_static(const LossArgs a)
     const int step = lane / P, part = lane % P;    // step within the wavefront, share of its dimensions
     const int rl = step / NB, bl = step % NB, tl = wave * RWP + rl;
     const bool lead = part == 0;                   // the lane that stores the step's scalars
-    const int tile = tile_of_block(blockIdx.x, gridDim.x);
+    // one workgroup per (tile, time segment); a single segment unless the launcher cut the trajectories
+    // (only the workgroup shape of small batches is ever launched that way: the others carry none of it)
+    constexpr bool SEGS = NW == NWAVES;
+    const int ntiles = SEGS ? num_tiles(a.B) : (int)gridDim.x;
+    const int seg = SEGS ? (int)blockIdx.x / ntiles : 0;
+    const int tile = tile_of_block((int)blockIdx.x - seg * ntiles, ntiles);
+    const bool agg_only = SEGS && a.phase == 1;    // first launch of a segmented step: the scan's pair only
     // The last tile of a batch may hold fewer than NB trajectories.  Its missing lanes shadow the last real
     // trajectory (every address stays inside the tensors) and drop their results; the tile takes the
     // masked copy of the chunk body for all its chunks.
@@ -108,11 +114,14 @@ void loss_static(const LossArgs a)
         if (TGT) ld_dist.issue(ld_dist.chunk_base(a.target, a.B, t_base, b0), r_tg, lane);
         if (CACHED) ld_lp.issue(ld_lp.chunk_base(a.logp, a.B, t_base, b0), r_lp, lane);
     };
-    const int nchunk = (a.T + TCH - 1) / TCH;
+    // chunks c_lo .. nchunk - 1 of the trajectory are this workgroup's, walked downwards
+    const int nchunk = SEGS && a.num_segs > 1 ? min((a.T + TCH - 1) / TCH, (seg + 1) * a.seg_chunks) : (a.T + TCH - 1) / TCH;
+    const int c_lo = SEGS && a.num_segs > 1 ? seg * a.seg_chunks : 0;
     const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
     if (tail_rows > 0) {
         ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * 4 / 16);
-        ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
+        if (!agg_only)
+            ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
         if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
         ld_dist.plan(a.B, tail_rows, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
         if (CACHED) ld_lp.plan(a.B, tail_rows, slot_lp0, lane, nb);
@@ -155,7 +164,15 @@ void loss_static(const LossArgs a)
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, c * TCH + wave * RWP, b0), region, lane);
     };
 
-    double carry = 0.0;
+    double carry = 0.0, coeff = 1.0;               // the scan's carry; phase 1: the coefficient of the carry-in
+    if (SEGS && a.phase == 2 && tid < NB) {
+        // the accumulated advantage at the first step after this segment: compose the later segments' pairs
+        const int bt = b0 + min(tid, nb - 1);
+        for (int j = a.num_segs - 1; j > seg; --j) {
+            const double *pair = a.seg_agg + ((size_t)j * a.B + bt) * 2;
+            carry = __builtin_fma(pair[1], carry, pair[0]);
+        }
+    }
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
     // The per-step scalars of a chunk are loaded one chunk ahead as well, into registers: a load issued
     // at the start of a chunk would have to wait for the previous chunk's gradient stores, since
@@ -221,6 +238,7 @@ void loss_static(const LossArgs a)
         const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
         const bool valid = !TAIL || (t < a.T && mine);
+        const bool skip = TAIL && agg_only;            // phase 1 (always on this copy of the body): no learner side
         constexpr int par = Q;
         const size_t s_tm = (size_t)min(t, a.T - 1) * a.B + b;
 
@@ -263,10 +281,10 @@ void loss_static(const LossArgs a)
             sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
             sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
         }
-        chunk_scan<TCH, NW>(sd[par], sg[par], carry, tid);
+        chunk_scan<TCH, NW>(sd[par], sg[par], carry, tid, SEGS && skip ? &coeff : nullptr);
         const double adv = sd[par][tl * NB + bl];
         // the per-step outputs that depend on the scan alone leave now, ahead of the next chunk's loads
-        if (valid && lead) {
+        if (valid && lead && !skip) {
             const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);        // V - vs = -adv
             const float vs_t = (float)((double)V + adv), adv_t = (float)adv;
             if (a.step_out) {
@@ -292,14 +310,14 @@ void loss_static(const LossArgs a)
         // that they fly during this chunk's learner pass.
         wave_lds_sync();
         wait_lds_reads_done();
-        if (c > 0) {
+        if (c > c_lo) {
             fetch_buffer_side(c - 1);
-            if (NLN == 2) fetch_learner(c - 1, r_ln_next);
+            if (NLN == 2 && !skip) fetch_learner(c - 1, r_ln_next);
             if (TAIL) fetch_scalars_tail(c - 1);       // (clamped addresses: the tile may be ragged)
             else fetch_scalars(c - 1);
         }
 
-        if (rows > 0) {
+        if (rows > 0 && !skip) {
             // ---- learner: ratio, surrogate, entropy, KL; gradients replace the learner's rows in LDS ----
             double s, H, KL;
             Policy::learner(kept, r_ln + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
@@ -318,32 +336,38 @@ void loss_static(const LossArgs a)
             // the gradients have left the learner region: start the next chunk's learner load into it
             wave_lds_sync();
             wait_lds_reads_done();
-            if (c > 0) fetch_learner(c - 1, r_ln_next);
+            if (c > c_lo && !skip) fetch_learner(c - 1, r_ln_next);
         }
         if (TAIL) wait_dma_done();   // the number of stores just issued varies: drain them
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    if (nb == NB) {
+    if (nb == NB && !agg_only) {
         chunk(P0{}, std::true_type{}, nchunk - 1);
-        for (int c = nchunk - 2; c >= 0; c -= 2) {
+        for (int c = nchunk - 2; c >= c_lo; c -= 2) {
             chunk(P1{}, std::false_type{}, c);
-            if (c >= 1) chunk(P0{}, std::false_type{}, c - 1);
+            if (c > c_lo) chunk(P0{}, std::false_type{}, c - 1);
         }
     } else {
-        for (int c = nchunk - 1; c >= 0; c -= 2) {
+        for (int c = nchunk - 1; c >= c_lo; c -= 2) {
             chunk(P0{}, std::true_type{}, c);
-            if (c >= 1) chunk(P1{}, std::true_type{}, c - 1);
+            if (c > c_lo) chunk(P1{}, std::true_type{}, c - 1);
         }
     }
-    store_partials<NW>(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    if (agg_only) {
+        // acc at this segment's first step = carry (found with carry-in 0) + coeff * carry-in
+        if (tid < nb) {
+            double *pair = a.seg_agg + ((size_t)seg * a.B + b0 + tid) * 2;
+            pair[0] = carry;
+            pair[1] = coeff;
+        }
+        return;
+    }
+    store_partials<NW>(red, a, tile + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
 
-// Workgroup shape by batch size: the fewer tiles, the more wavefronts share one, so that a SIMD has
-// about two wavefronts to switch between; single-wavefront workgroups once there are 8 tiles per compute
-// unit (and, for the fused form, the trajectory fits the preload arrays).
-inline int waves_per_tile(const LossArgs &a, bool slot_major)
+inline int compute_units()
 {
     static const int cus = [] {
         int dev = 0, n = 0;
@@ -352,6 +376,15 @@ inline int waves_per_tile(const LossArgs &a, bool slot_major)
             n = 256;
         return n;
     }();
+    return cus;
+}
+
+// Workgroup shape by batch size: the fewer tiles, the more wavefronts share one, so that a SIMD has
+// about two wavefronts to switch between; single-wavefront workgroups once there are 8 tiles per compute
+// unit (and, for the fused form, the trajectory fits the preload arrays).
+inline int waves_per_tile(const LossArgs &a, bool slot_major)
+{
+    const int cus = compute_units();
     const int tiles = num_tiles(a.B);
     if (tiles >= 8 * cus && (!slot_major || a.T <= T_PRELOAD)) return 1;
     if (tiles >= 4 * cus) return 2;
@@ -359,20 +392,34 @@ inline int waves_per_tile(const LossArgs &a, bool slot_major)
 }
 
 template <class Policy, int NW>
-void launch_loss_static_nw(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
-    const dim3 grid(num_tiles(a.B)), block(64 * NW);
-    if (dtype == IMPACT_F32) {
-        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, true, NW>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_static<Policy, float, false, NW>), grid, block, 0, s, a);
-    } else {
-        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, true, NW>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_static<Policy, bf16_t, false, NW>), grid, block, 0, s, a);
+    // Few tiles and many chunks: a workgroup would walk its trajectories' chunks one after the other, each
+    // a chain of memory latencies, on a mostly idle chip.  Cut the time axis into segments then (two
+    // launches, see LossArgs), aiming at about two workgroups per compute unit and at least two chunks each.
+    constexpr int TCH = NW * (64 / Policy::LANES / NB);
+    const int tiles = num_tiles(a.B), nchunk = (a.T + TCH - 1) / TCH;
+    a.num_segs = 1; a.seg_chunks = nchunk; a.phase = 0;
+    if (NW == NWAVES && a.seg_agg && tiles <= SEG_MAX_TILES && nchunk >= 8) {
+        const int want = max(1, min(min(SEG_MAX, 2 * compute_units() / tiles), nchunk / 2));
+        a.seg_chunks = (nchunk + want - 1) / want;
+        a.num_segs = (nchunk + a.seg_chunks - 1) / a.seg_chunks;
+    }
+    const dim3 grid(tiles * a.num_segs), block(64 * NW);
+    for (int phase = a.num_segs > 1 ? 1 : 0; phase <= (a.num_segs > 1 ? 2 : 0); ++phase) {
+        a.phase = phase;
+        if (dtype == IMPACT_F32) {
+            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, true, NW>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((loss_static<Policy, float, false, NW>), grid, block, 0, s, a);
+        } else {
+            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, true, NW>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((loss_static<Policy, bf16_t, false, NW>), grid, block, 0, s, a);
+        }
     }
 }
 
 template <class Policy>
-void launch_loss_static(int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
+void launch_loss_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
     switch (waves_per_tile(a, slot_major)) {
     case 1: launch_loss_static_nw<Policy, 1>(dtype, slot_major, a, s); break;

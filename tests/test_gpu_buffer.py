@@ -176,6 +176,10 @@ FUSED = [
     ("C5", dict(T=50, B=64, num_slots=128), 128, 64),                 # D = 17 bf16: 3400 and 1700 bytes
     ("C5", dict(T=33, B=64, num_slots=128, storage="f32"), 128, 64),  # D = 17 fp32: 4488 and 2244 bytes
     ("C2", dict(T=1000, B=64, A=6, num_slots=64), 64, 64),            # a long trajectory: 32 chunks and more
+    # long trajectories of a small batch: time segments (two launches), fused
+    ("C3", dict(T=1024, B=32, num_slots=64), 64, 32),
+    ("C5", dict(T=700, B=20, num_slots=32), 32, 20),
+    ("C2", dict(T=400, B=24, num_slots=32, storage="bf16"), 32, 24),
     # batches that end in a ragged tile of the specialised kernels
     ("C2", dict(T=50, B=10, num_slots=40), 40, 10),                   # fragments of 50 steps, 500 steps per batch
     ("C4", dict(T=23, B=1028, num_slots=2048, storage="bf16"), 2048, 1028),

@@ -26,6 +26,7 @@ CASES = [
     ("C3", dict(T=17, B=64, num_slots=128), "f32"), ("C5", dict(T=24, B=64, num_slots=128), "bf16"),
     ("C2", dict(T=9, B=21, A=7, num_slots=40), "f32"),                     # ragged batch, generic kernels
     ("C2", dict(T=50, B=10, num_slots=40), "f32"), ("C5", dict(T=30, B=20, num_slots=64), "bf16"),   # ragged tile
+    ("C3", dict(T=512, B=16, num_slots=32), "f32"), ("C2", dict(T=300, B=10, num_slots=32), "bf16"), # time segments
     # batches large enough for single-wavefront tiles (2048 of them) and for two wavefronts per tile
     ("C5", dict(T=22, B=16384, num_slots=16384), "bf16"), ("C4", dict(T=21, B=8192, num_slots=8192), "f32"),
     ("C3", dict(T=13, B=16384, num_slots=16384), "f32"), ("C4", dict(T=50, A=9, B=16384, num_slots=16384), "bf16"),

@@ -118,6 +118,35 @@ def test_per_step_scalars_as_packed_records(env, name, kw):
     check_against_oracle(wl, x, got, label=f"packed records {name}")
 
 
+LONG = [
+    ("gaussian", 1024, 32, 6, {}), ("gaussian", 1024, 32, 17, dict(lam=0.97, c_bar=0.8)),      # the MuJoCo table's shape
+    ("categorical", 600, 16, 18, {}), ("categorical", 333, 10, 18, dict(lam=0.9)),             # ragged tile as well
+    ("gaussian", 257, 8, 3, dict(rho_bar=2.0, c_bar=1.5)), ("categorical", 2000, 64, 6, dict(ratio_mode=1)),
+    ("categorical", 129, 8, 4, {}),
+]
+
+
+@pytest.mark.parametrize("dist,T,Bn,A,hyper", LONG)
+@pytest.mark.parametrize("packed", [False, True], ids=["separate", "packed"])
+def test_long_trajectories_of_a_small_batch(env, dist, T, Bn, A, hyper, packed):
+    """Few tiles and many chunks: the time axis is cut into segments that run side by side, each started from
+    the carry its successors compose to (the scan is affine in the carry).  Same results as ever."""
+    torch, binding = env
+    base = workloads.C2 if dist == "categorical" else workloads.C3
+    wl = shape_workload(base, T=T, B=Bn, A=A, storage="f32")
+    h = replace(wl.hyper, **hyper)
+    x = workloads.make_batch(wl, stream=T + Bn)
+    # some episode ends, so that the carry is cut inside segments and at their borders
+    x["dones"][::97] = 1
+    say(f"case long {dist} T={T} B={Bn} A={A} {hyper} packed={packed}")
+    d = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in x.items()}
+    out = binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, binding.config_from_hyper(h),
+                                      out=binding.alloc_loss_out(T, Bn, wl.W, packed=packed))
+    torch.cuda.synchronize()
+    got = {k: out[k].contiguous().cpu().numpy() for k in ("grad_dist", "grad_values", "vs", "adv", "loss5")}
+    check_against_oracle(wl, x, got, hyper=h, label=f"long {dist} T{T} B{Bn} A{A}")
+
+
 def test_optional_outputs_may_be_null(env):
     torch, binding = env
     wl = shape_workload(workloads.C2, B=16)
