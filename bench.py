@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 # HBM bytes per launch of the fused loss kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the
 # same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md, ..._cat18_C4_fused.md).  Tied to the
 # kernel as profiled: to be set to None whenever the kernel changes until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"C5": 1.0493e9, "C4": 2.670e8}
+MEASURED_TRAFFIC_BYTES = {"C5": 1.0341e9, "C4": 2.655e8}
 
 
 def algorithmic_bytes_per_step(wl, cached=None) -> int:
@@ -221,6 +221,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--packed-outputs", action="store_true",
                     help="per-step scalars as one 16-byte record per step (a layout variant; not the default)")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="time the headline configuration only (for profiler runs: one kind of launch in the trace)")
     ap.add_argument("--series", metavar="FILE", help="also write the per-step kernel durations (ms, one per line) to FILE")
     ap.add_argument("--table", action="store_true",
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
@@ -314,7 +316,7 @@ def main() -> int:
     # The same step with the per-step scalars written as packed records (a layout variant of the outputs,
     # not the default): a shorter run on the warm device, reported next to the headline figure.
     variant = None
-    if not args.packed_outputs:
+    if not args.packed_outputs and not args.no_variants:
         state["outs"] = [binding.alloc_loss_out(T, B, W, packed=True) for _ in range(2)]
         n_var = min(args.steps, 256)
         for _ in range(32):

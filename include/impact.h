@@ -220,7 +220,9 @@ impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int3
 /* ---------------------------------- loss ----------------------------------- */
 
 /* Bytes of device workspace the loss calls need for a batch of this shape
- * (partial sums of the five loss terms; 0 on invalid arguments). */
+ * (partial sums of the five loss terms per tile of 8 trajectories; for small
+ * batches, whose long trajectories are processed in time segments, per tile and
+ * segment, plus two doubles per trajectory and segment; 0 on invalid arguments). */
 size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A);
 
 /* One learner step of Algorithm 1 on a gathered batch.  Per trajectory b:
