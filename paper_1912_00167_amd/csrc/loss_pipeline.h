@@ -86,19 +86,10 @@ void loss_static(const LossArgs a)
     double *r_lp = r_lp_all[CACHED ? wave : 0];
 
     float bad = 0.f;
-    // the slot indices travel while the table is computed
+    // the slot indices travel (possibly across the bus, from page-locked host memory) while the first
+    // learner rows are requested, which need no slot, and the table is computed
     int my_slot = 0;
     if (SLOT && tid < NB) my_slot = a.slots[b0 + min(tid, nb - 1)];
-    exp64_table_init(exp_tbl, tid, 64 * NW);
-    if (SLOT && tid < NB) {
-        int s = my_slot;
-        if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
-        slot_row0[tid] = s * a.T;
-        slot_dist0[tid] = (unsigned)s * (unsigned)a.stride_dist;
-        slot_act0[tid] = (unsigned)s * (unsigned)a.stride_act;
-        slot_lp0[tid] = (unsigned)s * (unsigned)a.stride_lp;
-    }
-    __syncthreads();
     // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
     // have the same geometry and share their lane offsets).  The plans are made for full chunks; the
     // tail chunk, the only one that can be ragged, is fetched first, here, with plans of its own, so
@@ -122,6 +113,18 @@ void loss_static(const LossArgs a)
         ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * 4 / 16);
         if (!agg_only)
             ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
+    }
+    exp64_table_init(exp_tbl, tid, 64 * NW);
+    if (SLOT && tid < NB) {
+        int s = my_slot;
+        if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
+        slot_row0[tid] = s * a.T;
+        slot_dist0[tid] = (unsigned)s * (unsigned)a.stride_dist;
+        slot_act0[tid] = (unsigned)s * (unsigned)a.stride_act;
+        slot_lp0[tid] = (unsigned)s * (unsigned)a.stride_lp;
+    }
+    __syncthreads();
+    if (tail_rows > 0) {
         if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
         ld_dist.plan(a.B, tail_rows, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
         if (CACHED) ld_lp.plan(a.B, tail_rows, slot_lp0, lane, nb);
