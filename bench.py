@@ -150,7 +150,8 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         learner, values, boot = fill_ring(torch, binding, wl, buf, min(B, 4096))
         nq = len(learner)
         slots = [torch.arange(q * B, (q + 1) * B, dtype=torch.int32, device="cuda") for q in range(nq)]
-        out = binding.alloc_loss_out(T, B, W)
+        outs2 = [binding.alloc_loss_out(T, B, W) for _ in range(2)]      # alternate: no call overwrites what the last one wrote
+        out = outs2[0]
         ws = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, T, B, wl.A), dtype=torch.uint8, device="cuda")
         cfg = binding.config_from_hyper(wl.hyper)
         gathered = [binding.impact_buffer_gather(buf, slots[q]) for q in range(min(nq, 2))]
@@ -158,13 +159,13 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         n_calls = 100
         t_tm = timed(lambda i: binding.impact_loss_fwd_bwd(wl.dist, learner[i % len(gathered)], values[i % len(gathered)],
                                                            boot[i % len(gathered)], gathered[i % len(gathered)], cfg,
-                                                           out=out, workspace=ws), n_calls)
+                                                           out=outs2[i % 2], workspace=ws), n_calls)
         t_g = timed(lambda i: binding.impact_buffer_gather(buf, slots[i % nq], dst), n_calls)
         t_f = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
-                                                                      boot[i % nq], cfg, out=out, workspace=ws), n_calls)
-        out_p = binding.alloc_loss_out(T, B, W, packed=True)
+                                                                      boot[i % nq], cfg, out=outs2[i % 2], workspace=ws), n_calls)
+        out_p = [binding.alloc_loss_out(T, B, W, packed=True) for _ in range(2)]
         t_p = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
-                                                                      boot[i % nq], cfg, out=out_p, workspace=ws), n_calls)
+                                                                      boot[i % nq], cfg, out=out_p[i % 2], workspace=ws), n_calls)
         del out_p
         # host bookkeeping of one sample call (ring walk, counts), timed on its own
         s_np, c_np = np.empty(B, np.int32), np.empty(B, np.int32)
@@ -198,14 +199,14 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         del learner, values, boot
         learner, values, boot = fill_ring(torch, binding, wl, buf, min(B, 4096))
         t_c = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
-                                                                      boot[i % nq], cfg, out=out, workspace=ws), n_calls)
+                                                                      boot[i % nq], cfg, out=outs2[i % 2], workspace=ws), n_calls)
         bps = algorithmic_bytes_per_step(wl, cached)
         gbs = bps * steps / t_c / 1e3
         what = "kept for the KL term" if cached == "with_target" else "not kept"
         print(f"| {wl.name} | fused, cached log pi(a) pair ({bps} B/step; target distribution {what}) | {t_c:.1f} | "
               f"{steps / t_c * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | {clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
         buf.close()
-        del learner, values, boot, out
+        del learner, values, boot, out, outs2
         gc.collect()
     gc.enable()
 

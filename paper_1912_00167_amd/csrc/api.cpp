@@ -1,5 +1,6 @@
 // Host side of libimpact: argument checking, the circular buffer's integer bookkeeping,
 // and kernel dispatch.  Nothing here computes any part of the loss.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -395,7 +396,7 @@ static bool config_ok(const impact_loss_config_t *c)
 }
 
 static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T, int B, int A, int num_slots,
-                                const int32_t *dev_slots, const float *learner,
+                                const int32_t *dev_slots, int slot_first, const float *learner,
                                 const float *values, const float *bootstrap, const impact_batch_t &batch,
                                 const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
                                 size_t workspace_bytes, unsigned *done_count, hipStream_t s)
@@ -429,7 +430,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.worker = cached ? nullptr : batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
     a.logp = batch.logp;
     a.rewards = batch.rewards; a.dones = batch.dones;
-    a.slots = dev_slots; a.num_slots = num_slots;
+    a.slots = dev_slots; a.num_slots = num_slots; a.slot_first = slot_first;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
     a.rho_clip = cfg->rho_clip;
     a.ratio_worker = (cfg->flags & IMPACT_FLAG_RATIO_WORKER) ? 1 : 0;
@@ -502,7 +503,7 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
                                     impact_stream_t stream)
 {
     if (!batch) return IMPACT_ERR_INVALID_ARG;
-    return run_loss(dist, batch_dtype, nullptr, T, B, A, 0, nullptr, learner_dist, values, bootstrap, *batch, cfg,
+    return run_loss(dist, batch_dtype, nullptr, T, B, A, 0, nullptr, -1, learner_dist, values, bootstrap, *batch, cfg,
                     out, workspace, workspace_bytes, nullptr, static_cast<hipStream_t>(stream));
 }
 
@@ -515,10 +516,26 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
     if (!buf || !dev_slots) return IMPACT_ERR_INVALID_ARG;
     // The indices may also live in page-locked host memory: the kernel reads them once per tile, which
     // spares the caller a copy and its launch.  Pageable host memory is not reachable from the device.
+    // Indices in host memory can also be looked at here: sampling walks the ring, so a batch is very often
+    // one run of consecutive slots (modulo the ring size), and then the kernel needs no index array at all
+    // (2048 small reads across the bus at its start otherwise).
+    int slot_first = -1;
     hipPointerAttribute_t where;
     if (hipPointerGetAttributes(&where, dev_slots) == hipSuccess) {
-        if (where.type == hipMemoryTypeHost) dev_slots = static_cast<const int32_t *>(where.devicePointer);
-        else if (where.type == hipMemoryTypeUnregistered) return IMPACT_ERR_INVALID_ARG;
+        if (where.type == hipMemoryTypeHost) {
+            const int32_t *host = static_cast<const int32_t *>(where.hostPointer ? where.hostPointer : dev_slots);
+            const int32_t N = buf->desc.num_slots, first = B >= 1 ? host[0] : -1;
+            if (first >= 0 && first < N && B <= N) {
+                const int32_t until_wrap = std::min<int32_t>(B, N - first);
+                bool run = true;
+                for (int32_t i = 0; i < until_wrap && run; ++i) run = host[i] == first + i;
+                for (int32_t i = until_wrap; i < B && run; ++i) run = host[i] == i - until_wrap;
+                if (run) slot_first = first;
+            }
+            dev_slots = static_cast<const int32_t *>(where.devicePointer);
+        } else if (where.type == hipMemoryTypeUnregistered) {
+            return IMPACT_ERR_INVALID_ARG;
+        }
         if (!dev_slots) return IMPACT_ERR_INVALID_ARG;
     } else {
         (void)hipGetLastError();
@@ -543,7 +560,7 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
             buf->sync_zeroed = true;
         }
     }
-    return run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, learner_dist, values,
+    return run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, slot_first, learner_dist, values,
                     bootstrap, batch, cfg, out, workspace, workspace_bytes, done_count,
                     static_cast<hipStream_t>(stream));
 }

@@ -37,6 +37,7 @@ struct LossArgs {
     const double *logp;
     const int32_t *slots;     // device [B]; slot-major only
     int num_slots;
+    int slot_first;           // >= 0: trajectory b lies in slot (slot_first + b) mod num_slots and `slots` is not read
     // slot-major only: bytes from one slot's trajectory to the next in the distribution planes and in
     // the action plane (multiples of 16; rewards and flags lie T elements apart)
     size_t stride_dist, stride_act, stride_lp;

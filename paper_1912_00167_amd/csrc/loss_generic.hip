@@ -49,7 +49,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
     float bad = 0.f;
     int slot = 0;
     if (SLOT && b_ok) {
-        slot = a.slots[b];
+        slot = a.slot_first >= 0 ? (a.slot_first + b) % a.num_slots : a.slots[b];
         if (slot < 0 || slot >= a.num_slots) { if (rl == 0 && wave == 0) bad = 1.f; slot = min(max(slot, 0), a.num_slots - 1); }
     }
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;

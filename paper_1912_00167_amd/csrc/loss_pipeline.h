@@ -89,7 +89,15 @@ void loss_static(const LossArgs a)
     // the slot indices travel (possibly across the bus, from page-locked host memory) while the first
     // learner rows are requested, which need no slot, and the table is computed
     int my_slot = 0;
-    if (SLOT && tid < NB) my_slot = a.slots[b0 + min(tid, nb - 1)];
+    if (SLOT && tid < NB) {
+        const int at = b0 + min(tid, nb - 1);
+        if (a.slot_first >= 0) {                   // a run of consecutive slots (the ring's own order): nothing to read
+            my_slot = a.slot_first + at;
+            if (my_slot >= a.num_slots) my_slot -= a.num_slots;
+        } else {
+            my_slot = a.slots[at];
+        }
+    }
     // Asynchronous loads of one chunk's tensors into this wavefront's regions (worker and target planes
     // have the same geometry and share their lane offsets).  The plans are made for full chunks; the
     // tail chunk, the only one that can be ragged, is fetched first, here, with plans of its own, so

@@ -294,6 +294,18 @@ def test_slot_indices_in_host_memory(env):
         np.testing.assert_array_equal(on_device[k].cpu().numpy(), in_place[k].cpu().numpy(), err_msg=k)
     with pytest.raises(binding.ImpactError):
         binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots.copy()), learner, values, boot, cfg)
+    # A run of consecutive slots (the usual outcome of sampling in ring order), also across the ring's end:
+    # seen in host memory, it is passed to the kernel as its first slot.  Same bits as with an index array.
+    for first in (0, 37, 100):
+        run = ((first + np.arange(64)) % 128).astype(np.int32)
+        xr = workloads.take_trajectories(x, run)
+        lr, vr, br = (torch.from_numpy(xr[k]).cuda() for k in ("learner", "values", "bootstrap"))
+        as_array = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(run).cuda(), lr, vr, br, cfg)
+        as_run = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(run).pin_memory(), lr, vr, br, cfg)
+        torch.cuda.synchronize()
+        for k in as_array:
+            np.testing.assert_array_equal(as_array[k].cpu().numpy(), as_run[k].cpu().numpy(), err_msg=f"{first} {k}")
+        check_against_oracle(wl, xr, {k: v.cpu().numpy() for k, v in as_run.items()}, label=f"run from slot {first}")
     buf.close()
 
 
