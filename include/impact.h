@@ -254,7 +254,10 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * device memory, or in page-locked host memory, which the kernel then reads
  * across the bus once per tile and which must stay unchanged until the kernel
  * has run; pageable host memory is refused with IMPACT_ERR_INVALID_ARG;
- * out-of-range indices are clamped and turn the losses into NaN).
+ * out-of-range indices are clamped and turn the losses into NaN).  Indices
+ * in host memory are also looked at by the call itself: if they form one run
+ * of consecutive slots modulo the ring size, as sampling in ring order usually
+ * yields, the kernel is given the first slot and reads no index array.
  * dist, T, A and the batch dtype come from the buffer's descriptor.
  * One launch: the workgroup that finishes last also sums the loss terms, using
  * a counter in the buffer's storage that the first call on a handle clears (in

@@ -62,10 +62,10 @@ __global__ __launch_bounds__(256) void insert_tiles(const PlaneCopyArgs a, int R
         int at[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int f = min(f0 + 256 * u, total - 1);
+            const int f = f0 + 256 * u;
             const int r = (int)(((float)f + 0.5f) * inv_row), i = f - r * row_elems;
             at[u] = r * row_pitch + i;
-            v[u] = src0[(size_t)r * src_pitch + i];
+            v[u] = f < total ? src0[(size_t)r * src_pitch + i] : S(0);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -121,11 +121,17 @@ void launch_insert_plane(PlaneKind kind, const PlaneCopyArgs &a, hipStream_t s)
 }
 
 // dst[t][b][.] = plane[slots[b]][t][.]: a byte copy, done in words of WB bytes (the largest of 4, 2, 1
-// that divides a record).  A workgroup transposes a tile of GATHER_NB trajectories x RT rows through
+// that divides a record).  A workgroup transposes a tile of GATHER_NB (16) trajectories x RT rows through
 // LDS: each wavefront reads whole trajectories' pieces (RT records, contiguous in the plane), then
 // each wavefront writes whole rows (GATHER_NB records, contiguous in the batch tensor).
-constexpr int GATHER_NB = 8;
-constexpr int GATHER_TILE_BYTES = 16384;
+#ifndef IMPACT_GATHER_NB
+#define IMPACT_GATHER_NB 16
+#endif
+#ifndef IMPACT_GATHER_TILE_BYTES
+#define IMPACT_GATHER_TILE_BYTES 16384
+#endif
+constexpr int GATHER_NB = IMPACT_GATHER_NB;
+constexpr int GATHER_TILE_BYTES = IMPACT_GATHER_TILE_BYTES;
 
 template <typename Word>
 __global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr, int RT, size_t slot_words)
@@ -146,7 +152,14 @@ __global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr,
     for (int j = wave; j < nb; j += 4) {
         const Word *src = (const Word *)a.src + (size_t)slot_of[j] * slot_words + (size_t)t0 * wpr;
         if (vec_in && ((size_t)src % 16) == 0) {
-            for (int i = lane; i < piece / VW; i += 64) ((uint4 *)(tile + j * stride))[i] = ((const uint4 *)src)[i];
+            // two loads in flight per lane before the first LDS store (the bounds are run-time values)
+            const int nvec = piece / VW;
+            for (int i = lane; i < nvec; i += 128) {
+                const uint4 v0 = ((const uint4 *)src)[i];
+                const uint4 v1 = i + 64 < nvec ? ((const uint4 *)src)[i + 64] : make_uint4(0, 0, 0, 0);
+                ((uint4 *)(tile + j * stride))[i] = v0;
+                if (i + 64 < nvec) ((uint4 *)(tile + j * stride))[i + 64] = v1;
+            }
         } else {
             for (int i = lane; i < piece; i += 64) tile[j * stride + i] = src[i];
         }
@@ -155,7 +168,7 @@ __global__ __launch_bounds__(256) void gather_tiles(const GatherArgs a, int wpr,
     // out: a row of the batch tensor is the tile's nb records of that time step, one after the other
     const int row_words = nb * wpr;
     const float inv_wpr = 1.0f / (float)wpr;
-    auto from_tile = [&](int r, int c) {           // word c of row r (c < 8 * wpr: exact in float)
+    auto from_tile = [&](int r, int c) {           // word c of row r (c below a few thousand: exact in float)
         const int j = (int)(((float)c + 0.5f) * inv_wpr), k = c - j * wpr;
         return tile[j * stride + r * wpr + k];
     };
@@ -209,7 +222,10 @@ void launch_gather_plane(const GatherArgs &a, hipStream_t s)
     const int wpr = (int)(rec / WB);
     const size_t slot_words = a.slot_stride * a.elem_bytes / WB;   // (a stride is T records, or a multiple of 16 bytes)
     int RT = max(1, (int)(GATHER_TILE_BYTES / (GATHER_NB * rec)));
-    if (RT >= 16) RT &= ~15;                       // whole 16-byte vectors per trajectory piece, whatever the record size
+    // whole 16-byte vectors per trajectory piece: a multiple of 16 / gcd(record bytes, 16) rows
+    int unit = 1;
+    while ((rec * unit) % 16 != 0) unit <<= 1;
+    if (RT >= unit) RT -= RT % unit;
     RT = min(RT, a.T);
     const dim3 grid((a.B + GATHER_NB - 1) / GATHER_NB, (a.T + RT - 1) / RT), block(256);
     switch (WB) {
