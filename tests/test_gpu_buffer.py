@@ -150,6 +150,12 @@ def _fused_case(torch, binding, wl, n_fill, Bn, flags, seed, label):
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in out.items()}
     check_against_oracle(replace(wl, B=Bn), xb, got, label=label)
+    # the same call with the per-step scalars as packed records: the same bits
+    packed = binding.impact_loss_fwd_bwd_from_buffer(buf, dev_slots, learner, values, boot, cfg,
+                                                     out=binding.alloc_loss_out(wl.T, Bn, wl.W, packed=True))
+    torch.cuda.synchronize()
+    for k in ("vs", "adv", "grad_values", "grad_dist", "loss5"):
+        np.testing.assert_array_equal(packed[k].contiguous().cpu().numpy(), got[k], err_msg=f"{label}: packed {k}")
     # The unfused route (gather, then the time-major loss) must agree with the fused one.  The two may run
     # different kernels (the fused specialised ones need 16-byte aligned trajectories in the planes), so the
     # comparison is to the parity tolerance, on gradients scaled by M like the comparison with the oracle.
