@@ -390,16 +390,20 @@ inline int compute_units()
     return cus;
 }
 
-// Workgroup shape by batch size: the fewer tiles, the more wavefronts share one, so that a SIMD has
-// about two wavefronts to switch between; single-wavefront workgroups once there are 8 tiles per compute
-// unit (and, for the fused form, the trajectory fits the preload arrays).
+// Workgroup shape by batch size: the fewer tiles, the more wavefronts share one (they split a chunk's
+// rows), up to what the chip holds at once: all wavefronts of a launch should be resident together, at the
+// occupancy the policy's registers allow, because a second, partial round of workgroups costs more than
+// wider workgroups gain.  Single-wavefront workgroups (no barriers at all) once the tiles alone fill the
+// chip; in the fused form they need the trajectory to fit the preload arrays.
+template <class Policy>
 inline int waves_per_tile(const LossArgs &a, bool slot_major)
 {
-    const int cus = compute_units();
+    const int capacity = compute_units() * 4 * Policy::SIMD_WAVES;
     const int tiles = num_tiles(a.B);
-    if (tiles >= 8 * cus && (!slot_major || a.T <= T_PRELOAD)) return 1;
-    if (tiles >= 4 * cus) return 2;
-    return NWAVES;
+    int nw = NWAVES;
+    while (nw > 1 && tiles * nw > capacity) --nw;
+    if (nw == 1 && slot_major && a.T > T_PRELOAD) nw = 2;
+    return nw;
 }
 
 template <class Policy, int NW>
@@ -432,9 +436,10 @@ void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t 
 template <class Policy>
 void launch_loss_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
-    switch (waves_per_tile(a, slot_major)) {
+    switch (waves_per_tile<Policy>(a, slot_major)) {
     case 1: launch_loss_static_nw<Policy, 1>(dtype, slot_major, a, s); break;
     case 2: launch_loss_static_nw<Policy, 2>(dtype, slot_major, a, s); break;
+    case 3: launch_loss_static_nw<Policy, 3>(dtype, slot_major, a, s); break;
     default: launch_loss_static_nw<Policy, NWAVES>(dtype, slot_major, a, s); break;
     }
 }

@@ -22,6 +22,7 @@ template <int A, int P, int MODE = POLICY_FULL>
 struct CatPolicy {
     static constexpr int W = A, ACT = 0, LANES = P;
     static constexpr bool CACHED = MODE != POLICY_FULL, TGT = MODE != POLICY_CACHED;
+    static constexpr int SIMD_WAVES = 3;           // wavefronts per SIMD that the kernels' registers (<= 168) allow
     static constexpr int AH = A / P;               // logits per lane
     static_assert(AH * P == A, "the lanes of a step split the logits evenly");
 

@@ -21,6 +21,7 @@ template <int D, int P, int MODE = POLICY_FULL>
 struct GaussPolicy {
     static constexpr int W = 2 * D, ACT = D, LANES = P;
     static constexpr bool CACHED = MODE != POLICY_FULL, TGT = MODE != POLICY_CACHED;
+    static constexpr int SIMD_WAVES = D <= 3 ? 3 : 2;   // wavefronts per SIMD that the kernels' registers allow
     static constexpr int DH = (D + P - 1) / P;     // dimensions per lane
 
     struct Kept {
