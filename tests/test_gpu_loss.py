@@ -39,6 +39,8 @@ RAGGED = [
     ("categorical", 64, 8, 18), ("categorical", 45, 24, 18), ("categorical", 7, 16, 4), ("categorical", 100, 40, 9),
     ("gaussian", 1, 1, 1), ("gaussian", 33, 37, 2), ("gaussian", 65, 9, 5), ("gaussian", 40, 24, 17),
     ("gaussian", 96, 16, 3), ("gaussian", 50, 8, 6),
+    # many actions / dimensions: no specialised kernel
+    ("categorical", 6, 16, 300), ("gaussian", 5, 8, 40),
     # batches that end in a ragged tile of the specialised kernels (rows and ragged segment whole 16-byte vectors)
     ("categorical", 50, 10, 18), ("categorical", 21, 500, 18), ("categorical", 9, 4, 4), ("categorical", 30, 20, 6),
     ("gaussian", 40, 12, 6), ("gaussian", 19, 36, 17), ("gaussian", 5, 2, 6), ("gaussian", 70, 100, 3),
