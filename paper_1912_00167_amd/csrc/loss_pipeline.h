@@ -1,6 +1,10 @@
 // The pipeline all specialised loss kernels share; the distribution-specific arithmetic comes in
-// through a Policy class (GaussPolicy in loss_gauss.hip, CatPolicy in loss_cat.hip):
+// through a Policy class (GaussPolicy in policy_gauss.h, CatPolicy in policy_cat.h):
 //   W, ACT, LANES          tensor widths per step and the number of lanes that share a step
+//   CACHED, TGT            where the behaviour side comes from: the worker's and the target's distributions,
+//                          or the buffer's cached pair of log-probabilities (then the target's distribution
+//                          is read for the KL term only, if it is kept at all)
+//   SIMD_WAVES             wavefronts per SIMD that the kernels' register use allows
 //   Kept                   registers that live from the behaviour pass to the learner pass
 //   behaviour(...)         worker and target passes at the action taken: returns pi_target / pi_worker
 //   learner(...)           ratio, surrogate, entropy, KL and the gradients, written over the learner's
@@ -15,8 +19,8 @@ namespace impact {
 // Order per chunk: (wait for the chunk's data) behaviour pass, scan, (issue the next chunk's loads)
 // learner pass, gradient stores.
 //
-// NW wavefronts per workgroup.  Four (the usual tiling: the wavefronts split each chunk's rows and
-// meet in the scan) keep a small batch spread over the chip.  With one, every wavefront is a workgroup
+// NW wavefronts per workgroup (see waves_per_tile).  Several (they split each chunk's rows and meet in
+// the scan) keep a smaller batch spread over the chip.  With one, every wavefront is a workgroup
 // of its own that walks its 8 trajectories alone, without barriers: once the batch is large enough to
 // fill the chip that way, the wavefronts of a compute unit drift apart in phase, and while some are
 // held up issuing loads into a full memory queue the others compute.
