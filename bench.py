@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 MEASURED_TRAFFIC_BYTES = {"C5": 1.0336e9, "C4": 2.709e8}
 
 
-def algorithmic_bytes_per_step(wl, cached=None) -> int:
+def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False) -> int:
     """Each input read once, each output written once (single pass), per (t, b) step.
     cached: None (both distributions in the batch), or "with_target" / "no_target": the buffer keeps
     log pi_worker(a), log pi_target(a) as two doubles in place of the worker's distribution (and of the
@@ -42,7 +42,7 @@ def algorithmic_bytes_per_step(wl, cached=None) -> int:
     W = wl.A if wl.dist == workloads.CATEGORICAL else 2 * wl.A
     action = 4 if wl.dist == workloads.CATEGORICAL else wl.A * es
     behaviour = {None: 2 * W * es, "with_target": 16 + W * es, "no_target": 16}[cached]
-    reads = 4 * W + behaviour + action + es + 1 + 4      # learner, behaviour side, action, reward, done, value
+    reads = (2 if learner_bf16 else 4) * W + behaviour + action + es + 1 + 4      # learner, behaviour side, action, reward, done, value
     writes = 4 * W + 12                                  # gradient of the distribution, of the value, vs, adv
     return reads + writes
 
@@ -167,6 +167,12 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         t_p = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
                                                                       boot[i % nq], cfg, out=out_p[i % 2], workspace=ws), n_calls)
         del out_p
+        t_b = None
+        if wl.storage == "bf16":                     # the learner's distribution in bf16 as well (a dtype variant)
+            lb = [x.to(torch.bfloat16) for x in learner]
+            t_b = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], lb[i % nq], values[i % nq],
+                                                                          boot[i % nq], cfg, out=outs2[i % 2], workspace=ws), n_calls)
+            del lb
         # host bookkeeping of one sample call (ring walk, counts), timed on its own
         s_np, c_np = np.empty(B, np.int32), np.empty(B, np.int32)
         n_samples = 200
@@ -188,6 +194,11 @@ def table(torch, binding, names, repeats: int = 5) -> None:
             gbs = bps * steps / us / 1e3
             print(f"| {wl.name} | {line} | {us:.1f} | {steps / us * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | "
                   f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
+        if t_b is not None:
+            bps = algorithmic_bytes_per_step(wl, learner_bf16=True)
+            gbs = bps * steps / t_b / 1e3
+            print(f"| {wl.name} | fused, learner distribution in bf16 ({bps} B/step) | {t_b:.1f} | {steps / t_b * 1e6:.3e} | "
+                  f"{gbs:.0f} | {gbs / 80:.1f} | {clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
         print(f"| {wl.name} | sample (host bookkeeping, incl. refill) | {t_s:.1f} | {steps / t_s * 1e6:.3e} | - | - | - | - |", flush=True)
         buf.close()
         del gathered, dst

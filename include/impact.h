@@ -84,7 +84,9 @@ typedef struct {
  *                           terms (Algorithm 1, Appendix B)
  *   flags                   bit 0: use the shape-generic kernels even when a specialised one exists
  *                           bit 1: surrogate ratio pi_theta / pi_worker (R_2 of Section 4.1's ablation)
- *                                  instead of the target-worker clipped one; rho_clip is then unused */
+ *                                  instead of the target-worker clipped one; rho_clip is then unused
+ *                           bit 2: learner_dist holds bfloat16 values (a network under mixed precision);
+ *                                  the gradients are fp32 all the same */
 typedef struct {
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;
@@ -95,6 +97,7 @@ typedef struct {
 
 #define IMPACT_FLAG_FORCE_GENERIC 1u
 #define IMPACT_FLAG_RATIO_WORKER 2u
+#define IMPACT_FLAG_LEARNER_BF16 4u
 
 /* The buffer-resident part of a batch (what a worker sent plus the target
  * network's evaluation appended at k = 0, Algorithm 1).  All device pointers.
@@ -236,15 +239,16 @@ size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A
  *       + kl_coeff mean KL(pi_target || pi_theta),   means over the T*B steps
  * and the gradients of L with respect to the learner's distribution parameters
  * and values, with vs and adv held constant (Algorithm 1).
- *   batch_dtype   dtype of the float fields of `batch` (learner_dist, values, bootstrap are fp32)
- *   learner_dist  [T][B][W], values [T][B], bootstrap [B]  (device, fp32)
+ *   batch_dtype   dtype of the float fields of `batch` (values and bootstrap are fp32)
+ *   learner_dist  [T][B][W] (device; fp32, or bf16 with IMPACT_FLAG_LEARNER_BF16)
+ *   values [T][B], bootstrap [B]  (device, fp32)
  *   workspace     device, >= impact_loss_workspace_bytes(...)
  * Errors: INVALID_ARG (NULL or misaligned pointers, T,B,A < 1, non-finite gamma/lambda/
  * coefficients, negative truncation levels, rho_clip < 1, eps < 0), HIP.
  * A categorical action outside [0, A) is clamped for addressing and turns all
  * five losses into NaN. */
 impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
-                                    const float *learner_dist, const float *values, const float *bootstrap,
+                                    const void *learner_dist, const float *values, const float *bootstrap,
                                     const impact_batch_t *batch, const impact_loss_config_t *cfg,
                                     const impact_loss_out_t *out, void *workspace, size_t workspace_bytes,
                                     impact_stream_t stream);
@@ -266,7 +270,7 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * launches only (no memset, no copy, no allocation), so it can be captured in a
  * HIP graph and replayed. */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
-                                                const float *learner_dist, const float *values,
+                                                const void *learner_dist, const float *values,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,
                                                 const impact_loss_out_t *out, void *workspace,
                                                 size_t workspace_bytes, impact_stream_t stream);

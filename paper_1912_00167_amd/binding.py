@@ -31,6 +31,7 @@ IMPACT_F32 = 0
 IMPACT_BF16 = 1
 IMPACT_FLAG_FORCE_GENERIC = 1
 IMPACT_FLAG_RATIO_WORKER = 2
+IMPACT_FLAG_LEARNER_BF16 = 4
 IMPACT_BUFFER_CACHE_LOGP = 1
 IMPACT_BUFFER_NO_TARGET_DIST = 2
 
@@ -172,6 +173,17 @@ def config_from_hyper(h, flags: int = 0) -> impact_loss_config_t:
         flags |= IMPACT_FLAG_RATIO_WORKER
     return make_config(h.gamma, h.lam, h.rho_bar, h.c_bar, h.rho_clip, h.eps, h.vf_coeff, h.ent_coeff,
                        h.kl_coeff, flags)
+
+
+def _cfg_for(cfg: impact_loss_config_t, learner: torch.Tensor) -> impact_loss_config_t:
+    """The configuration with the learner tensor's dtype flagged (fp32 or bf16)."""
+    if learner.dtype == torch.float32:
+        return cfg
+    if learner.dtype != torch.bfloat16:
+        raise ValueError("the learner's distribution tensor is fp32 or bf16")
+    c = impact_loss_config_t.from_buffer_copy(cfg)
+    c.flags |= IMPACT_FLAG_LEARNER_BF16
+    return c
 
 
 def _batch_struct(batch: Dict[str, torch.Tensor], need_target: bool = True) -> impact_batch_t:
@@ -348,6 +360,7 @@ def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, boots
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(d, T, B, A), dtype=torch.uint8, device=learner.device)
     b, o = _batch_struct(batch), _out_struct(out)
+    cfg = _cfg_for(cfg, learner)
     _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
                                       _ptr(bootstrap), ctypes.byref(b), ctypes.byref(cfg), ctypes.byref(o),
                                       _ptr(workspace), workspace.numel(), _stream(stream)), "impact_loss_fwd_bwd")
@@ -365,6 +378,7 @@ def impact_loss_fwd_bwd_from_buffer(buf: Buffer, dev_slots: torch.Tensor, learne
         workspace = torch.empty(impact_loss_workspace_bytes(buf.dist, T, B, buf.A), dtype=torch.uint8,
                                 device=learner.device)
     o = _out_struct(out)
+    cfg = _cfg_for(cfg, learner)
     _check(load().impact_loss_fwd_bwd_from_buffer(buf.handle, B, _ptr(dev_slots), _ptr(learner), _ptr(values),
                                                   _ptr(bootstrap), ctypes.byref(cfg), ctypes.byref(o),
                                                   _ptr(workspace), workspace.numel(), _stream(stream)),

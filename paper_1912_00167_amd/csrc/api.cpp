@@ -396,7 +396,7 @@ static bool config_ok(const impact_loss_config_t *c)
 }
 
 static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T, int B, int A, int num_slots,
-                                const int32_t *dev_slots, int slot_first, const float *learner,
+                                const int32_t *dev_slots, int slot_first, const void *learner,
                                 const float *values, const float *bootstrap, const impact_batch_t &batch,
                                 const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
                                 size_t workspace_bytes, unsigned *done_count, hipStream_t s)
@@ -427,6 +427,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     std::memset(&a, 0, sizeof(a));
     a.T = T; a.B = B; a.A = A;
     a.learner = learner; a.values = values; a.bootstrap = bootstrap;
+    a.learner_bf16 = (cfg->flags & IMPACT_FLAG_LEARNER_BF16) ? 1 : 0;
     a.worker = cached ? nullptr : batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
     a.logp = batch.logp;
     a.rewards = batch.rewards; a.dones = batch.dones;
@@ -461,7 +462,8 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
             return ((size_t)B * elems * elem_bytes) % 16 == 0 && (nbr * elems * elem_bytes) % 16 == 0;
         };
         const size_t Wd = dist == IMPACT_CATEGORICAL ? (size_t)A : 2 * (size_t)A;
-        if (!whole_vectors(Wd, 4)) fast = false;                                  // learner rows, gradient rows
+        if (!whole_vectors(Wd, 4)) fast = false;                                  // gradient rows, fp32 learner rows
+        if (a.learner_bf16 && !whole_vectors(Wd, 2)) fast = false;
         if (!slot_major) {
             if ((batch.target_dist || !cached) && !whole_vectors(Wd, es)) fast = false;
             if (dist == IMPACT_DIAG_GAUSSIAN && !whole_vectors((size_t)A, es)) fast = false;
@@ -469,6 +471,8 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     }
     // they address a wavefront's rows with 32-bit byte offsets from a 64-bit base
     if ((double)B * W * 4.0 * (64 / NB) >= 2147483648.0) fast = false;
+    // a bf16 learner tensor has specialised kernels in the fused form on a bf16 buffer
+    if (a.learner_bf16 && !(slot_major && dtype == IMPACT_BF16)) fast = false;
     if (slot_major) {
         if ((double)num_slots * T >= 2147483648.0 || (double)num_slots * (double)planes->stride_dist >= 4294967296.0 ||
             (double)num_slots * (double)planes->stride_act >= 4294967296.0)
@@ -497,7 +501,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
 }
 
 impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
-                                    const float *learner_dist, const float *values, const float *bootstrap,
+                                    const void *learner_dist, const float *values, const float *bootstrap,
                                     const impact_batch_t *batch, const impact_loss_config_t *cfg,
                                     const impact_loss_out_t *out, void *workspace, size_t workspace_bytes,
                                     impact_stream_t stream)
@@ -508,7 +512,7 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
 }
 
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
-                                                const float *learner_dist, const float *values,
+                                                const void *learner_dist, const float *values,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,
                                                 const impact_loss_out_t *out, void *workspace,
                                                 size_t workspace_bytes, impact_stream_t stream)

@@ -23,7 +23,7 @@ constexpr int PARTIAL_STRIDE = 8;           // floats per workgroup in the parti
 struct LossArgs {
     int T, B, A;
     // learner side, always time-major fp32
-    const float *learner;     // [T][B][W]
+    const void *learner;      // [T][B][W], fp32 or (learner_bf16) bf16
     const float *values;      // [T][B]
     const float *bootstrap;   // [B]
     // buffer-resident side: time-major [T][B][..] or slot-major [slot][T][..]
@@ -35,6 +35,7 @@ struct LossArgs {
     // cached log pi_worker(a), log pi_target(a): [T][B][2] or the buffer's plane [slot][T][2], or null.
     // Where given, `worker` is null, and `target` may be (then the KL coefficient is zero).
     const double *logp;
+    int learner_bf16;
     const int32_t *slots;     // device [B]; slot-major only
     int num_slots;
     int slot_first;           // >= 0: trajectory b lies in slot (slot_first + b) mod num_slots and `slots` is not read

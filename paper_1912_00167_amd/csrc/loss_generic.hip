@@ -30,7 +30,7 @@ __device__ __forceinline__ double gauss_logp(const ST *p, const AT *act, int D)
     return lp;
 }
 
-template <int DIST, typename ST, bool SLOT>
+template <int DIST, typename ST, typename LT, bool SLOT>
 __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
 {
     __shared__ double sd[2][TC_MAX * NB];
@@ -72,7 +72,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         // quantities the gradient pass needs again
         float m_l = 0.f, m_t = 0.f;
         double S_l = 1.0, S_t = 1.0;
-        const float *zl = a.learner + s_tm * W;
+        const LT *zl = (const LT *)a.learner + s_tm * W;
         // in the buffer's planes a slot's trajectory starts at a multiple of the plane's stride
         const size_t dist_at = SLOT ? (size_t)slot * a.stride_dist + (size_t)t * W * sizeof(ST) : s_tm * W * sizeof(ST);
         const ST *zt = (const ST *)((const char *)a.target + dist_at);
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
                 if (has_target) softmax_stats(zt, A, m_t, S_t);
                 softmax_stats(zl, A, m_l, S_l);
-                const double xl = (double)zl[act] - (double)m_l;
+                const double xl = (double)widen(zl[act]) - (double)m_l;
                 const double logS_l = log(S_l), logS_t = log(S_t);
                 if (cached) {
                     w = exp(lp2[1] - lp2[0]);
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                     R1 = exp(xl - xt) * (S_t / S_l);
                 }
                 for (int k = 0; k < A; ++k) {
-                    const double lpl = ((double)zl[k] - (double)m_l) - logS_l;
+                    const double lpl = ((double)widen(zl[k]) - (double)m_l) - logS_l;
                     H -= exp(lpl) * lpl;
                     if (has_target) {
                         const double lpt = ((double)widen(zt[k]) - (double)m_t) - logS_t;
@@ -129,11 +129,11 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                     R1 = exp(ll - lt);
                 }
                 for (int d = 0; d < A; ++d) {
-                    const double ls = (double)zl[A + d];
+                    const double ls = (double)widen(zl[A + d]);
                     H += ls;
                     if (has_target) {
                         const double lst = (double)widen(zt[A + d]);
-                        const double dm = (double)zl[d] - (double)widen(zt[d]);
+                        const double dm = (double)widen(zl[d]) - (double)widen(zt[d]);
                         KL += (ls - lst) + 0.5 * (exp(2.0 * lst) + dm * dm) * exp(-2.0 * ls) - 0.5;
                     }
                 }
@@ -155,9 +155,9 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 const double logS_l = log(S_l), logS_t = log(S_t);
                 double others = 0.0;                     // 1 - p_a as a sum, free of cancellation
                 for (int k = 0; k < A; ++k)
-                    if (k != act) others += exp(((double)zl[k] - (double)m_l) - logS_l);
+                    if (k != act) others += exp(((double)widen(zl[k]) - (double)m_l) - logS_l);
                 for (int k = 0; k < A; ++k) {
-                    const double lp = ((double)zl[k] - (double)m_l) - logS_l;
+                    const double lp = ((double)widen(zl[k]) - (double)m_l) - logS_l;
                     const double p = exp(lp);
                     const double pt = has_target ? exp(((double)widen(zt[k]) - (double)m_t) - logS_t) : p;   // no target: no KL term
                     const double base = ce * p * (lp + H) + ck * (p - pt);
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 }
             } else {
                 for (int d = 0; d < A; ++d) {
-                    const double mu = (double)zl[d], ls = (double)zl[A + d];
+                    const double mu = (double)widen(zl[d]), ls = (double)widen(zl[A + d]);
                     const double E = exp(-2.0 * ls);
                     const double diff = (double)widen(av[d]) - mu;
                     const double dm = has_target ? mu - (double)widen(zt[d]) : 0.0;
@@ -194,14 +194,21 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
 {
     const dim3 grid(num_tiles(a.B)), block(NTHREADS);
-#define IMPACT_LAUNCH(DIST, ST, SLOT) hipLaunchKernelGGL((loss_generic<DIST, ST, SLOT>), grid, block, 0, s, a)
-    if (dist == IMPACT_CATEGORICAL) {
-        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(IMPACT_CATEGORICAL, float, true); else IMPACT_LAUNCH(IMPACT_CATEGORICAL, float, false); }
-        else { if (slot_major) IMPACT_LAUNCH(IMPACT_CATEGORICAL, bf16_t, true); else IMPACT_LAUNCH(IMPACT_CATEGORICAL, bf16_t, false); }
-    } else {
-        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH(IMPACT_DIAG_GAUSSIAN, float, true); else IMPACT_LAUNCH(IMPACT_DIAG_GAUSSIAN, float, false); }
-        else { if (slot_major) IMPACT_LAUNCH(IMPACT_DIAG_GAUSSIAN, bf16_t, true); else IMPACT_LAUNCH(IMPACT_DIAG_GAUSSIAN, bf16_t, false); }
-    }
+#define IMPACT_LAUNCH(DIST, ST, LT, SLOT) hipLaunchKernelGGL((loss_generic<DIST, ST, LT, SLOT>), grid, block, 0, s, a)
+#define IMPACT_LAUNCH_LT(DIST, ST, SLOT)                              \
+    do {                                                              \
+        if (a.learner_bf16) IMPACT_LAUNCH(DIST, ST, bf16_t, SLOT);    \
+        else IMPACT_LAUNCH(DIST, ST, float, SLOT);                    \
+    } while (0)
+#define IMPACT_LAUNCH_ST(DIST)                                                                  \
+    do {                                                                                        \
+        if (dtype == IMPACT_F32) { if (slot_major) IMPACT_LAUNCH_LT(DIST, float, true); else IMPACT_LAUNCH_LT(DIST, float, false); }   \
+        else { if (slot_major) IMPACT_LAUNCH_LT(DIST, bf16_t, true); else IMPACT_LAUNCH_LT(DIST, bf16_t, false); }                   \
+    } while (0)
+    if (dist == IMPACT_CATEGORICAL) IMPACT_LAUNCH_ST(IMPACT_CATEGORICAL);
+    else IMPACT_LAUNCH_ST(IMPACT_DIAG_GAUSSIAN);
+#undef IMPACT_LAUNCH_ST
+#undef IMPACT_LAUNCH_LT
 #undef IMPACT_LAUNCH
 }
 

@@ -24,10 +24,14 @@ namespace impact {
 // of its own that walks its 8 trajectories alone, without barriers: once the batch is large enough to
 // fill the chip that way, the wavefronts of a compute unit drift apart in phase, and while some are
 // held up issuing loads into a full memory queue the others compute.
-template <class Policy, typename ST, bool SLOT, int NW>
+// ST: storage type of the buffer-resident fields; LT: type of the learner's distribution tensor (fp32, or
+// bf16 as a network under mixed precision produces it; the gradients leave in fp32 either way).
+template <class Policy, typename ST, typename LT, bool SLOT, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
 void loss_static(const LossArgs a)
 {
+    // fp32 learner rows are overwritten by their gradients in place; narrower ones get a region for them
+    constexpr bool INPLACE = std::is_same<LT, float>::value;
     constexpr int W = Policy::W;                   // elements of a distribution tensor per step
     constexpr int ACT = Policy::ACT;               // elements of the action tensor per step; 0: one int32 index
     constexpr int ACTR = ACT > 0 ? ACT : 1;
@@ -47,12 +51,14 @@ void loss_static(const LossArgs a)
     // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
     // while this chunk's gradients are still being produced in the other one
     constexpr int BEHAVIOUR_BYTES = (ACT + (CACHED ? 0 : W) + (TGT ? W : 0)) * (int)sizeof(ST) + (CACHED ? 16 : 0);
-    constexpr int LDS_ONE = NW * SPW * (BEHAVIOUR_BYTES + W * 4) + 4 * TCH * NB * 8 + 1024;
-    constexpr int NLN = (LDS_ONE + NW * SPW * W * 4 <= 64 * 1024) ? 2 : 1;
+    constexpr int LEARNER_BYTES = W * (int)sizeof(LT);
+    constexpr int LDS_ONE = NW * SPW * (BEHAVIOUR_BYTES + LEARNER_BYTES + (INPLACE ? 0 : W * 4)) + 4 * TCH * NB * 8 + 1024;
+    constexpr int NLN = (LDS_ONE + NW * SPW * LEARNER_BYTES <= 64 * 1024) ? 2 : 1;
     // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
     // tell a read of one region from an asynchronous load still in flight into the other)
-    __shared__ __align__(16) float r_ln0_all[NW][SPW * W];
-    __shared__ __align__(16) float r_ln1_all[NLN == 2 ? NW : 1][NLN == 2 ? SPW * W : 4];
+    __shared__ __align__(16) LT r_ln0_all[NW][SPW * W];
+    __shared__ __align__(16) LT r_ln1_all[NLN == 2 ? NW : 1][NLN == 2 ? SPW * W : 8];
+    __shared__ __align__(16) float r_gr_all[INPLACE ? 1 : NW][INPLACE ? 4 : SPW * W];
     __shared__ double sd[2][TCH * NB];
     __shared__ double sg[2][TCH * NB];
     // where the tile's trajectories start in the buffer: in steps (rewards, flags), and in bytes of the
@@ -109,7 +115,7 @@ void loss_static(const LossArgs a)
     ChunkLoader<ST, ACTR, RWP, SLOT> ld_act;
     ChunkLoader<ST, W, RWP, SLOT> ld_dist;
     ChunkLoader<double, 2, RWP, SLOT> ld_lp;
-    ChunkLoader<float, W, RWP, false> ld_lrn;
+    ChunkLoader<LT, W, RWP, false> ld_lrn;
     auto fetch_buffer_side = [&](int c) {
         const int t_base = c * TCH + wave * RWP;
         if (ACT > 0) ld_act.issue(ld_act.chunk_base(a.actions, a.B, t_base, b0), r_act, lane);
@@ -122,7 +128,7 @@ void loss_static(const LossArgs a)
     const int c_lo = SEGS && a.num_segs > 1 ? seg * a.seg_chunks : 0;
     const int tail_rows = min(RWP, a.T - ((nchunk - 1) * TCH + wave * RWP));   // may be <= 0
     if (tail_rows > 0) {
-        ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * 4 / 16);
+        ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * (int)sizeof(LT) / 16);
         if (!agg_only)
             ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
     }
@@ -175,7 +181,7 @@ void loss_static(const LossArgs a)
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
     ChunkStorer<W, RWP> st_grad;
-    auto fetch_learner = [&](int c, float *region) {
+    auto fetch_learner = [&](int c, LT *region) {
         ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, c * TCH + wave * RWP, b0), region, lane);
     };
 
@@ -235,7 +241,7 @@ void loss_static(const LossArgs a)
         if (ACT > 0) ld_act.plan(a.B, RWP, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
         ld_dist.plan(a.B, RWP, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
         if (CACHED) ld_lp.plan(a.B, RWP, slot_lp0, lane, nb);
-        ld_lrn.plan(a.B, RWP, nullptr, lane, nb * W * 4 / 16);
+        ld_lrn.plan(a.B, RWP, nullptr, lane, nb * W * (int)sizeof(LT) / 16);
         st_grad.plan(a.B, lane);
     }
     wait_dma_done();
@@ -247,8 +253,9 @@ void loss_static(const LossArgs a)
     auto chunk = [&](auto parity, auto is_tail, int c) {
         constexpr int Q = decltype(parity)::value;
         constexpr bool TAIL = decltype(is_tail)::value;
-        float *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
-        float *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
+        LT *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
+        LT *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
+        float *r_gr = INPLACE ? (float *)r_ln : r_gr_all[INPLACE ? 0 : wave];     // where this chunk's gradients go
         const int t_base = c * TCH + wave * RWP;
         const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
@@ -335,10 +342,10 @@ void loss_static(const LossArgs a)
         if (rows > 0 && !skip) {
             // ---- learner: ratio, surrogate, entropy, KL; gradients replace the learner's rows in LDS ----
             double s, H, KL;
-            Policy::learner(kept, r_ln + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
+            Policy::learner(kept, r_ln + step * W, r_gr + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
             char *gbase = st_grad.chunk_base(a.grad_dist, a.B, t_base, b0);
-            if (TAIL) st_grad.template store<false>(gbase, r_ln, rows, lane, nb * W * 4 / 16);
-            else st_grad.template store<true>(gbase, r_ln, rows, lane);
+            if (TAIL) st_grad.template store<false>(gbase, r_gr, rows, lane, nb * W * 4 / 16);
+            else st_grad.template store<true>(gbase, r_gr, rows, lane);
 
             if (valid && lead) {
                 sum_s += (float)s;
@@ -427,12 +434,14 @@ void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t 
     const dim3 grid(tiles * a.num_segs), block(64 * NW);
     for (int phase = a.num_segs > 1 ? 1 : 0; phase <= (a.num_segs > 1 ? 2 : 0); ++phase) {
         a.phase = phase;
-        if (dtype == IMPACT_F32) {
-            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, true, NW>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((loss_static<Policy, float, false, NW>), grid, block, 0, s, a);
+        if (a.learner_bf16) {      // (instantiated for the fused form on a bf16 buffer; see learner_bf16_has_kernel)
+            hipLaunchKernelGGL((loss_static<Policy, bf16_t, bf16_t, true, NW>), grid, block, 0, s, a);
+        } else if (dtype == IMPACT_F32) {
+            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, float, true, NW>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((loss_static<Policy, float, float, false, NW>), grid, block, 0, s, a);
         } else {
-            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, true, NW>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((loss_static<Policy, bf16_t, false, NW>), grid, block, 0, s, a);
+            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, true, NW>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, false, NW>), grid, block, 0, s, a);
         }
     }
 }

@@ -82,16 +82,18 @@ struct CatPolicy {
         return exp64(k.xt - xw, exp_tbl) * (Sw / k.St);
     }
 
-    // own: this step's learner logits in LDS, replaced by the gradients
-    __device__ __forceinline__ static void learner(const Kept &k, float *own, int part, double adv, double w,
-                                                   const LossArgs &a, double ce_, double ck_, const double *exp_tbl,
-                                                   double &s, double &H_, double &KL_)
+    // own: this step's learner logits in LDS; grad: where its gradients go (the same place for fp32
+    // logits: all of them are read before the first is overwritten)
+    template <typename LT>
+    __device__ __forceinline__ static void learner(const Kept &k, const LT *own, float *grad, int part, double adv,
+                                                   double w, const LossArgs &a, double ce_, double ck_,
+                                                   const double *exp_tbl, double &s, double &H_, double &KL_)
     {
         const float ce = (float)ce_, ck = (float)ck_;
         float x[AH], p[AH];
 #pragma unroll
-        for (int i = 0; i < AH; ++i) x[i] = own[part * AH + i];
-        const float za = own[k.act];
+        for (int i = 0; i < AH; ++i) x[i] = widen(own[part * AH + i]);
+        const float za = widen(own[k.act]);
         float m = x[0];
 #pragma unroll
         for (int i = 1; i < AH; ++i) m = fmaxf(m, x[i]);
@@ -135,7 +137,7 @@ struct CatPolicy {
             const float lp = x[i] - logSl;
             // dL/dz_k: policy term, entropy term, KL term
             const float base = TGT ? ce * pk * (lp + H) + ck * (pk - k.et[i] * invSt) : ce * pk * (lp + H);
-            own[part * AH + i] = fmaf(gf, (part * AH + i == k.act) ? one_minus_pa : -pk, base);
+            grad[part * AH + i] = fmaf(gf, (part * AH + i == k.act) ? one_minus_pa : -pk, base);
         }
         H_ = (double)H;
         KL_ = (double)KL;

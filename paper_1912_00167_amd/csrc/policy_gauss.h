@@ -91,17 +91,19 @@ struct GaussPolicy {
         return exp64((pair_sum<P>(Qw + Sw) - k.Qt) - k.St, exp_tbl);
     }
 
-    // own: this step's learner parameters in LDS, replaced by the gradients
-    __device__ __forceinline__ static void learner(const Kept &k, float *own, int part, double adv, double w,
-                                                   const LossArgs &a, double ce, double ck, const double *exp_tbl,
-                                                   double &s, double &H, double &KL)
+    // own: this step's learner parameters in LDS; grad: where its gradients go (the same place for fp32
+    // parameters: every element is read before it is overwritten)
+    template <typename LT>
+    __device__ __forceinline__ static void learner(const Kept &k, const LT *own, float *grad, int part, double adv,
+                                                   double w, const LossArgs &a, double ce, double ck,
+                                                   const double *exp_tbl, double &s, double &H, double &KL)
     {
         double E[DH];                                  // 1 / (2 sigma_theta^2)
         double Ql = 0.0, Sl = 0.0, Qk = 0.0;
 #pragma unroll
         for (int i = 0; i < DH; ++i) {
-            const double ls = (double)own[D + dim(part, i)];
-            const double diff = k.act[i] - (double)own[dim(part, i)];
+            const double ls = (double)widen(own[D + dim(part, i)]);
+            const double diff = k.act[i] - (double)widen(own[dim(part, i)]);
             E[i] = half_inv_var(ls, exp_tbl);
             Ql += keep(part, i, diff * diff * E[i]);
             Sl += keep(part, i, ls);
@@ -119,7 +121,7 @@ struct GaussPolicy {
         const double g2 = 2.0 * g, ck2 = 2.0 * ck, c0 = ck - g - ce;
 #pragma unroll
         for (int i = 0; i < DH; ++i) {
-            const double mu = (double)own[dim(part, i)];
+            const double mu = (double)widen(own[dim(part, i)]);
             const double diff = k.act[i] - mu;
             float gmu, gls;
             if constexpr (TGT) {
@@ -134,8 +136,8 @@ struct GaussPolicy {
                 gls = (float)__builtin_fma(g2, diff * diff * E[i], c0);
             }
             if (P * DH == D || i < DH - 1 || part * DH + i < D) {
-                own[dim(part, i)] = gmu;
-                own[D + dim(part, i)] = gls;
+                grad[dim(part, i)] = gmu;
+                grad[D + dim(part, i)] = gls;
             }
             sched_fence(i);
         }

@@ -206,6 +206,35 @@ def test_loss_from_buffer(env, ci, flags):
     _fused_case(torch, binding, wl, n_fill, Bn, flags, seed=ci, label=f"fused {name} {kw} flags={flags}")
 
 
+@pytest.mark.parametrize("case", [("C5", dict(T=24, B=64, num_slots=128), "bf16"), ("C4", dict(T=21, B=64, num_slots=128), "bf16"),
+                                  ("C2", dict(T=17, B=24, num_slots=64), "f32"), ("C5", dict(T=40, B=16384, num_slots=16384), "bf16"),
+                                  ("C4", dict(T=30, B=8192, num_slots=8192), "bf16"), ("C3", dict(T=300, B=16, num_slots=32), "bf16")])
+def test_learner_distribution_in_bf16(env, case):
+    """The learner's distribution tensor as a network under mixed precision hands it over (bf16); gradients in
+    fp32.  The oracle sees the same, already rounded, values."""
+    import oracle
+    torch, binding = env
+    name, kw, storage = case
+    wl = shape_workload(workloads.WORKLOADS[name], storage=storage, **kw)
+    say(f"case bf16 learner {name} {kw} {storage}")
+    n = wl.num_slots
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, n, wl.K, storage)
+    x = dict(workloads.make_trajectories(wl, n, stream=61))
+    x["learner"] = oracle.quantize_bf16(x["learner"])[1]
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots = np.random.default_rng(8).permutation(n)[: wl.B].astype(np.int32)
+    xb = workloads.take_trajectories(x, slots)
+    learner = torch.from_numpy(xb["learner"]).cuda().to(torch.bfloat16)
+    assert torch.equal(learner.float().cpu(), torch.from_numpy(xb["learner"]))           # exactly the rounded values
+    values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("values", "bootstrap"))
+    for flags in (0, 1):
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot,
+                                                      binding.config_from_hyper(wl.hyper, flags))
+        torch.cuda.synchronize()
+        check_against_oracle(wl, xb, {k: v.cpu().numpy() for k, v in out.items()}, label=f"bf16 learner {name} flags={flags}")
+    buf.close()
+
+
 def test_fused_calls_in_a_row_on_one_handle(env):
     """The last workgroup to finish sums the loss terms with a counter kept in the buffer's storage, which
     every call must leave at zero: calls of different sizes (many tiles, one tile, a ragged batch on the
