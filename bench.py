@@ -160,6 +160,11 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         t_tm = timed(lambda i: binding.impact_loss_fwd_bwd(wl.dist, learner[i % len(gathered)], values[i % len(gathered)],
                                                            boot[i % len(gathered)], gathered[i % len(gathered)], cfg,
                                                            out=outs2[i % 2], workspace=ws), n_calls)
+        out_tp = [binding.alloc_loss_out(T, B, W, packed=True) for _ in range(2)]
+        t_tp = timed(lambda i: binding.impact_loss_fwd_bwd(wl.dist, learner[i % len(gathered)], values[i % len(gathered)],
+                                                            boot[i % len(gathered)], gathered[i % len(gathered)], cfg,
+                                                            out=out_tp[i % 2], workspace=ws), n_calls)
+        del out_tp
         t_g = timed(lambda i: binding.impact_buffer_gather(buf, slots[i % nq], dst), n_calls)
         t_f = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
                                                                       boot[i % nq], cfg, out=outs2[i % 2], workspace=ws), n_calls)
@@ -188,6 +193,7 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         resident = (2 * W * es + (4 if wl.dist == workloads.CATEGORICAL else wl.A * es) + es + 1)   # buffer bytes per step
         steps = T * B
         for line, us, bps in (("loss, time-major batch", t_tm, algorithmic_bytes_per_step(wl)),
+                              ("loss, time-major batch, per-step scalars as packed records", t_tp, algorithmic_bytes_per_step(wl)),
                               ("gather alone", t_g, 2 * resident),
                               ("fused gather + loss", t_f, algorithmic_bytes_per_step(wl)),
                               ("fused, per-step scalars as packed records", t_p, algorithmic_bytes_per_step(wl))):
