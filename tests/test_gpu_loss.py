@@ -98,6 +98,22 @@ def test_impala_objective_with_the_learner_in_the_targets_place(env, name, flags
     check_against_oracle(wl, x, got, hyper=h, label=f"impala objective {name}")
 
 
+@pytest.mark.parametrize("name", ["C2", "C3"])
+@pytest.mark.parametrize("flags", [0, FORCE_GENERIC], ids=["specialised", "generic"])
+def test_ppo_with_gae_with_the_worker_in_the_targets_place(env, name, flags):
+    """The on-policy baseline (Section 2.1's clipped surrogate on GAE(lambda) advantages) from the same kernels:
+    with the worker's distribution handed over as the target's every weight of the scan is one and the ratio
+    is pi_theta / pi_worker."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], B=64, num_slots=64)
+    x = dict(workloads.make_trajectories(wl, 64, stream=19))
+    x["target"] = x["worker"].copy()
+    h = replace(wl.hyper, lam=0.95, rho_bar=1.0, c_bar=1.0, eps=0.2, kl_coeff=0.0)
+    say(f"case ppo+gae {name} flags={flags}")
+    got = gpu_loss(torch, binding, wl, x, hyper=h, flags=flags)
+    check_against_oracle(wl, x, got, hyper=h, label=f"ppo+gae {name}")
+
+
 @pytest.mark.parametrize("name,kw", [("C1", {}), ("C3", dict(B=64)), ("C2", dict(T=50, B=10)), ("C2", dict(T=33, B=37, A=5)),
                                      ("C5", dict(T=40, B=2048))])
 def test_per_step_scalars_as_packed_records(env, name, kw):
