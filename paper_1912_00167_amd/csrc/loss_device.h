@@ -410,32 +410,45 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+// U tiles per lane, from tile i0 on, 64 apart: all the loads first (one exposed memory latency), then the
+// additions in the order of the tiles.  GUARD: the block may reach past the last tile.
+template <int U, bool GUARD>
+__device__ __forceinline__ void add_tile_block(const float *partials, int i0, int num_tiles, double (&v)[5])
+{
+    float4 q[U];
+    float q4[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = GUARD ? min(i0 + 64 * u, num_tiles - 1) : i0 + 64 * u;
+        q[u] = *(const float4 *)(partials + (size_t)i * PARTIAL_STRIDE);
+        q4[u] = partials[(size_t)i * PARTIAL_STRIDE + 4];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!GUARD || i0 + 64 * u < num_tiles) {
+            v[0] += (double)q[u].x; v[1] += (double)q[u].y; v[2] += (double)q[u].z; v[3] += (double)q[u].w;
+            v[4] += (double)q4[u];
+        }
+    }
+}
+
 // The five loss terms from the tiles' partial sums, by one wavefront and in an order that depends on
 // nothing but the number of tiles: lane l adds tiles l, l + 64, ... in fp64, then the lanes combine.
 // An invalid index anywhere in the batch (flagged in the fifth partial) turns all five into NaN.
+// The wavefront that runs this is the last one at work on the chip, so every memory latency here is
+// exposed: the loads go out in blocks as large as the registers hold.
+// UMAX: tiles per lane in the largest block (5 registers each: a kernel that runs three wavefronts per
+// SIMD on 168 registers takes 16, one that has 256 takes 32).
+template <int UMAX = 16>
 __device__ __forceinline__ void reduce_tiles(const float *partials, int num_tiles, double inv_M, float vf_coeff,
                                              float ent_coeff, float kl_coeff, float *loss5, int lane)
 {
+    static_assert(UMAX == 16 || UMAX == 32, "block sizes of the cascade");
     double v[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    // several tiles' loads in flight per lane; the additions keep the order of the tiles
-    constexpr int U = 8;
-    for (int i0 = lane; i0 < num_tiles; i0 += 64 * U) {
-        float4 q[U];
-        float q4[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = min(i0 + 64 * u, num_tiles - 1);
-            q[u] = *(const float4 *)(partials + (size_t)i * PARTIAL_STRIDE);
-            q4[u] = partials[(size_t)i * PARTIAL_STRIDE + 4];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (i0 + 64 * u < num_tiles) {
-                v[0] += (double)q[u].x; v[1] += (double)q[u].y; v[2] += (double)q[u].z; v[3] += (double)q[u].w;
-                v[4] += (double)q4[u];
-            }
-        }
-    }
+    int done = 0;                                  // tiles before this one are summed
+    for (; num_tiles - done >= 64 * UMAX; done += 64 * UMAX) add_tile_block<UMAX, false>(partials, done + lane, num_tiles, v);
+    if (UMAX == 32 && num_tiles - done >= 64 * 16) { add_tile_block<16, false>(partials, done + lane, num_tiles, v); done += 64 * 16; }
+    for (; done < num_tiles; done += 64 * 8) add_tile_block<8, true>(partials, done + lane, num_tiles, v);
 #pragma unroll
     for (int j = 0; j < 5; ++j) v[j] = wave_sum(v[j]);
     if (lane == 0) {
@@ -451,7 +464,7 @@ __device__ __forceinline__ void reduce_tiles(const float *partials, int num_tile
 // Sum the per-thread loss terms over the workgroup and store them for the final reduction.  With a
 // completion counter (zero before the launch) the workgroup that finishes last does that reduction
 // itself and leaves the counter at zero again; without one a separate launch follows.
-template <int NW = NWAVES>
+template <int NW = NWAVES, int UMAX = 16>
 __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], const LossArgs &a, int tile, int tid,
                                                float s, float v, float h, float k, float bad)
 {
@@ -486,7 +499,7 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], con
     // Every other tile's sums were acknowledged before its count.  Copies of those lines that this die's
     // cache may hold from an earlier launch are dropped before they are read (acquire: invalidate only).
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    reduce_tiles(a.partials, (int)gridDim.x, a.inv_M, a.vf_coeff, a.ent_coeff, a.kl_coeff, a.loss5, lane);
+    reduce_tiles<UMAX>(a.partials, (int)gridDim.x, a.inv_M, a.vf_coeff, a.ent_coeff, a.kl_coeff, a.loss5, lane);
     if (lane == 0) *a.done_count = 0;
 }
 

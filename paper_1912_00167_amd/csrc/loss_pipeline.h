@@ -385,7 +385,8 @@ void loss_static(const LossArgs a)
         }
         return;
     }
-    store_partials<NW>(red, a, tile + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    // (the final sum's load blocks sized to the registers this policy's kernels have anyway)
+    store_partials<NW, Policy::SIMD_WAVES == 2 && !CACHED ? 32 : 16>(red, a, tile + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
 
