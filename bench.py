@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 # HBM bytes per launch of the fused loss kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the
 # same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md, ..._cat18_C4_fused.md).  Tied to the
 # kernel as profiled: to be set to None whenever the kernel changes until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"C5": 1.0342e9, "C4": 2.709e8}
+MEASURED_TRAFFIC_BYTES = {"C5": 1.0340e9, "C4": 2.710e8}
 
 
 def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False) -> int:
