@@ -18,7 +18,9 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "impact_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# ORACLE_LIB_OVERRIDE: load this library instead (the tests that plant mistakes in a copy of the C source
+# and check that the pins notice them set it; nothing else does)
+_LIB = os.environ.get("ORACLE_LIB_OVERRIDE") or os.path.join(_HERE, "liboracle.so")
 
 CATEGORICAL = 0
 GAUSSIAN = 1
@@ -26,6 +28,8 @@ GAUSSIAN = 1
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (a few hundred ms)."""
+    if os.environ.get("ORACLE_LIB_OVERRIDE"):
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
