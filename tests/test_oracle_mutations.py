@@ -85,3 +85,55 @@ def test_the_untouched_source_passes_the_same_way(source, tmp_path):
     run = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", "-m", "not gpu"]
                          + [os.path.join(HERE, p) for p in pins], env=env, cwd=ROOT, capture_output=True, text=True)
     assert run.returncode == 0, run.stdout[-800:]
+
+
+# ---- the ring's bookkeeping oracle (plain Python): the same game, in-process ----------------------
+
+RING_SRC = os.path.join(ROOT, "oracle", "buffer.py")
+# (Not in the list: taking the search for an empty slot out of insert.  Items retire in the order they were
+# inserted, so the live slots form one arc of the ring and the write cursor, which follows its newest end,
+# stands on an empty slot whenever there is one: on every reachable state that search finds its slot at once.)
+RING_MUTATIONS = [
+    ("an item lives for K + 1 traversals", "if self.count[s] == self.K:", "if self.count[s] == self.K + 1:"),
+    ("the count returned includes this traversal", "counts.append(self.count[s])", "counts.append(self.count[s] + 1)"),
+    ("sample does not skip empty slots", "while self.count[self.r] < 0:", "while False:"),
+    ("the read cursor stays where it is", "            self.r = (self.r + 1) % self.N\n        return slots, counts", "        return slots, counts"),
+    ("an insert that fits exactly is refused", "if self.N - self.num_live() < n:", "if self.N - self.num_live() <= n:"),
+    ("a fresh item starts at count one", "self.count[self.w] = 0", "self.count[self.w] = 1"),
+]
+
+
+def _ring_pins(monkeypatch, module):
+    import test_oracle_buffer as pins
+    for name in ("RingOracle", "BufferOracle", "BufferFull", "NotEnoughLive"):
+        monkeypatch.setattr(pins, name, getattr(module, name))
+    for N, K in [(1, 1), (3, 1), (4, 2), (5, 3), (8, 3)]:
+        pins.test_every_item_is_replayed_exactly_K_times_in_order(N, K)
+    pins.test_full_ring_without_inserts_is_K_passes_of_the_same_minibatches()
+    pins.test_fifo_and_replacement_after_discard()
+    pins.test_bad_arguments()
+
+
+def _ring_module(source, name):
+    import types
+    module = types.ModuleType("oracle." + name)
+    module.__file__ = RING_SRC
+    module.__package__ = "oracle"                  # its relative import of the bf16 rounding resolves as in the original
+    exec(compile(source, RING_SRC, "exec"), module.__dict__)
+    return module
+
+
+@pytest.mark.timeout(60)
+@pytest.mark.parametrize("mi", range(len(RING_MUTATIONS)), ids=[m[0] for m in RING_MUTATIONS])
+def test_a_planted_mistake_in_the_ring_fails_a_pin(monkeypatch, mi):
+    what, old, new = RING_MUTATIONS[mi]
+    with open(RING_SRC) as f:
+        source = f.read()
+    assert source.count(old) == 1, f"'{old}' must occur exactly once in the ring oracle"
+    with pytest.raises((AssertionError, KeyError, IndexError, pytest.fail.Exception)):
+        _ring_pins(monkeypatch, _ring_module(source.replace(old, new), "ring_mutant"))
+
+
+def test_the_untouched_ring_passes_the_same_way(monkeypatch):
+    with open(RING_SRC) as f:
+        _ring_pins(monkeypatch, _ring_module(f.read(), "ring_copy"))
