@@ -142,6 +142,19 @@ def table(torch, binding, names, repeats: int = 5) -> None:
             us.append(e0.elapsed_time(e1) * 1e3 / n_calls)
         return float(np.median(us))
 
+    def timed_wall(call, n_calls):
+        for i in range(max(10, n_calls)):
+            call(i)
+        torch.cuda.synchronize()
+        us = []
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            for i in range(n_calls):
+                call(i)
+            torch.cuda.synchronize()
+            us.append((time.perf_counter() - t0) * 1e6 / n_calls)
+        return float(np.median(us))
+
     gc.collect()
     gc.disable()       # a full collection (about 30 ms with torch loaded) would land in one of the timing loops
     print("| workload | line | us/call | steps/s | algorithmic GB/s | % of 8 TB/s | clipped | truncated |")
@@ -175,6 +188,16 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         t_p = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
                                                                       boot[i % nq], cfg, out=out_p[i % 2], workspace=ws), n_calls)
         del out_p
+        # successive calls alternating between two streams and two lanes (wall clock: no stream sees both)
+        lanes = [dict(stream=torch.cuda.Stream(), cfg=binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_LANE(n + 1)),
+                      ws=torch.empty_like(ws), outs=[binding.alloc_loss_out(T, B, W) for _ in range(2)]) for n in range(2)]
+
+        def two(i):
+            ln = lanes[i % 2]
+            binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq], boot[i % nq], ln["cfg"],
+                                                    out=ln["outs"][(i // 2) % 2], workspace=ln["ws"], stream=ln["stream"])
+        t_2 = timed_wall(two, n_calls)
+        del lanes
         t_b = None
         if wl.storage == "bf16":                     # the learner's distribution in bf16 as well (a dtype variant)
             lb = [x.to(torch.bfloat16) for x in learner]
@@ -199,7 +222,8 @@ def table(torch, binding, names, repeats: int = 5) -> None:
                               ("loss, time-major batch, per-step scalars as packed records", t_tp, algorithmic_bytes_per_step(wl)),
                               ("gather alone", t_g, 2 * resident),
                               ("fused gather + loss", t_f, algorithmic_bytes_per_step(wl)),
-                              ("fused, per-step scalars as packed records", t_p, algorithmic_bytes_per_step(wl))):
+                              ("fused, per-step scalars as packed records", t_p, algorithmic_bytes_per_step(wl)),
+                              ("fused, successive calls alternating between two streams", t_2, algorithmic_bytes_per_step(wl))):
             gbs = bps * steps / us / 1e3
             print(f"| {wl.name} | {line} | {us:.1f} | {steps / us * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | "
                   f"{clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
@@ -366,6 +390,45 @@ def main() -> int:
         variant = float(np.mean(kernel_times))
         state["outs"] = outs
     kernel_times = main_times
+
+    # Successive steps alternating between two streams (a lane of the buffer's completion counters, a
+    # workspace and output tensors each): one launch starts while the other drains.  Whole-step throughput
+    # only; a launch's own duration is not meaningful while two share the chip.
+    two_streams = None
+    if not args.packed_outputs and not args.no_variants:
+        n_var, n_warm = min(args.steps, 256), min(args.warmup, 128)      # (the device idled while the buffers below were made)
+        lanes = [dict(stream=torch.cuda.Stream(), cfg=binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_LANE(n + 1)),
+                      workspace=torch.empty_like(workspace),
+                      outs=[binding.alloc_loss_out(T, B, W) for _ in range(2)]) for n in range(2)]
+        staging = [torch.empty(B, dtype=torch.int32).pin_memory() for _ in range(n_var + n_warm)]   # one per step: nothing to wait for
+        staging_np = [p.numpy() for p in staging]
+        torch.cuda.synchronize()
+
+        def lane_step(i):
+            if binding.impact_buffer_num_live(buf) < B:
+                binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
+            binding.impact_buffer_sample(buf, B, staging_np[i], counts_np)
+            q = int(staging_np[i][0]) // B
+            ln = lanes[i % 2]
+            binding.impact_loss_fwd_bwd_from_buffer(buf, staging[i], learner[q % n_batches], values[q % n_batches],
+                                                    boot[q % n_batches], ln["cfg"], out=ln["outs"][(i // 2) % 2],
+                                                    workspace=ln["workspace"], stream=ln["stream"])
+        for i in range(n_warm):
+            lane_step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(n_warm, n_warm + n_var):
+            lane_step(i)
+        two_issued = (time.perf_counter() - t1) * 1e3 / n_var
+        torch.cuda.synchronize()
+        two_ms = (time.perf_counter() - t1) * 1e3 / n_var
+        for ln in lanes:
+            for o in ln["outs"]:
+                assert np.all(np.isfinite(o["loss5"].cpu().numpy()))
+        two_streams = {"ms_per_step": two_ms, "value": T * B / (two_ms * 1e-3), "host_issue_ms_per_step": two_issued,
+                       "algorithmic_GBps": algorithmic_bytes_per_step(wl) * T * B / (two_ms * 1e-3) / 1e9,
+                       "what": "successive steps alternate between two streams and two lanes of the buffer's completion "
+                               "counters, so that one launch starts while the other drains; whole-step throughput"}
     gc.enable()
     if args.series:
         with open(args.series, "w") as f:
@@ -400,11 +463,13 @@ def main() -> int:
                      "traffic": None if args.packed_outputs else MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)"},
     }
+    if two_streams is not None:
+        result.setdefault("variants", {})["two_streams"] = two_streams
     if variant is not None:
-        result["variants"] = {"packed_step_outputs": {
+        result.setdefault("variants", {})["packed_step_outputs"] = {
             "kernel_ms": variant, "frac": bytes_per_call / (variant * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "what": "grad_values, vs, adv written as one 16-byte record per step (whole lines per wavefront) "
-                    "instead of three [T][B] tensors; same algorithmic bytes"}}
+                    "instead of three [T][B] tensors; same algorithmic bytes"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, max(8, min(B, 4096)))
     print(json.dumps(result))

@@ -86,7 +86,9 @@ typedef struct {
  *                           bit 1: surrogate ratio pi_theta / pi_worker (R_2 of Section 4.1's ablation)
  *                                  instead of the target-worker clipped one; rho_clip is then unused
  *                           bit 2: learner_dist holds bfloat16 values (a network under mixed precision);
- *                                  the gradients are fp32 all the same */
+ *                                  the gradients are fp32 all the same
+ *                           bits 8-11: lane of impact_loss_fwd_bwd_from_buffer, 0..15 (see there); other
+ *                                  calls ignore it */
 typedef struct {
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;
@@ -98,6 +100,8 @@ typedef struct {
 #define IMPACT_FLAG_FORCE_GENERIC 1u
 #define IMPACT_FLAG_RATIO_WORKER 2u
 #define IMPACT_FLAG_LEARNER_BF16 4u
+#define IMPACT_FLAG_LANE(n) (((uint32_t)(n) & 15u) << 8)
+#define IMPACT_LANES 16
 
 /* The buffer-resident part of a batch (what a worker sent plus the target
  * network's evaluation appended at k = 0, Algorithm 1).  All device pointers.
@@ -264,9 +268,13 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * yields, the kernel is given the first slot and reads no index array.
  * dist, T, A and the batch dtype come from the buffer's descriptor.
  * One launch: the workgroup that finishes last also sums the loss terms, using
- * a counter in the buffer's storage that the first call on a handle clears (in
- * stream order).  Calls on one handle must therefore not overlap on the device:
- * issue them on one stream, or order them with events.  The call enqueues kernel
+ * a counter in the buffer's storage that the first call of its lane clears (in
+ * stream order).  The storage holds one such counter per lane: calls of one
+ * lane (cfg->flags, IMPACT_FLAG_LANE; lane 0 unless set) must not overlap on the
+ * device, so issue them on one stream or order them with events; calls of
+ * different lanes may run side by side, e.g. the steps of successive batches
+ * alternating between two streams so that one launch starts while the other
+ * drains, each lane with a workspace and outputs of its own.  The call enqueues kernel
  * launches only (no memset, no copy, no allocation), so it can be captured in a
  * HIP graph and replayed. */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,

@@ -32,6 +32,12 @@ IMPACT_BF16 = 1
 IMPACT_FLAG_FORCE_GENERIC = 1
 IMPACT_FLAG_RATIO_WORKER = 2
 IMPACT_FLAG_LEARNER_BF16 = 4
+IMPACT_LANES = 16
+
+
+def IMPACT_FLAG_LANE(n: int) -> int:
+    return (n & 15) << 8
+
 IMPACT_BUFFER_CACHE_LOGP = 1
 IMPACT_BUFFER_NO_TARGET_DIST = 2
 

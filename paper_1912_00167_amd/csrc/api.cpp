@@ -79,7 +79,7 @@ struct impact_buffer {
     char *storage;
     std::vector<int32_t> count;   // -1 empty, else traversals so far (0 .. K-1)
     int32_t w, r, live;
-    bool sync_zeroed = false;     // the completion counter in the storage has been cleared
+    uint32_t lanes_zeroed = 0;    // bit n: the completion counter of lane n in the storage has been cleared
     std::mutex mu;
 
     int W() const { return desc.dist == IMPACT_CATEGORICAL ? desc.A : 2 * desc.A; }
@@ -556,12 +556,16 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
     // The storage holds a completion counter with which the kernel's last workgroup finishes the loss
     // terms itself (no second launch).  The kernel leaves it at zero; before the first use it is cleared
     // here, by a kernel in stream order (a fill that a caller's graph capture records like any other launch).
-    unsigned *done_count = reinterpret_cast<unsigned *>(buf->storage + buf->planes.sync);
+    // One counter per lane, 16 bytes apart: calls of different lanes may be on the device together.
+    if (!cfg) return IMPACT_ERR_INVALID_ARG;
+    const uint32_t lane = (cfg->flags >> 8) & (IMPACT_LANES - 1);
+    static_assert(IMPACT_LANES * 16 <= kPlaneAlign, "the counters fit the block reserved for them");
+    unsigned *done_count = reinterpret_cast<unsigned *>(buf->storage + buf->planes.sync + lane * 16);
     {
         std::lock_guard<std::mutex> g(buf->mu);
-        if (!buf->sync_zeroed) {
+        if (!(buf->lanes_zeroed >> lane & 1u)) {
             launch_zero_words(done_count, 1, static_cast<hipStream_t>(stream));
-            buf->sync_zeroed = true;
+            buf->lanes_zeroed |= 1u << lane;
         }
     }
     return run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, slot_first, learner_dist, values,

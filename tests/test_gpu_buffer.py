@@ -258,6 +258,54 @@ def test_fused_calls_in_a_row_on_one_handle(env):
     buf.close()
 
 
+def test_calls_of_different_lanes_run_side_by_side_on_two_streams(env):
+    """Each lane has a completion counter of its own in the buffer's storage, so the steps of successive
+    batches may alternate between two streams (one launch starts while the other drains).  The results
+    are those of the same calls made one after the other: checked against the oracle once, then bit for bit."""
+    torch, binding = env
+    wl = shape_workload(workloads.C5, T=64, B=4096, num_slots=8192)
+    say("case lanes on two streams")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, 2048, stream=12)
+    d = to_device(x, torch)
+    for _ in range(4):                              # the ring holds the 2048 trajectories four times over
+        binding.impact_buffer_insert(buf, d)
+    rng = np.random.default_rng(6)
+    batches = []
+    for q in range(4):
+        slots = rng.permutation(8192)[: wl.B].astype(np.int32)
+        xb = workloads.take_trajectories(x, slots % 2048)
+        batches.append((torch.from_numpy(slots).cuda(), xb,
+                        [torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap")]))
+    cfg0 = binding.config_from_hyper(wl.hyper)
+    serial = []
+    for slots, xb, (learner, values, boot) in batches:
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, slots, learner, values, boot, cfg0)
+        torch.cuda.synchronize()
+        serial.append({k: v.clone() for k, v in out.items()})
+    check_against_oracle(wl, batches[0][1], {k: v.cpu().numpy() for k, v in serial[0].items()}, label="lane 0, alone")
+
+    lanes = (3, 15)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cfgs = [binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_LANE(n)) for n in lanes]
+    ws = [torch.empty(binding.impact_loss_workspace_bytes(wl.dist, wl.T, wl.B, wl.A), dtype=torch.uint8, device="cuda")
+          for _ in lanes]
+    outs = [binding.alloc_loss_out(wl.T, wl.B, wl.W) for _ in range(8)]
+    torch.cuda.synchronize()
+    for rnd in range(5):
+        for i in range(8):                          # eight launches in flight over the two streams, then a look at each
+            slots, _, (learner, values, boot) = batches[i % 4]
+            binding.impact_loss_fwd_bwd_from_buffer(buf, slots, learner, values, boot, cfgs[i % 2], out=outs[i],
+                                                    workspace=ws[i % 2], stream=streams[i % 2])
+        torch.cuda.synchronize()
+        for i in range(8):
+            for k, v in serial[i % 4].items():
+                assert torch.equal(outs[i][k], v), (rnd, i, k)
+            outs[i]["loss5"].fill_(float("nan"))
+        torch.cuda.synchronize()
+    buf.close()
+
+
 def test_fused_full_size_c5(env):
     """The headline configuration as the benchmark launches it: a full ring of 65536 bf16 slots, 16384
     sampled trajectories of 128 steps, D = 17; every output element against the oracle.  (The ring holds
