@@ -318,7 +318,7 @@ def main() -> int:
     # Only every `every`-th launch is bracketed: the two records between back-to-back launches cost the
     # stream about 5 us per step (217 us per step against 211 with every fourth launch bracketed), which
     # would be charged to the throughput; the sampled launches give the kernel's average duration.
-    every = args.event_every
+    every = args.event_every if args.steps >= 8 * args.event_every else 1     # a short run brackets every launch
     assert depth % every == 0
 
     def retire(j, keep):
