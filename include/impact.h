@@ -276,7 +276,8 @@ impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T
  * alternating between two streams so that one launch starts while the other
  * drains, each lane with a workspace and outputs of its own.  The call enqueues kernel
  * launches only (no memset, no copy, no allocation), so it can be captured in a
- * HIP graph and replayed. */
+ * HIP graph and replayed (a lane whose first call is a captured one is cleared by
+ * the graph at every replay, and once more by its first call outside a capture). */
 impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B, const int32_t *dev_slots,
                                                 const void *learner_dist, const float *values,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,

@@ -565,7 +565,14 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
         std::lock_guard<std::mutex> g(buf->mu);
         if (!(buf->lanes_zeroed >> lane & 1u)) {
             launch_zero_words(done_count, 1, static_cast<hipStream_t>(stream));
-            buf->lanes_zeroed |= 1u << lane;
+            // A launch that is only being recorded into a graph has cleared nothing yet: the graph keeps its
+            // clearing launch (every replay then clears again, which is harmless), and the next call clears too.
+            hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capturing) != hipSuccess) {
+                (void)hipGetLastError();
+                capturing = hipStreamCaptureStatusNone;
+            }
+            if (capturing == hipStreamCaptureStatusNone) buf->lanes_zeroed |= 1u << lane;
         }
     }
     return run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, slot_first, learner_dist, values,

@@ -434,6 +434,46 @@ def test_fused_step_replays_in_a_captured_graph(env):
     buf.close()
 
 
+def test_a_lane_first_used_inside_a_graph_capture(env):
+    """The first call of a lane clears its completion counter; a call that is only recorded into a graph has
+    cleared nothing yet.  The buffer's storage starts out as garbage here, the first call ever made on the
+    handle is a captured one, and both the replays and the eager calls that follow have to be right."""
+    torch, binding = env
+    wl = shape_workload(workloads.C3, B=64, num_slots=128)
+    say("case lane first used under capture")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    buf.storage[-256:] = 0x5A                            # the block of completion counters at the end of the storage
+    x = workloads.make_trajectories(wl, 128, stream=22)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots_np = np.random.default_rng(3).permutation(128)[:64].astype(np.int32)
+    dev_slots = torch.from_numpy(slots_np).cuda()
+    xb = workloads.take_trajectories(x, slots_np)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    out = binding.alloc_loss_out(wl.T, 64, wl.W)
+    ws = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, wl.T, 64, wl.A), dtype=torch.uint8, device="cuda")
+    call = lambda lane: binding.impact_loss_fwd_bwd_from_buffer(
+        buf, dev_slots, learner, values, boot, binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_LANE(lane)), out=out, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(5)
+    torch.cuda.synchronize()
+
+    def result(run):
+        for v in out.values():
+            v.fill_(float("nan"))
+        run()
+        torch.cuda.synchronize()
+        return {k: v.clone() for k, v in out.items()}
+    first = result(graph.replay)
+    check_against_oracle(replace(wl, B=64), xb, {k: v.cpu().numpy() for k, v in first.items()}, label="first replay")
+    for run in (lambda: call(0), lambda: call(5), graph.replay, lambda: call(5), graph.replay):
+        again = result(run)
+        for k in first:
+            assert torch.equal(again[k], first[k]), k
+    buf.close()
+
+
 def test_out_of_range_slot_is_flagged_not_dereferenced(env):
     torch, binding = env
     wl = shape_workload(workloads.C1, num_slots=16)
