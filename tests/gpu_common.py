@@ -142,3 +142,27 @@ def gpu_loss(torch, binding, wl, x, hyper=None, flags=0, want_targets=True):
     binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg, out=out)
     torch.cuda.synchronize()
     return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+def wide_range_inputs(wl, x, seed):
+    """The batch with peaked and nearly flat policies: categorical logits scaled to a magnitude of up to 40;
+    Gaussian standard deviations from about e^-4 to e^1.5, one offset per step and dimension moving the three
+    policies' log-sigma together and scaling the distances between their means with it (so that they stay as
+    close, in standard deviations, as the workload made them), actions out to four standard deviations."""
+    x = dict(x)
+    rng = np.random.default_rng(seed)
+    if wl.dist == "categorical":
+        for k, scale in (("learner", 10.0), ("target", 10.0), ("worker", 8.0)):
+            x[k] = (x[k] * scale).astype(np.float32)
+        return x
+    D = wl.A
+    u = rng.uniform(-2.5, 1.0, size=x["learner"][..., D:].shape)
+    centre = x["learner"][..., :D].astype(np.float64) * 3.0
+    for k in ("target", "worker", "learner"):
+        p = x[k].astype(np.float64)
+        p[..., :D] = centre + (p[..., :D] - x["learner"][..., :D]) * np.exp(u)
+        p[..., D:] += u
+        x[k] = p.astype(np.float32)
+    mu, sigma = x["worker"][..., :D].astype(np.float64), np.exp(x["worker"][..., D:].astype(np.float64))
+    x["actions"] = (mu + sigma * rng.uniform(-4.0, 4.0, size=mu.shape)).astype(np.float32)
+    return x

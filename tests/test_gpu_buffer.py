@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import workloads
-from gpu_common import check_against_oracle, say, shape_workload, to_device
+from gpu_common import check_against_oracle, say, shape_workload, to_device, wide_range_inputs
 from oracle.buffer import BufferOracle, bf16_bits_to_f32
 
 pytestmark = pytest.mark.gpu
@@ -471,6 +471,31 @@ def test_a_lane_first_used_inside_a_graph_capture(env):
         again = result(run)
         for k in first:
             assert torch.equal(again[k], first[k]), k
+    buf.close()
+
+
+@pytest.mark.parametrize("name,storage", [("C4", "f32"), ("C4", "bf16"), ("C5", "bf16"), ("C5", "f32")])
+@pytest.mark.parametrize("cached", [False, True], ids=["full", "cached"])
+def test_fused_wide_range_inputs(env, name, storage, cached):
+    """Peaked and nearly flat policies, ratios over fifty orders of magnitude, through the ring (rounded to bf16
+    where it stores bf16) and, with cached log-probabilities, through the stored fp64 pair."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], T=24, B=64, num_slots=64, storage=storage)
+    x = wide_range_inputs(wl, workloads.make_trajectories(wl, 64, stream=33), seed=10)
+    say(f"case fused wide range {name} {storage} cached={cached}")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, 64, wl.K, storage, flags=binding.IMPACT_BUFFER_CACHE_LOGP if cached else 0)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots = np.random.default_rng(3).permutation(64).astype(np.int32)
+    xb = workloads.take_trajectories(x, slots)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    for flag_bits in (0, 1):
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot,
+                                                      binding.config_from_hyper(wl.hyper, flag_bits))
+        torch.cuda.synchronize()
+        got = {k: v.cpu().numpy() for k, v in out.items()}
+        for k, v in got.items():
+            assert np.all(np.isfinite(v)), k
+        check_against_oracle(wl, xb, got, cached="with_target" if cached else None, label=f"fused wide range {name} {storage}")
     buf.close()
 
 

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import workloads
-from gpu_common import check_against_oracle, gpu_loss, say, shape_workload
+from gpu_common import check_against_oracle, gpu_loss, say, shape_workload, wide_range_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -224,25 +224,7 @@ def test_wide_range_inputs(env, dist, flags):
     torch, binding = env
     base = workloads.C4 if dist == "categorical" else workloads.C5
     wl = shape_workload(base, T=24, B=64, storage="f32")
-    x = dict(workloads.make_batch(wl, stream=31))
-    rng = np.random.default_rng(9)
-    if dist == "categorical":
-        for k, scale in (("learner", 10.0), ("target", 10.0), ("worker", 8.0)):
-            x[k] = (x[k] * scale).astype(np.float32)
-    else:
-        # one offset per step and dimension moves the three policies' log-sigma together (from about e^-4 to e^1.5)
-        # and scales the distances between their means with it, so that they stay as close, in standard
-        # deviations, as the workload made them
-        D = wl.A
-        u = rng.uniform(-2.5, 1.0, size=x["learner"][..., D:].shape)
-        centre = x["learner"][..., :D].astype(np.float64) * 3.0
-        for k in ("target", "worker", "learner"):
-            p = x[k].astype(np.float64)
-            p[..., :D] = centre + (p[..., :D] - x["learner"][..., :D]) * np.exp(u)
-            p[..., D:] += u
-            x[k] = p.astype(np.float32)
-        mu, sigma = x["worker"][..., :D].astype(np.float64), np.exp(x["worker"][..., D:].astype(np.float64))
-        x["actions"] = (mu + sigma * rng.uniform(-4.0, 4.0, size=mu.shape)).astype(np.float32)
+    x = wide_range_inputs(wl, workloads.make_batch(wl, stream=31), seed=9)
     say(f"case wide range {dist} flags={flags}")
     got = gpu_loss(torch, binding, wl, x, flags=flags)
     for k, v in got.items():
