@@ -65,6 +65,7 @@ HYPERS = [
     dict(kl_coeff=0.7, ent_coeff=0.05), dict(rho_bar=1.5, c_bar=0.7), dict(rho_bar=0.0), dict(c_bar=0.0),
     dict(vf_coeff=0.5, ent_coeff=0.0, kl_coeff=0.0), dict(eps=0.0), dict(rho_clip=1.0),
     dict(ratio_mode=1), dict(ratio_mode=1, kl_coeff=0.5, eps=0.1),      # the ablation's ratio pi_theta / pi_worker
+    dict(gamma=0.0), dict(lam=0.0), dict(gamma=1.0, lam=1.0, rho_bar=3.0, c_bar=3.0),
 ]
 
 
@@ -230,3 +231,26 @@ def test_wide_range_inputs(env, dist, flags):
     for k, v in got.items():
         assert np.all(np.isfinite(v)), k
     check_against_oracle(wl, x, got, label=f"wide range {dist}")
+
+
+@pytest.mark.parametrize("dist", ["categorical", "gaussian"])
+@pytest.mark.parametrize("pattern", ["every step", "none", "last step only", "first step only"])
+def test_episode_end_patterns(env, dist, pattern):
+    """The flag cuts the bootstrap and the carry at its own step: all steps terminal (every advantage is its own
+    delta), none, and a single flag at either end of the trajectory, on both kernel families."""
+    torch, binding = env
+    base = workloads.C4 if dist == "categorical" else workloads.C5
+    wl = shape_workload(base, T=37, B=24, storage="f32")
+    x = dict(workloads.make_batch(wl, stream=41))
+    d = np.zeros_like(x["dones"])
+    if pattern == "every step":
+        d[:] = 1
+    elif pattern == "last step only":
+        d[-1] = 1
+    elif pattern == "first step only":
+        d[0] = 1
+    x["dones"] = d
+    say(f"case episode ends {dist} {pattern}")
+    for flags in (0, FORCE_GENERIC):
+        got = gpu_loss(torch, binding, wl, x, flags=flags)
+        check_against_oracle(wl, x, got, label=f"episode ends {pattern} {dist} flags={flags}")
