@@ -335,6 +335,24 @@ def test_fused_full_size_c5(env):
                                                   boot, binding.config_from_hyper(wl.hyper))
     torch.cuda.synchronize()
     got = {k: v.cpu().numpy() for k, v in out.items()}
+    # the same batch as the benchmark's two-stream variant issues it: four launches over two lanes and two streams,
+    # in flight together, each with the bits of the launch above
+    say("  two lanes")
+    dev_slots = torch.from_numpy(np.ascontiguousarray(slots)).cuda()
+    lanes = [dict(stream=torch.cuda.Stream(), cfg=binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_LANE(n + 1)),
+                  ws=torch.empty(binding.impact_loss_workspace_bytes(wl.dist, wl.T, wl.B, wl.A), dtype=torch.uint8, device="cuda"),
+                  outs=[binding.alloc_loss_out(wl.T, wl.B, wl.W) for _ in range(2)]) for n in range(2)]
+    torch.cuda.synchronize()
+    for i in range(4):
+        ln = lanes[i % 2]
+        binding.impact_loss_fwd_bwd_from_buffer(buf, dev_slots, learner, values, boot, ln["cfg"], out=ln["outs"][i // 2],
+                                                workspace=ln["ws"], stream=ln["stream"])
+    torch.cuda.synchronize()
+    for ln in lanes:
+        for o in ln["outs"]:
+            for k in out:
+                assert torch.equal(o[k], out[k]), k
+    del lanes
     buf.close()
     say("  oracle")
     check_against_oracle(wl, xb, got, label="fused C5 full")
