@@ -434,6 +434,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.slots = dev_slots; a.num_slots = num_slots; a.slot_first = slot_first;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;
     a.rho_clip = cfg->rho_clip;
+    a.log_rho_clip = std::isinf(cfg->rho_clip) ? (double)INFINITY : std::log((double)cfg->rho_clip);
     a.ratio_worker = (cfg->flags & IMPACT_FLAG_RATIO_WORKER) ? 1 : 0;
     a.clip_lo = std::isinf(cfg->eps) ? -(double)INFINITY : 1.0 - (double)cfg->eps;
     a.clip_hi = std::isinf(cfg->eps) ? (double)INFINITY : 1.0 + (double)cfg->eps;

@@ -45,6 +45,7 @@ struct LossArgs {
     // hyper-parameters, pre-digested on the host
     float gamma, lambda, rho_bar, c_bar;
     float rho_clip;           // target-worker clipping rho; may be +inf
+    double log_rho_clip;      // its logarithm (+inf with it)
     int ratio_worker;         // surrogate ratio pi_theta / pi_worker instead (Section 4.1, R_2)
     double clip_lo, clip_hi;  // 1 - eps, 1 + eps (-inf / +inf when eps = +inf)
     float vf_coeff, ent_coeff, kl_coeff;

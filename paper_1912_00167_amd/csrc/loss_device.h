@@ -354,10 +354,23 @@ __device__ __forceinline__ ScanInputs scan_inputs(const LossArgs &a, double w, f
 // Surrogate ratio R = pi_theta / max(pi_target, pi_worker / rho_clip) from R1 = pi_theta / pi_target
 // and w = pi_target / pi_worker: the maximum picks pi_target when w >= 1 / rho_clip, and otherwise
 // R = R1 * w * rho_clip (the first form of J_AIS).  rho_clip = +inf never takes the second branch.
+// (The product form is for policies whose ratios stay inside the fp64 range: softmax policies with logits
+// of any sane magnitude.  R1 = inf next to w = 0 would give NaN; Gaussian policies, whose log-probabilities
+// reach the thousands, use the log form below.)
 __device__ __forceinline__ double surrogate_ratio(const LossArgs &a, double R1, double w)
 {
     if (a.ratio_worker) return R1 * w;     // pi_theta / pi_worker: Section 4.1's R_2
     return (w * (double)a.rho_clip >= 1.0) ? R1 : R1 * w * (double)a.rho_clip;
+}
+
+// The same in log space, from lr1 = log(pi_theta / pi_target) and lw = log(pi_target / pi_worker):
+// log R = lr1 + min(0, lw + log rho_clip), exponentiated once by the caller.  Either ratio alone may lie
+// far outside the fp64 range (pi_theta / pi_target = e^1000 where the target gives the action next to no
+// probability, with pi_target / pi_worker = e^-1000) while R itself is moderate.
+__device__ __forceinline__ double surrogate_log_ratio(const LossArgs &a, double lr1, double lw)
+{
+    if (a.ratio_worker) return lr1 + lw;
+    return lr1 + fmin(0.0, lw + a.log_rho_clip);
 }
 
 // Surrogate value s = min(R adv, clip(R) adv) and the weight g = dL/dlogp_theta(a) of the policy term.

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             const float Vn = (t + 1 < a.T) ? a.values[s_tm + a.B] : a.bootstrap[b];
             const float r = widen(((const ST *)a.rewards)[s_buf]);
             const bool done = a.dones[s_buf] != 0;
-            double w, R1;
+            double lw, lr1;      // log(pi_target / pi_worker), log(pi_theta / pi_target) at the action taken
             if (DIST == IMPACT_CATEGORICAL) {
                 act = ((const int *)act_slot)[SLOT ? (size_t)t : s_tm];
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
@@ -99,16 +99,16 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 const double xl = (double)widen(zl[act]) - (double)m_l;
                 const double logS_l = log(S_l), logS_t = log(S_t);
                 if (cached) {
-                    w = exp(lp2[1] - lp2[0]);
-                    R1 = exp((xl - logS_l) - lp2[1]);
+                    lw = lp2[1] - lp2[0];
+                    lr1 = (xl - logS_l) - lp2[1];
                 } else {
                     float m_w;
                     double S_w;
                     softmax_stats(zw, A, m_w, S_w);
                     const double xw = (double)widen(zw[act]) - (double)m_w;
                     const double xt = (double)widen(zt[act]) - (double)m_t;
-                    w = exp(xt - xw) * (S_w / S_t);
-                    R1 = exp(xl - xt) * (S_t / S_l);
+                    lw = (xt - logS_t) - (xw - log(S_w));
+                    lr1 = (xl - logS_l) - (xt - logS_t);
                 }
                 for (int k = 0; k < A; ++k) {
                     const double lpl = ((double)widen(zl[k]) - (double)m_l) - logS_l;
@@ -121,12 +121,12 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             } else {
                 const double ll = gauss_logp(zl, av, A);
                 if (cached) {                      // the cached values carry the -D/2 log 2pi that gauss_logp omits
-                    w = exp(lp2[1] - lp2[0]);
-                    R1 = exp((ll - A * kHalfLog2Pi) - lp2[1]);
+                    lw = lp2[1] - lp2[0];
+                    lr1 = (ll - A * kHalfLog2Pi) - lp2[1];
                 } else {
-                    const double lw = gauss_logp(zw, av, A), lt = gauss_logp(zt, av, A);
-                    w = exp(lt - lw);
-                    R1 = exp(ll - lt);
+                    const double lpw = gauss_logp(zw, av, A), lpt = gauss_logp(zt, av, A);
+                    lw = lpt - lpw;
+                    lr1 = ll - lpt;
                 }
                 for (int d = 0; d < A; ++d) {
                     const double ls = (double)widen(zl[A + d]);
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 }
                 H += A * (kHalfLog2Pi + 0.5);
             }
-            sc = scan_inputs(a, w, r, done, V, Vn);
-            R = surrogate_ratio(a, R1, w);
+            sc = scan_inputs(a, exp(lw), r, done, V, Vn);
+            R = exp(surrogate_log_ratio(a, lr1, lw));
         }
         sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
         sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;

@@ -28,6 +28,7 @@ struct GaussPolicy {
         double act[DH];                            // action (converted once, used by all three policies)
         float tgm[DH], tgl[DH];                    // target mean and log-std of my dimensions, for the KL term
         double Qt, St;                             // the target's Q and S
+        double lw;                                 // log(pi_target(a) / pi_worker(a))
     };
 
     // my i-th dimension; only the last one can fall past D (padding lane), where a valid one is re-read
@@ -63,7 +64,8 @@ struct GaussPolicy {
             }
             k.St = St;
             k.Qt = -(lp[1] + D * kHalfLog2Pi) - St;
-            return exp64(lp[1] - lp[0], exp_tbl);
+            k.lw = lp[1] - lp[0];
+            return exp64(k.lw, exp_tbl);
         }
         double Qw = 0.0, Sw = 0.0;
 #pragma unroll
@@ -88,7 +90,8 @@ struct GaussPolicy {
         k.Qt = pair_sum<P>(Qt);
         k.St = pair_sum<P>(St);
         // pi_target(a) / pi_worker(a) = exp((Q_w + S_w) - (Q_t + S_t))
-        return exp64((pair_sum<P>(Qw + Sw) - k.Qt) - k.St, exp_tbl);
+        k.lw = (pair_sum<P>(Qw + Sw) - k.Qt) - k.St;
+        return exp64(k.lw, exp_tbl);
     }
 
     // own: this step's learner parameters in LDS; grad: where its gradients go (the same place for fp32
@@ -112,8 +115,9 @@ struct GaussPolicy {
         Ql = pair_sum<P>(Ql);
         Sl = pair_sum<P>(Sl);
         H = Sl + D * (kHalfLog2Pi + 0.5);
-        // pi_theta / pi_target = exp((Q_t + S_t) - (Q_l + S_l))
-        const double R = surrogate_ratio(a, exp64((k.Qt - Ql) + (k.St - Sl), exp_tbl), w);
+        // log(pi_theta / pi_target) = (Q_t + S_t) - (Q_l + S_l); the ratio is formed in log space and
+        // exponentiated once (the two factors alone can leave the fp64 range in opposite directions)
+        const double R = exp64(surrogate_log_ratio(a, (k.Qt - Ql) + (k.St - Sl), k.lw), exp_tbl);
         double g;
         surrogate(a, R, adv, s, g);
         // With E = 1 / (2 sigma^2):  dL/dmu = (2g (a - mu) + 2 ck (mu - mu_t)) E

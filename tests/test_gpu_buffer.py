@@ -358,6 +358,48 @@ def test_fused_full_size_c5(env):
     check_against_oracle(wl, xb, got, label="fused C5 full")
 
 
+def test_fused_full_size_c4(env):
+    """The large discrete workload as the benchmark launches it: fp32 ring of 32768 slots, 8192 sampled
+    trajectories of 100 steps, 18 actions, the slots scattered over the ring; every output element against
+    the oracle.  (This is the three-wavefronts-per-tile form of the fused categorical kernel.)"""
+    torch, binding = env
+    wl = workloads.C4
+    distinct, block = 8192, 4096
+    say(f"case fused full C4 T={wl.T} B={wl.B} A={wl.A} slots={wl.num_slots}: generating")
+    parts = [workloads.make_trajectories(wl, block, stream=600 + i) for i in range(distinct // block)]
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    for rnd in range(wl.num_slots // distinct):
+        for i, part in enumerate(parts):
+            slots_in = binding.impact_buffer_insert(buf, to_device(part, torch))
+            assert int(slots_in[0]) == rnd * distinct + i * block
+    x = {k: np.concatenate([p_[k] for p_ in parts], axis=0 if k == "bootstrap" else 1) for k in parts[0]}
+    del parts
+    ring = np.concatenate([binding.impact_buffer_sample(buf, wl.B)[0].copy() for _ in range(wl.num_slots // wl.B)])
+    assert sorted(ring.tolist()) == list(range(wl.num_slots))
+    slots = np.ascontiguousarray(np.random.default_rng(6).permutation(ring)[: wl.B].astype(np.int32))
+    xb = workloads.take_trajectories(x, slots % distinct)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    say("  gpu")
+    out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot,
+                                                  binding.config_from_hyper(wl.hyper))
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    # a run of consecutive slots across the ring's end, in page-locked memory: what the benchmark's sampling
+    # yields (the kernel is then given the first slot and reads no index array)
+    run = ((wl.num_slots - 3000 + np.arange(wl.B)) % wl.num_slots).astype(np.int32)
+    xr = workloads.take_trajectories(x, run % distinct)
+    del x
+    lr, vr, br = (torch.from_numpy(xr[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    out_r = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(run).pin_memory(), lr, vr, br,
+                                                    binding.config_from_hyper(wl.hyper))
+    torch.cuda.synchronize()
+    got_r = {k: v.cpu().numpy() for k, v in out_r.items()}
+    buf.close()
+    say("  oracle")
+    check_against_oracle(wl, xr, got_r, label="fused C4 full, consecutive slots")
+    check_against_oracle(wl, xb, got, label="fused C4 full")
+
+
 @pytest.mark.parametrize("case", [("C2", dict(T=22, A=6, B=16384, num_slots=16384), "f32"),
                                   ("C2", dict(T=24, A=18, B=16384, num_slots=16384), "bf16"),
                                   ("C2", dict(T=13, A=18, B=16384, num_slots=16384), "bf16"),

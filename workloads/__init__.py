@@ -65,6 +65,8 @@ class Workload:
     worker_noise: float = 0.0
     logstd_lo: float = -1.5
     logstd_hi: float = 0.0
+    logstd_mode: str = "per_policy"   # "per_policy": each policy's log-std drawn on its own | "offsets": like the means
+    mean_mode: str = "offsets"        # "offsets": target/worker means a small offset away | "per_policy": drawn on their own
     reward_mode: str = "uniform"      # "uniform" | "sparse_sign" | "normal"
     reward_p_nonzero: float = 0.05
     done_p: float = 0.01
@@ -146,17 +148,18 @@ def make_trajectories(wl: Workload, n: int, stream: int = 0) -> Dict[str, np.nda
         target = derive(wl.target_mode, wl.target_noise, learner, None)
         worker = derive(wl.worker_mode, wl.worker_noise, learner, target)
     else:
-        # Means and log standard deviations follow the same recipe: the learner's are drawn
-        # fresh, the target's and worker's are the stated small offsets away (a target
-        # network is a lagged copy of the learner, a worker a lagged copy of either), so
-        # every policy's log-std stays in (about) the stated range.
+        # Means: the learner's are drawn fresh, the target's and the worker's lie the stated small offsets
+        # away (a target network is a lagged copy of the learner, a worker a lagged copy of either), or, with
+        # mean_mode "per_policy", are drawn on their own.  Log standard deviations: uniform in the stated
+        # range for each policy and element on its own ("per_policy"), or offsets like the means.
         l_mean = normal((T, n, A), wl.learner_std)
         l_lstd = g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
-        t_mean = derive(wl.target_mode, wl.target_noise, l_mean, None)
-        w_mean = derive(wl.worker_mode, wl.worker_noise, l_mean, t_mean)
+        own_means = wl.mean_mode == "per_policy"
+        t_mean = derive("independent" if own_means else wl.target_mode, wl.target_noise, l_mean, None)
+        w_mean = derive("independent" if own_means else wl.worker_mode, wl.worker_noise, l_mean, t_mean)
 
         def derive_lstd(mode, noise, target_part):
-            if mode == "independent":
+            if mode == "independent" or wl.logstd_mode == "per_policy":
                 return g.uniform(wl.logstd_lo, wl.logstd_hi, (T, n, A)).astype(f32)
             base = l_lstd if mode == "learner_plus" else target_part
             return (base + normal(base.shape, noise)).astype(f32)
