@@ -43,7 +43,8 @@ typedef enum {
     IMPACT_ERR_BUFFER_FULL = -2,     /* insert: fewer empty slots than trajectories offered */
     IMPACT_ERR_NOT_ENOUGH_LIVE = -3, /* sample: fewer live slots than trajectories asked for */
     IMPACT_ERR_HIP = -4,             /* a HIP runtime call or a kernel launch failed */
-    IMPACT_ERR_UNSUPPORTED = -5      /* a valid request the library has no kernel for */
+    IMPACT_ERR_UNSUPPORTED = -5,     /* a valid request the library has no kernel for */
+    IMPACT_ERR_TOO_LARGE = -6        /* impact_loss_fwd_bwd_static: the batch needs more workspace than the library holds */
 } impact_status_t;
 
 typedef enum { IMPACT_CATEGORICAL = 0, IMPACT_DIAG_GAUSSIAN = 1 } impact_dist_t;
@@ -283,6 +284,26 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
                                                 const float *bootstrap, const impact_loss_config_t *cfg,
                                                 const impact_loss_out_t *out, void *workspace,
                                                 size_t workspace_bytes, impact_stream_t stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): impact_loss_fwd_bwd with
+ * the workspace taken from a device array of IMPACT_STATIC_WORKSPACE_BYTES that is
+ * part of the library's code object (each GPU the library runs on holds its copy
+ * until the process ends).  Same arguments, results and errors as
+ * impact_loss_fwd_bwd, without workspace and workspace_bytes.  The call allocates
+ * and frees nothing; it enqueues kernel launches only.
+ *   Limit: impact_loss_workspace_bytes(dist, T, B, A) <= IMPACT_STATIC_WORKSPACE_BYTES
+ *   (2 MiB: batches of up to 524288 trajectories, at 32 bytes per tile of 8; a batch
+ *   of at most 1024 trajectories, processed in time segments, needs up to 1.25 MiB); beyond it
+ *   the call returns IMPACT_ERR_TOO_LARGE and enqueues nothing.
+ *   Every call on a GPU uses that GPU's one array, whatever the stream: calls that
+ *   overlap on one device race on it.  Issue them on one stream, or order them with
+ *   events.  Nothing in the array has to be cleared between calls. */
+#define IMPACT_STATIC_WORKSPACE_BYTES (2u << 20)
+impact_status_t impact_loss_fwd_bwd_static(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
+                                           const void *learner_dist, const float *values, const float *bootstrap,
+                                           const impact_batch_t *batch, const impact_loss_config_t *cfg,
+                                           const impact_loss_out_t *out, impact_stream_t stream);
 
 #ifdef __cplusplus
 }

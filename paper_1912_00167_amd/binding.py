@@ -24,6 +24,8 @@ IMPACT_ERR_BUFFER_FULL = -2
 IMPACT_ERR_NOT_ENOUGH_LIVE = -3
 IMPACT_ERR_HIP = -4
 IMPACT_ERR_UNSUPPORTED = -5
+IMPACT_ERR_TOO_LARGE = -6
+IMPACT_STATIC_WORKSPACE_BYTES = 2 << 20
 
 IMPACT_CATEGORICAL = 0
 IMPACT_DIAG_GAUSSIAN = 1
@@ -47,7 +49,7 @@ EXPORTS = [
     "impact_buffer_state_bytes", "impact_buffer_export_state", "impact_buffer_import_state",
     "impact_buffer_reserve", "impact_buffer_insert", "impact_buffer_put_target", "impact_buffer_sample",
     "impact_buffer_gather", "impact_loss_workspace_bytes", "impact_loss_fwd_bwd",
-    "impact_loss_fwd_bwd_from_buffer",
+    "impact_loss_fwd_bwd_from_buffer", "impact_loss_fwd_bwd_static",
 ]
 
 
@@ -128,6 +130,9 @@ def load() -> ctypes.CDLL:
     L.impact_loss_fwd_bwd_from_buffer.restype = ctypes.c_int
     L.impact_loss_fwd_bwd_from_buffer.argtypes = [vp, i32, vp, vp, vp, vp, ctypes.POINTER(impact_loss_config_t),
                                                   ctypes.POINTER(impact_loss_out_t), vp, sz, vp]
+    L.impact_loss_fwd_bwd_static.restype = ctypes.c_int
+    L.impact_loss_fwd_bwd_static.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, ctypes.POINTER(impact_batch_t),
+                                             ctypes.POINTER(impact_loss_config_t), ctypes.POINTER(impact_loss_out_t), vp]
     _lib = L
     return L
 
@@ -370,6 +375,21 @@ def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, boots
     _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
                                       _ptr(bootstrap), ctypes.byref(b), ctypes.byref(cfg), ctypes.byref(o),
                                       _ptr(workspace), workspace.numel(), _stream(stream)), "impact_loss_fwd_bwd")
+    return out
+
+
+def impact_loss_fwd_bwd_static(dist, learner: torch.Tensor, values: torch.Tensor, bootstrap: torch.Tensor,
+                               batch: Dict[str, torch.Tensor], cfg: impact_loss_config_t,
+                               out: Dict[str, torch.Tensor], stream=None) -> Dict[str, torch.Tensor]:
+    """The caller brings every tensor (outputs included): this call allocates nothing, here or in the library."""
+    d = dist_code(dist)
+    T, B, W = (int(x) for x in learner.shape)
+    A = W if d == IMPACT_CATEGORICAL else W // 2
+    b, o = _batch_struct(batch), _out_struct(out)
+    cfg = _cfg_for(cfg, learner)
+    _check(load().impact_loss_fwd_bwd_static(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
+                                             _ptr(bootstrap), ctypes.byref(b), ctypes.byref(cfg), ctypes.byref(o),
+                                             _stream(stream)), "impact_loss_fwd_bwd_static")
     return out
 
 

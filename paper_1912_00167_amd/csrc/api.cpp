@@ -115,6 +115,7 @@ const char *impact_status_string(impact_status_t s)
     case IMPACT_ERR_NOT_ENOUGH_LIVE: return "not enough live slots";
     case IMPACT_ERR_HIP: return "HIP error";
     case IMPACT_ERR_UNSUPPORTED: return "unsupported";
+    case IMPACT_ERR_TOO_LARGE: return "batch too large for the library's static workspace";
     }
     return "unknown status";
 }
