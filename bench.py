@@ -31,9 +31,27 @@ import workloads  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 # HBM bytes per launch of the fused loss kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by what the
-# same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md, ..._cat18_C4_fused.md).  Tied to the
-# kernel as profiled: to be set to None whenever the kernel changes until the counters are taken again.
-MEASURED_TRAFFIC_BYTES = {"C5": 1.0340e9, "C4": 2.710e8}
+# same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md).  Each figure
+# is tied to the kernel sources it was taken on (kernel_sources_digest below): once any of them changes, the
+# benchmark reports null until the counters are taken again.
+MEASURED_TRAFFIC = {}       # workload -> (bytes per launch, digest of the kernel sources at that time)
+
+
+def kernel_sources_digest() -> str:
+    """A digest of the library's device and host sources (what the counters were measured on)."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_1912_00167_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip", ".cpp")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    entry = MEASURED_TRAFFIC.get(workload)
+    return entry[0] if entry and entry[1] == kernel_sources_digest() else None
 
 
 def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False) -> int:
@@ -76,33 +94,71 @@ def fill_ring(torch, binding, wl, buf, block: int):
     return learner, values, boot
 
 
-def cpu_baseline(wl, sample_B: int, min_wall_s: float = 1.5):
-    """Time the oracle (as it is) on a bounded sample of the workload, all host threads: whole passes
-    (sample, gather, loss with gradients) over sample_B trajectories until min_wall_s has elapsed."""
+def cpu_model_string() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, sample_B: int, min_wall_s: float = 8.0, single_B: int = 256, single_wall_s: float = 4.0):
+    """Time the oracle (as it is) on a bounded sample of the workload: whole passes (sample, gather, loss with
+    gradients) over sample_B trajectories on all host threads until min_wall_s has elapsed, then the same on
+    single_B trajectories with one thread."""
     import oracle
     from oracle.buffer import BufferOracle, bf16_bits_to_f32
 
+    def leg(n_traj, threads, wall_s):
+        x = workloads.make_trajectories(wl, n_traj, stream=77)
+        ob = BufferOracle(wl.dist, wl.T, wl.A, n_traj, max(wl.K, 1 << 20), wl.storage)
+        ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"], target=x["target"])
+        cfg = oracle.config_from_hyper(wl.hyper)
+        passes = 0
+        t0 = time.perf_counter()
+        while True:
+            slots, _ = ob.sample(n_traj)
+            g = ob.gather(slots)
+            if wl.storage == "bf16":
+                g = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in g.items()}
+            oracle.impact_loss(wl.dist, x["learner"], g["target"], g["worker"], g["actions"], g["rewards"], g["dones"],
+                               x["values"], x["bootstrap"], cfg, n_threads=threads)
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= wall_s:
+                break
+        return passes, dt
+
     threads = min(oracle.max_threads(), os.cpu_count() or 1)
-    x = workloads.make_trajectories(wl, sample_B, stream=77)
-    ob = BufferOracle(wl.dist, wl.T, wl.A, sample_B, max(wl.K, 1 << 20), wl.storage)
-    ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"], target=x["target"])
-    cfg = oracle.config_from_hyper(wl.hyper)
-    passes = 0
-    t0 = time.perf_counter()
-    while True:
-        slots, _ = ob.sample(sample_B)
-        g = ob.gather(slots)
-        if wl.storage == "bf16":
-            g = {k: (bf16_bits_to_f32(v) if v.dtype == np.uint16 else v) for k, v in g.items()}
-        oracle.impact_loss(wl.dist, x["learner"], g["target"], g["worker"], g["actions"], g["rewards"], g["dones"],
-                           x["values"], x["bootstrap"], cfg, n_threads=threads)
-        passes += 1
-        dt = time.perf_counter() - t0
-        if dt >= min_wall_s:
-            break
+    passes, dt = leg(sample_B, threads, min_wall_s)
+    p1, dt1 = leg(single_B, 1, single_wall_s)
     return dict(value=passes * wl.T * sample_B / dt, unit="trajectory-steps/s", cores=threads, kind="oracle",
                 sample=f"{passes} passes over {sample_B} of {wl.B} trajectories of {wl.name} (T={wl.T}): sample + gather + "
-                       f"loss with gradients, {dt:.2f} s wall on {threads} threads ({dt * threads:.0f} core-seconds)")
+                       f"loss with gradients, {dt:.2f} s wall on {threads} threads ({dt * threads:.0f} core-seconds); "
+                       f"single thread: {p1} passes over {single_B} trajectories in {dt1:.2f} s",
+                single_thread_value=p1 * wl.T * single_B / dt1, nproc=os.cpu_count(), cpu_model=cpu_model_string())
+
+
+def device_copy_ceiling(torch, nbytes: int = 1 << 30, repeats: int = 20):
+    """The box's device-to-device copy rate (read + written bytes per second), timed in this process: a
+    torch copy of nbytes between two resident tensors, HIP events around `repeats` back-to-back copies."""
+    a = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    a.zero_()
+    for _ in range(5):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(repeats):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / repeats
+    del a, b
+    return 2 * nbytes / (ms * 1e-3) / 1e9
 
 
 def branch_fractions(wl, n: int = 256):
@@ -258,10 +314,13 @@ def table(torch, binding, names, repeats: int = 5) -> None:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # Defaults long enough to be past the clock transient after idle: for the first ~12 ms of sustained
-    # load launches take up to 20 % longer than in the steady state that follows (kernel trace in profiles/).
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=128)
+    # After idle the chip runs its first ~12 ms of sustained load with launches up to 20 % longer than in the
+    # steady state that follows (kernel trace in profiles/).  Whatever --warmup says, the run therefore starts
+    # with an untimed settle phase of this many steps of the same fused launch (reported as config.settle_steps).
+    ap.add_argument("--settle-ms", type=float, default=40.0,
+                    help="untimed settle phase before the warm-up: at least this much device time of fused steps (default 40)")
     ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--packed-outputs", action="store_true",
@@ -318,7 +377,7 @@ def main() -> int:
     # Only every `every`-th launch is bracketed: the two records between back-to-back launches cost the
     # stream about 5 us per step (217 us per step against 211 with every fourth launch bracketed), which
     # would be charged to the throughput; the sampled launches give the kernel's average duration.
-    every = args.event_every if args.steps >= 8 * args.event_every else 1     # a short run brackets every launch
+    every = args.event_every if args.steps >= args.event_every else 1
     assert depth % every == 0
 
     def retire(j, keep):
@@ -354,6 +413,13 @@ def main() -> int:
     # 30 ms per full pass over torch's object graph: more than a hundred steps.  It stays off while steps run.
     gc.collect()
     gc.disable()
+    # settle phase: fused steps until the device has been busy for --settle-ms (clock steady state); the host
+    # runs at most `depth` steps ahead of the device (it waits for each staging buffer), so wall time is device time
+    settle_steps = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms or settle_steps < depth:
+        one_step(False)
+        settle_steps += 1
     for _ in range(args.warmup):
         one_step(False)
     for j in range(depth):
@@ -429,6 +495,36 @@ def main() -> int:
                        "algorithmic_GBps": algorithmic_bytes_per_step(wl) * T * B / (two_ms * 1e-3) / 1e9,
                        "what": "successive steps alternate between two streams and two lanes of the buffer's completion "
                                "counters, so that one launch starts while the other drains; whole-step throughput"}
+    # The headline samples in ring order, which yields runs of consecutive slots (the kernel is then given the
+    # first slot and reads no index array).  The same step on a batch whose slots lie scattered over the ring
+    # (a shuffled quarter of it; the index array in page-locked host memory, read by the kernel): kernel time only.
+    scattered = None
+    if not args.packed_outputs and not args.no_variants:
+        rng = np.random.default_rng(12)
+        n_var = min(args.steps, 128)
+        perms = []
+        for q in range(n_batches):
+            perm = torch.from_numpy((q * B + rng.permutation(B)).astype(np.int32))
+            order = (perm.long() - q * B).cuda()
+            perms.append((perm.pin_memory(), learner[q].index_select(1, order).contiguous(),
+                          values[q].index_select(1, order).contiguous(), boot[q].index_select(0, order).contiguous()))
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_var // 4)]
+        for i in range(32 + n_var):
+            sl, ln, va, bo = perms[i % n_batches]
+            k = i - 32
+            if k >= 0 and k % 4 == 0:
+                ev[k // 4][0].record(stream)
+            binding.impact_loss_fwd_bwd_from_buffer(buf, sl, ln, va, bo, cfg, out=outs[i % 2], workspace=workspace, stream=stream)
+            if k >= 0 and k % 4 == 0:
+                ev[k // 4][1].record(stream)
+        torch.cuda.synchronize()
+        sc_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        scattered = {"kernel_ms": sc_ms, "frac": algorithmic_bytes_per_step(wl) * T * B / (sc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "what": "the batch's slots scattered over a quarter of the ring (shuffled), index array in page-locked "
+                             "host memory read by the kernel; HIP events around every fourth launch"}
+        del perms
+    copy_ceiling = device_copy_ceiling(torch)
     gc.enable()
     if args.series:
         with open(args.series, "w") as f:
@@ -456,15 +552,21 @@ def main() -> int:
                                f"ring {wl.num_slots} slots K={wl.K}, fused gather+loss+grad"
                                + (", per-step scalars as packed records" if args.packed_outputs else ""),
                    "algorithmic_bytes_per_step": algorithmic_bytes_per_step(wl),
+                   "settle_steps": settle_steps,
                    "host_issue_ms_per_step": issued * 1e3 / args.steps,
                    "loss5": [float(v) for v in loss]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if args.packed_outputs else MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)"},
+                     "traffic": None if args.packed_outputs else measured_traffic(args.workload),
+                     "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)",
+                     "kernel_launches_timed": len(kernel_times),
+                     "device_copy_ceiling_GBps": copy_ceiling,
+                     "frac_of_copy_ceiling": achieved / copy_ceiling},
     }
     if two_streams is not None:
         result.setdefault("variants", {})["two_streams"] = two_streams
+    if scattered is not None:
+        result.setdefault("variants", {})["scattered_slots"] = scattered
     if variant is not None:
         result.setdefault("variants", {})["packed_step_outputs"] = {
             "kernel_ms": variant, "frac": bytes_per_call / (variant * 1e-3) / 1e9 / HBM_PEAK_GBS,
