@@ -68,6 +68,14 @@ def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False) -> int:
     return reads + writes
 
 
+def refill(binding, buf) -> None:
+    """The workers' side of the ring, as bookkeeping only (the records are in place): once fewer live slots
+    than a batch remain, free the places of what has been replayed K times (its loss has been enqueued by now)
+    and mark every empty slot live again."""
+    binding.impact_buffer_release_discarded(buf)
+    binding.impact_buffer_reserve(buf, binding.impact_buffer_num_empty(buf))
+
+
 def fill_ring(torch, binding, wl, buf, block: int):
     """Fill all num_slots slots block by block; return the learner-side tensors (learner dist, values,
     bootstrap) per batch-sized group of consecutive slots.  One batch worth of distinct synthetic
@@ -267,7 +275,7 @@ def table(torch, binding, names, repeats: int = 5) -> None:
             if k == 20:                             # after a warm-up
                 t0 = time.perf_counter()
             if binding.impact_buffer_num_live(buf) < B:
-                binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
+                refill(binding, buf)
             binding.impact_buffer_sample(buf, B, s_np, c_np)
         t_s = (time.perf_counter() - t0) * 1e6 / n_samples
         clip, trunc = branch_fractions(wl)
@@ -394,7 +402,7 @@ def main() -> int:
         j = i % depth
         retire(j, timed)
         if binding.impact_buffer_num_live(buf) < B:
-            binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))   # workers' refill: bookkeeping only, the data is in place
+            refill(binding, buf)
         binding.impact_buffer_sample(buf, B, pinned_np[j], counts_np)
         q = int(pinned_np[j][0]) // B              # ring order: batch q holds slots [qB, (q+1)B)
         host_marks.append(time.perf_counter())
@@ -472,7 +480,7 @@ def main() -> int:
 
         def lane_step(i):
             if binding.impact_buffer_num_live(buf) < B:
-                binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
+                refill(binding, buf)
             binding.impact_buffer_sample(buf, B, staging_np[i], counts_np)
             q = int(staging_np[i][0]) // B
             ln = lanes[i % 2]

@@ -21,8 +21,17 @@
  *                                 standard deviations),
  *       step scalars  [T][B],  bootstrap [B].
  *     Inside the buffer the same records are slot-major, [slot][T][...].
- *   - Arithmetic is fp32.  IMPACT_BF16 is a storage format only (bfloat16,
- *     round-to-nearest-even at insert); values are widened to fp32 on load.
+ *   - Inputs and outputs are fp32 (or bf16 where stated); the arithmetic in
+ *     between is fp64 wherever a rounding error of fp32 size would show in the
+ *     results: all of it for Gaussian policies (log-probabilities, ratios, the
+ *     scan, gradients; own table-based exp, relative error about 1e-10), and
+ *     for categorical policies the softmax normalisers, importance weights,
+ *     ratios and the scan (the softmax inside the gradient is fp32).  Results
+ *     are rounded to fp32 once, on output.  IMPACT_BF16 is a storage format only
+ *     (bfloat16, round-to-nearest-even at insert); values are widened exactly.
+ *     Ratios of categorical policies are formed as products of two exponentials:
+ *     logits are expected below 350 in magnitude (beyond that a ratio may
+ *     overflow fp64 where the true value is representable).
  *   - One buffer handle may be used from several host threads (one mutex per
  *     handle).  Device work of different calls is ordered only by the streams
  *     the caller passes.
@@ -167,11 +176,16 @@ impact_status_t impact_buffer_create(const impact_buffer_desc_t *desc, void *dev
 /* Free the handle (not the device storage).  NULL is allowed. */
 impact_status_t impact_buffer_destroy(impact_buffer_t *buf);
 
-/* Number of live slots (inserted and not yet traversed K times), or a negative status. */
+/* Number of live slots (inserted and not yet handed out K times), or a negative status. */
 int32_t impact_buffer_num_live(impact_buffer_t *buf);
+/* Number of empty slots (free for impact_buffer_insert / _reserve), or a negative status.  A slot that
+ * has been handed out for the K-th time is neither live nor empty until it is released (see
+ * impact_buffer_sample): num_live + num_empty <= num_slots. */
+int32_t impact_buffer_num_empty(impact_buffer_t *buf);
 
 /* The ring's bookkeeping (which slots are live, how often each was traversed, the
- * two cursors: Section 3.2) as a flat host record, so that a learner can be
+ * two cursors, which hold a target output, the learner step counter: Section 3.2,
+ * Algorithm 1) as a flat host record, so that a learner can be
  * stopped and resumed; the slots' contents live in the caller's device storage
  * and are the caller's to save.  state_bytes: size of the record.  export: write it
  * to host_dst (at least state_bytes).  import: replace the bookkeeping of `buf` by
@@ -184,7 +198,8 @@ impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *hos
 /* Host bookkeeping half of an insert: choose n empty slots in ring order from the
  * write cursor (never a live one, Section 3.2), mark them live with a traversal
  * count of 0 and report them in out_slots (host, n entries).  No device work:
- * the caller fills the slots itself.  All-or-nothing: BUFFER_FULL if fewer than
+ * the caller fills the slots itself (they count as lacking a target output, see
+ * impact_buffer_missing_targets).  All-or-nothing: BUFFER_FULL if fewer than
  * n slots are empty. */
 impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *out_slots);
 
@@ -210,10 +225,63 @@ impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const 
 /* "Obtain batch B of size M traversed k times from C(N,K)" (Algorithm 1), host
  * bookkeeping only: walk the read cursor over the ring, take the next B live
  * slots, report each slot and how often it had been traversed before this call,
- * count the traversal, and empty a slot once its count reaches K ("discard",
- * Algorithm 1; Section 3.2).  out_slots/out_counts: host, B entries each.
- * All-or-nothing: NOT_ENOUGH_LIVE if fewer than B slots are live.  B = 0 is a no-op. */
+ * count the traversal, and take a slot out of circulation once its count
+ * reaches K.  out_slots/out_counts: host, B entries each.
+ * All-or-nothing: NOT_ENOUGH_LIVE if fewer than B slots are live.  B = 0 is a no-op.
+ *
+ * Discard follows the gradient step (Algorithm 1: "compute ... gradients", then "if k = K,
+ * discard batch B from C(N,K)"): a slot handed out for the K-th time is not sampled again,
+ * but its place stays occupied, so that no insert can overwrite records which the loss
+ * of this batch, not yet enqueued, is going to read.  The places become empty
+ *   - when impact_buffer_release_discarded is called (after the batch's loss has been
+ *     enqueued), or
+ *   - at the next successful impact_buffer_sample on the handle, which begins the next
+ *     iteration of the learner loop.
+ * Device-side ordering is the caller's, through streams: an insert or put_target that
+ * reuses a released slot must be enqueued on the stream of the loss that read the slot, or
+ * be ordered after it with an event. */
 impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *out_slots, int32_t *out_counts);
+
+/* "If k = K, discard batch B from C(N,K)" (Algorithm 1): the places of all slots that
+ * have been handed out K times become empty.  Call it once the loss of the batch that
+ * held their K-th traversal has been enqueued.  Host bookkeeping only. */
+impact_status_t impact_buffer_release_discarded(impact_buffer_t *buf);
+
+/* "If k = 0, evaluate B on target, append target output to B" (Algorithm 1), the
+ * bookkeeping half: of the B slots of a sampled batch (host array `slots`, each in
+ * [0, num_slots)), list the positions i whose slot holds no target output yet (it was
+ * inserted without target_dist, or only reserved, and impact_buffer_put_target has not
+ * named it since).  out_positions: host, room for B entries, receives the positions in
+ * increasing order; *out_n their number.  The caller evaluates the target network on
+ * those trajectories and hands the result to impact_buffer_put_target.  Under the
+ * protocol of Algorithm 1 these are exactly the positions with out_counts[i] = 0. */
+impact_status_t impact_buffer_missing_targets(impact_buffer_t *buf, int32_t B, const int32_t *slots,
+                                              int32_t *out_positions, int32_t *out_n);
+
+/* The bookkeeping half of impact_buffer_put_target alone, for callers that fill reserved
+ * slots themselves (impact_buffer_reserve): record that the n slots listed (host array)
+ * hold their target output.  No device work. */
+impact_status_t impact_buffer_mark_target(impact_buffer_t *buf, int32_t n, const int32_t *slots);
+
+/* "If t = 0 (mod t_target), update target network" (Algorithm 1): count one learner
+ * step on the handle's step counter t (which starts at 0 and is part of the exported
+ * state) and report the new t (out_t, may be NULL) and whether t is a multiple of
+ * t_target (out_sync_due, may be NULL).  t_target >= 1, else INVALID_ARG. */
+impact_status_t impact_buffer_learner_step(impact_buffer_t *buf, int64_t t_target, int64_t *out_t,
+                                           int32_t *out_sync_due);
+
+/* The target-update period the paper benchmarks with (Section 4.1.1): n = N K, where N is
+ * the number of batches the buffer holds, here floor(num_slots / B), and K the replay
+ * limit; with it a full ring is PPO's schedule of K epochs over N minibatches between
+ * target updates (Section 3.2).  0 on invalid arguments. */
+int64_t impact_target_period(int32_t num_slots, int32_t B, int32_t K);
+
+/* Forget which lanes' completion counters (see impact_loss_fwd_bwd_from_buffer) have
+ * been cleared: the next call of every lane clears its counter again, in stream order.
+ * For recovery after a fused loss launch did not run to completion (a device error, a
+ * stream destroyed with work pending): the kernel then may have left its counter
+ * non-zero, and later launches on that lane would never write loss5. */
+impact_status_t impact_buffer_reset_lanes(impact_buffer_t *buf);
 
 /* Copy the records of B slots into time-major tensors [T][B][...] of the
  * buffer's storage dtype (a byte copy, no conversion).  dev_slots: device int32

@@ -7,6 +7,15 @@ text that is silent on them: ring order from a read cursor, inserts never
 overwrite a live item, insert and sample are all-or-nothing.  (The bookkeeping
 itself is pinned by a brute-force simulation in the tests.)
 
+Algorithm 1's learner loop orders a step as: obtain the batch and its count k;
+if k = 0 evaluate it on the target and append the result; compute the gradients;
+"if k = K, discard"; "if t = 0 (mod t_target), update the target network".  So a
+batch handed out for the K-th time is still needed by the gradient computation
+that follows: its place becomes free for a new worker batch only after that,
+here when `release` is called or at the next `sample` (which begins the next
+iteration of the loop).  The same loop's bookkeeping of "does this batch still
+need the target's evaluation" and of the step counter t live here as well.
+
 Plain Python, one loop per operation; the stored records are numpy arrays in
 slot-major order ``[N, T, ...]``.
 """
@@ -18,6 +27,8 @@ import numpy as np
 
 from . import quantize_bf16
 
+EMPTY, DISCARDED = -1, -2
+
 
 class BufferFull(Exception):
     pass
@@ -27,6 +38,12 @@ class NotEnoughLive(Exception):
     pass
 
 
+def target_period(num_slots: int, B: int, K: int) -> int:
+    """Section 4.1.1: the target is updated every n = N K learner steps, N the number of batches the
+    buffer holds (here num_slots trajectories in batches of B) and K the replay limit."""
+    return (num_slots // B) * K
+
+
 class RingOracle:
     """Integer bookkeeping only."""
 
@@ -34,32 +51,49 @@ class RingOracle:
         if num_slots < 1 or K < 1:
             raise ValueError("num_slots and K must be positive")
         self.N, self.K = num_slots, K
-        self.count = [-1] * num_slots   # -1 empty, else times traversed so far (0..K-1)
+        # EMPTY, DISCARDED (traversed K times, its last gradient step possibly still to come), else times traversed so far (0..K-1)
+        self.count = [EMPTY] * num_slots
+        self.has_target = [False] * num_slots   # the target network's output for this item is stored
         self.w = 0                      # write cursor
         self.r = 0                      # read cursor
+        self.t = 0                      # learner steps counted
 
     def num_live(self) -> int:
         return sum(1 for c in self.count if c >= 0)
 
-    def insert(self, n: int) -> List[int]:
+    def num_empty(self) -> int:
+        return sum(1 for c in self.count if c == EMPTY)
+
+    def insert(self, n: int, with_target: bool = True) -> List[int]:
         if n < 0:
             raise ValueError("n < 0")
-        if self.N - self.num_live() < n:
+        if self.num_empty() < n:
             raise BufferFull()
         slots = []
         for _ in range(n):
-            while self.count[self.w] >= 0:
+            while self.count[self.w] != EMPTY:
                 self.w = (self.w + 1) % self.N
             self.count[self.w] = 0
+            self.has_target[self.w] = with_target
             slots.append(self.w)
             self.w = (self.w + 1) % self.N
         return slots
+
+    def release(self) -> None:
+        """Algorithm 1, "if k = K, discard": the places of the items whose K-th traversal was handed out
+        become free for new worker batches."""
+        for s in range(self.N):
+            if self.count[s] == DISCARDED:
+                self.count[s] = EMPTY
 
     def sample(self, B: int) -> Tuple[List[int], List[int]]:
         if B < 0:
             raise ValueError("B < 0")
         if self.num_live() < B:
             raise NotEnoughLive()
+        if B == 0:
+            return [], []                         # an empty request is no iteration of the loop: nothing changes
+        self.release()                            # the previous iteration's gradient step is behind us
         slots, counts = [], []
         for _ in range(B):
             while self.count[self.r] < 0:
@@ -69,9 +103,25 @@ class RingOracle:
             counts.append(self.count[s])          # traversals before this one
             self.count[s] += 1
             if self.count[s] == self.K:
-                self.count[s] = -1                # traversed K times: discarded
+                self.count[s] = DISCARDED         # traversed K times: not handed out again
             self.r = (self.r + 1) % self.N
         return slots, counts
+
+    def mark_target(self, slots) -> None:
+        for s in slots:
+            self.has_target[s] = True
+
+    def missing_targets(self, slots) -> List[int]:
+        """Algorithm 1, "if k = 0, evaluate B on target, append target output to B": the positions in
+        the batch whose item has no target output stored yet."""
+        return [i for i, s in enumerate(slots) if not self.has_target[s]]
+
+    def learner_step(self, t_target: int) -> bool:
+        """Count one learner step; Algorithm 1, "if t = 0 (mod t_target), update target network"."""
+        if t_target < 1:
+            raise ValueError("t_target < 1")
+        self.t += 1
+        return self.t % t_target == 0
 
 
 class BufferOracle(RingOracle):
@@ -96,7 +146,7 @@ class BufferOracle(RingOracle):
     def insert_records(self, worker, actions, rewards, dones, target=None) -> List[int]:
         """Time-major fp32 inputs [T, n, ...]; returns the slots used."""
         n = worker.shape[1]
-        slots = self.insert(n)
+        slots = self.insert(n, with_target=target is not None)
         for i, s in enumerate(slots):
             self.worker[s] = self._store(worker[:, i])
             if self.dist == "categorical":
@@ -112,6 +162,7 @@ class BufferOracle(RingOracle):
     def put_target(self, slots, target) -> None:
         for i, s in enumerate(slots):
             self.target[s] = self._store(target[:, i])
+        self.mark_target(slots)
 
     def gather(self, slots) -> Dict[str, np.ndarray]:
         """Time-major copies, in the storage dtype (bf16 as uint16 bit patterns)."""

@@ -46,6 +46,8 @@ IMPACT_BUFFER_NO_TARGET_DIST = 2
 EXPORTS = [
     "impact_version", "impact_status_string",
     "impact_buffer_storage_bytes", "impact_buffer_create", "impact_buffer_destroy", "impact_buffer_num_live",
+    "impact_buffer_num_empty", "impact_buffer_release_discarded", "impact_buffer_missing_targets",
+    "impact_buffer_mark_target", "impact_buffer_learner_step", "impact_target_period", "impact_buffer_reset_lanes",
     "impact_buffer_state_bytes", "impact_buffer_export_state", "impact_buffer_import_state",
     "impact_buffer_reserve", "impact_buffer_insert", "impact_buffer_put_target", "impact_buffer_sample",
     "impact_buffer_gather", "impact_loss_workspace_bytes", "impact_loss_fwd_bwd",
@@ -105,6 +107,20 @@ def load() -> ctypes.CDLL:
     L.impact_buffer_destroy.argtypes = [vp]
     L.impact_buffer_num_live.restype = i32
     L.impact_buffer_num_live.argtypes = [vp]
+    L.impact_buffer_num_empty.restype = i32
+    L.impact_buffer_num_empty.argtypes = [vp]
+    L.impact_buffer_release_discarded.restype = ctypes.c_int
+    L.impact_buffer_release_discarded.argtypes = [vp]
+    L.impact_buffer_missing_targets.restype = ctypes.c_int
+    L.impact_buffer_missing_targets.argtypes = [vp, i32, vp, vp, vp]
+    L.impact_buffer_mark_target.restype = ctypes.c_int
+    L.impact_buffer_mark_target.argtypes = [vp, i32, vp]
+    L.impact_buffer_learner_step.restype = ctypes.c_int
+    L.impact_buffer_learner_step.argtypes = [vp, ctypes.c_int64, vp, vp]
+    L.impact_target_period.restype = ctypes.c_int64
+    L.impact_target_period.argtypes = [i32, i32, i32]
+    L.impact_buffer_reset_lanes.restype = ctypes.c_int
+    L.impact_buffer_reset_lanes.argtypes = [vp]
     L.impact_buffer_state_bytes.restype = sz
     L.impact_buffer_state_bytes.argtypes = [vp]
     L.impact_buffer_export_state.restype = ctypes.c_int
@@ -249,6 +265,47 @@ class Buffer:
 
 def impact_buffer_num_live(buf: Buffer) -> int:
     return int(load().impact_buffer_num_live(buf.handle))
+
+
+def impact_buffer_num_empty(buf: Buffer) -> int:
+    return int(load().impact_buffer_num_empty(buf.handle))
+
+
+def impact_buffer_release_discarded(buf: Buffer) -> None:
+    _check(load().impact_buffer_release_discarded(buf.handle), "impact_buffer_release_discarded")
+
+
+def impact_buffer_missing_targets(buf: Buffer, slots: np.ndarray) -> np.ndarray:
+    """Positions in the batch whose slot holds no target output yet."""
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    pos = np.empty(max(slots.size, 1), dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(load().impact_buffer_missing_targets(buf.handle, slots.size, slots.ctypes.data_as(ctypes.c_void_p),
+                                                pos.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n)),
+           "impact_buffer_missing_targets")
+    return pos[: n.value].copy()
+
+
+def impact_buffer_mark_target(buf: Buffer, slots: np.ndarray) -> None:
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    _check(load().impact_buffer_mark_target(buf.handle, slots.size, slots.ctypes.data_as(ctypes.c_void_p)),
+           "impact_buffer_mark_target")
+
+
+def impact_buffer_learner_step(buf: Buffer, t_target: int) -> Tuple[int, bool]:
+    """Counts one learner step; returns (t, target update due)."""
+    t, due = ctypes.c_int64(0), ctypes.c_int32(0)
+    _check(load().impact_buffer_learner_step(buf.handle, int(t_target), ctypes.byref(t), ctypes.byref(due)),
+           "impact_buffer_learner_step")
+    return int(t.value), bool(due.value)
+
+
+def impact_target_period(num_slots: int, B: int, K: int) -> int:
+    return int(load().impact_target_period(num_slots, B, K))
+
+
+def impact_buffer_reset_lanes(buf: Buffer) -> None:
+    _check(load().impact_buffer_reset_lanes(buf.handle), "impact_buffer_reset_lanes")
 
 
 def impact_buffer_export_state(buf: Buffer) -> np.ndarray:

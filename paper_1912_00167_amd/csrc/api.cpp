@@ -77,28 +77,45 @@ struct impact_buffer {
     impact_buffer_desc_t desc;
     Planes planes;
     char *storage;
-    std::vector<int32_t> count;   // -1 empty, else traversals so far (0 .. K-1)
-    int32_t w, r, live;
+    // kEmpty; kDiscarded (handed out for the K-th time: not handed out again, its place not yet free, because
+    // the gradient step that reads it may still be to come); else traversals so far (0 .. K-1)
+    std::vector<int32_t> count;
+    std::vector<uint8_t> has_target;   // the target network's output for the slot's trajectory is stored
+    std::vector<int32_t> discarded;    // the slots that are kDiscarded (so that freeing them need not walk the ring)
+    int32_t w, r, live, empty;
+    int64_t t = 0;                // learner steps counted (impact_buffer_learner_step)
     uint32_t lanes_zeroed = 0;    // bit n: the completion counter of lane n in the storage has been cleared
     std::mutex mu;
+
+    static constexpr int32_t kEmpty = -1, kDiscarded = -2;
 
     int W() const { return desc.dist == IMPACT_CATEGORICAL ? desc.A : 2 * desc.A; }
     int es() const { return desc.storage == IMPACT_F32 ? 4 : 2; }
 
     // Ring order from the write cursor over empty slots.  Caller has checked there is room.
-    void reserve(int32_t n, int32_t *out)
+    void reserve(int32_t n, int32_t *out, bool with_target)
     {
         const int32_t N = desc.num_slots;
         int32_t *const cnt = count.data();
         int32_t at = w;
         for (int32_t i = 0; i < n; ++i) {
-            while (cnt[at] >= 0) at = (at + 1 == N) ? 0 : at + 1;
+            while (cnt[at] != kEmpty) at = (at + 1 == N) ? 0 : at + 1;
             cnt[at] = 0;
+            has_target[at] = with_target ? 1 : 0;
             out[i] = at;
             at = (at + 1 == N) ? 0 : at + 1;
         }
         w = at;
         live += n;
+        empty -= n;
+    }
+
+    // "If k = K, discard batch B" (Algorithm 1): the places of the discarded trajectories become free.
+    void release()
+    {
+        for (int32_t s : discarded) count[s] = kEmpty;
+        empty += (int32_t)discarded.size();
+        discarded.clear();
     }
 };
 
@@ -141,12 +158,15 @@ impact_status_t impact_buffer_create(const impact_buffer_desc_t *desc, void *dev
     b->planes = p;
     b->storage = static_cast<char *>(dev_storage);
     try {
-        b->count.assign((size_t)desc->num_slots, -1);
+        b->count.assign((size_t)desc->num_slots, impact_buffer::kEmpty);
+        b->has_target.assign((size_t)desc->num_slots, 0);
+        b->discarded.reserve((size_t)desc->num_slots);
     } catch (...) {
         delete b;
         return IMPACT_ERR_INVALID_ARG;
     }
     b->w = b->r = b->live = 0;
+    b->empty = desc->num_slots;
     *out = b;
     return IMPACT_OK;
 }
@@ -164,19 +184,85 @@ int32_t impact_buffer_num_live(impact_buffer_t *buf)
     return buf->live;
 }
 
+int32_t impact_buffer_num_empty(impact_buffer_t *buf)
+{
+    if (!buf) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    return buf->empty;
+}
+
+impact_status_t impact_buffer_release_discarded(impact_buffer_t *buf)
+{
+    if (!buf) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    buf->release();
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_missing_targets(impact_buffer_t *buf, int32_t B, const int32_t *slots,
+                                              int32_t *out_positions, int32_t *out_n)
+{
+    if (!buf || B < 0 || !out_n) return IMPACT_ERR_INVALID_ARG;
+    if (B > 0 && (!slots || !out_positions)) return IMPACT_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < B; ++i)
+        if (slots[i] < 0 || slots[i] >= buf->desc.num_slots) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    int32_t n = 0;
+    for (int32_t i = 0; i < B; ++i)
+        if (!buf->has_target[slots[i]]) out_positions[n++] = i;
+    *out_n = n;
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_mark_target(impact_buffer_t *buf, int32_t n, const int32_t *slots)
+{
+    if (!buf || n < 0 || (n > 0 && !slots)) return IMPACT_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (slots[i] < 0 || slots[i] >= buf->desc.num_slots) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    for (int32_t i = 0; i < n; ++i) buf->has_target[slots[i]] = 1;
+    return IMPACT_OK;
+}
+
+impact_status_t impact_buffer_learner_step(impact_buffer_t *buf, int64_t t_target, int64_t *out_t, int32_t *out_sync_due)
+{
+    if (!buf || t_target < 1) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    buf->t += 1;
+    if (out_t) *out_t = buf->t;
+    if (out_sync_due) *out_sync_due = (buf->t % t_target == 0) ? 1 : 0;
+    return IMPACT_OK;
+}
+
+int64_t impact_target_period(int32_t num_slots, int32_t B, int32_t K)
+{
+    if (num_slots < 1 || B < 1 || K < 1) return 0;
+    return (int64_t)(num_slots / B) * (int64_t)K;
+}
+
+impact_status_t impact_buffer_reset_lanes(impact_buffer_t *buf)
+{
+    if (!buf) return IMPACT_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(buf->mu);
+    buf->lanes_zeroed = 0;
+    return IMPACT_OK;
+}
+
 namespace {
 struct RingStateHeader {
     uint32_t magic, version;
     int32_t dist, T, A, num_slots, K, storage;
     int32_t w, r, live;
     uint32_t flags;
+    int64_t t;
 };
-constexpr uint32_t kStateMagic = 0x504d4952u, kStateVersion = 1;   // "RIMP"
+constexpr uint32_t kStateMagic = 0x504d4952u, kStateVersion = 2;   // "RIMP"
 }  // namespace
 
+// the record: header, one int32 per slot (count), one byte per slot (target stored)
 size_t impact_buffer_state_bytes(impact_buffer_t *buf)
 {
-    return buf ? sizeof(RingStateHeader) + (size_t)buf->desc.num_slots * sizeof(int32_t) : 0;
+    return buf ? sizeof(RingStateHeader) + (size_t)buf->desc.num_slots * (sizeof(int32_t) + 1) : 0;
 }
 
 impact_status_t impact_buffer_export_state(impact_buffer_t *buf, void *host_dst, size_t bytes)
@@ -185,9 +271,11 @@ impact_status_t impact_buffer_export_state(impact_buffer_t *buf, void *host_dst,
     std::lock_guard<std::mutex> lock(buf->mu);
     const impact_buffer_desc_t &d = buf->desc;
     const RingStateHeader h{kStateMagic, kStateVersion, d.dist, d.T, d.A, d.num_slots, d.K, d.storage,
-                            buf->w, buf->r, buf->live, d.flags};
-    std::memcpy(host_dst, &h, sizeof h);
-    std::memcpy(static_cast<char *>(host_dst) + sizeof h, buf->count.data(), buf->count.size() * sizeof(int32_t));
+                            buf->w, buf->r, buf->live, d.flags, buf->t};
+    char *dst = static_cast<char *>(host_dst);
+    std::memcpy(dst, &h, sizeof h);
+    std::memcpy(dst + sizeof h, buf->count.data(), buf->count.size() * sizeof(int32_t));
+    std::memcpy(dst + sizeof h + buf->count.size() * sizeof(int32_t), buf->has_target.data(), buf->has_target.size());
     return IMPACT_OK;
 }
 
@@ -196,22 +284,32 @@ impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *hos
     if (!buf || !host_src || bytes < impact_buffer_state_bytes(buf)) return IMPACT_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lock(buf->mu);
     const impact_buffer_desc_t &d = buf->desc;
+    const char *src = static_cast<const char *>(host_src);
     RingStateHeader h;
-    std::memcpy(&h, host_src, sizeof h);
+    std::memcpy(&h, src, sizeof h);
     if (h.magic != kStateMagic || h.version != kStateVersion || h.dist != d.dist || h.T != d.T || h.A != d.A ||
         h.num_slots != d.num_slots || h.K != d.K || h.storage != d.storage || h.flags != d.flags)
         return IMPACT_ERR_INVALID_ARG;
-    if (h.w < 0 || h.w >= d.num_slots || h.r < 0 || h.r >= d.num_slots) return IMPACT_ERR_INVALID_ARG;
+    if (h.w < 0 || h.w >= d.num_slots || h.r < 0 || h.r >= d.num_slots || h.t < 0) return IMPACT_ERR_INVALID_ARG;
     std::vector<int32_t> count(d.num_slots);
-    std::memcpy(count.data(), static_cast<const char *>(host_src) + sizeof h, count.size() * sizeof(int32_t));
-    int32_t live = 0;
+    std::vector<uint8_t> has_target(d.num_slots);
+    std::memcpy(count.data(), src + sizeof h, count.size() * sizeof(int32_t));
+    std::memcpy(has_target.data(), src + sizeof h + count.size() * sizeof(int32_t), has_target.size());
+    int32_t live = 0, empty = 0;
     for (int32_t c : count) {
-        if (c < -1 || c >= d.K) return IMPACT_ERR_INVALID_ARG;
+        if (c < impact_buffer::kDiscarded || c >= d.K) return IMPACT_ERR_INVALID_ARG;
         live += c >= 0;
+        empty += c == impact_buffer::kEmpty;
     }
+    for (uint8_t f : has_target)
+        if (f > 1) return IMPACT_ERR_INVALID_ARG;
     if (live != h.live) return IMPACT_ERR_INVALID_ARG;
     buf->count.swap(count);
-    buf->w = h.w; buf->r = h.r; buf->live = live;
+    buf->has_target.swap(has_target);
+    buf->discarded.clear();
+    for (int32_t i = 0; i < d.num_slots; ++i)
+        if (buf->count[i] == impact_buffer::kDiscarded) buf->discarded.push_back(i);
+    buf->w = h.w; buf->r = h.r; buf->live = live; buf->empty = empty; buf->t = h.t;
     return IMPACT_OK;
 }
 
@@ -219,8 +317,8 @@ impact_status_t impact_buffer_reserve(impact_buffer_t *buf, int32_t n, int32_t *
 {
     if (!buf || n < 0 || (n > 0 && !out_slots)) return IMPACT_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> g(buf->mu);
-    if (buf->desc.num_slots - buf->live < n) return IMPACT_ERR_BUFFER_FULL;
-    buf->reserve(n, out_slots);
+    if (buf->empty < n) return IMPACT_ERR_BUFFER_FULL;
+    buf->reserve(n, out_slots, false);
     return IMPACT_OK;
 }
 
@@ -264,9 +362,9 @@ impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impa
     if (!src || !out_slots || !src->worker_dist || !src->actions || !src->rewards || !src->dones)
         return IMPACT_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> g(buf->mu);
-    if (buf->desc.num_slots - buf->live < n) return IMPACT_ERR_BUFFER_FULL;
+    if (buf->empty < n) return IMPACT_ERR_BUFFER_FULL;
     const int32_t w0 = buf->w;
-    buf->reserve(n, out_slots);
+    buf->reserve(n, out_slots, src->target_dist != nullptr);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const impact_buffer_desc_t &d = buf->desc;
@@ -292,8 +390,9 @@ impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impa
     scatter_field(PLANE_U8, src->dones, base + pl.dones, pl.stride_done, d.T, n, 1, out_slots, s);
     if (hipGetLastError() != hipSuccess) {
         // undo the bookkeeping: the slots just reserved become empty again
-        for (int32_t i = 0; i < n; ++i) buf->count[out_slots[i]] = -1;
+        for (int32_t i = 0; i < n; ++i) buf->count[out_slots[i]] = impact_buffer::kEmpty;
         buf->live -= n;
+        buf->empty += n;
         buf->w = w0;
         return IMPACT_ERR_HIP;
     }
@@ -316,7 +415,9 @@ impact_status_t impact_buffer_put_target(impact_buffer_t *buf, int32_t n, const 
         scatter_field(fk, target_dist, buf->storage + buf->planes.target, buf->planes.stride_dist / (size_t)buf->es(),
                       d.T, n, buf->W(), slots, static_cast<hipStream_t>(stream));
     if (buf->planes.has_logp) cache_logp_field(buf, 1, target_dist, n, slots, static_cast<hipStream_t>(stream));
-    return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return IMPACT_ERR_HIP;
+    for (int32_t i = 0; i < n; ++i) buf->has_target[slots[i]] = 1;
+    return IMPACT_OK;
 }
 
 impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *out_slots, int32_t *out_counts)
@@ -326,6 +427,9 @@ impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *o
     if (!out_slots || !out_counts) return IMPACT_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> g(buf->mu);
     if (buf->live < B) return IMPACT_ERR_NOT_ENOUGH_LIVE;
+    // a new iteration of the learner loop begins: the gradient step of the previous one has been issued, so the
+    // places of the trajectories it discarded are free from here on (Algorithm 1: discard follows the gradients)
+    buf->release();
     const int32_t N = buf->desc.num_slots, K = buf->desc.K;
     // (locals: the stores through the output pointers could alias the handle's fields)
     int32_t *const cnt = buf->count.data();
@@ -336,7 +440,8 @@ impact_status_t impact_buffer_sample(impact_buffer_t *buf, int32_t B, int32_t *o
         out_slots[i] = r;
         out_counts[i] = k;
         if (++k == K) {
-            k = -1;
+            k = impact_buffer::kDiscarded;
+            buf->discarded.push_back(r);     // (capacity reserved at creation: no allocation here)
             --live;
         }
         cnt[r] = k;
@@ -400,7 +505,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
                                 const int32_t *dev_slots, int slot_first, const void *learner,
                                 const float *values, const float *bootstrap, const impact_batch_t &batch,
                                 const impact_loss_config_t *cfg, const impact_loss_out_t *out, void *workspace,
-                                size_t workspace_bytes, unsigned *done_count, hipStream_t s)
+                                size_t workspace_bytes, unsigned *done_count, hipStream_t s, bool check_only = false)
 {
     const bool slot_major = planes != nullptr;     // the batch fields are the buffer's planes, read in place
     if (dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) return IMPACT_ERR_INVALID_ARG;
@@ -423,6 +528,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
         if (p && !aligned16(p)) return IMPACT_ERR_INVALID_ARG;
     if ((out->vs && !aligned16(out->vs)) || (out->adv && !aligned16(out->adv))) return IMPACT_ERR_INVALID_ARG;
     if ((double)T * B * (2.0 * A) > 1.0e12) return IMPACT_ERR_INVALID_ARG;
+    if (check_only) return IMPACT_OK;              // every argument check is above this line, every HIP call below
 
     LossArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -555,11 +661,16 @@ impact_status_t impact_loss_fwd_bwd_from_buffer(impact_buffer_t *buf, int32_t B,
     batch.actions = base + buf->planes.actions;
     batch.rewards = base + buf->planes.rewards;
     batch.dones = reinterpret_cast<const uint8_t *>(base + buf->planes.dones);
+    // All argument checks first: on an invalid call nothing is enqueued and the handle is left as it was.
+    if (!cfg) return IMPACT_ERR_INVALID_ARG;
+    const impact_status_t checked = run_loss(d.dist, d.storage, &buf->planes, d.T, B, d.A, d.num_slots, dev_slots, slot_first,
+                                             learner_dist, values, bootstrap, batch, cfg, out, workspace, workspace_bytes,
+                                             nullptr, static_cast<hipStream_t>(stream), true);
+    if (checked != IMPACT_OK) return checked;
     // The storage holds a completion counter with which the kernel's last workgroup finishes the loss
     // terms itself (no second launch).  The kernel leaves it at zero; before the first use it is cleared
     // here, by a kernel in stream order (a fill that a caller's graph capture records like any other launch).
     // One counter per lane, 16 bytes apart: calls of different lanes may be on the device together.
-    if (!cfg) return IMPACT_ERR_INVALID_ARG;
     const uint32_t lane = (cfg->flags >> 8) & (IMPACT_LANES - 1);
     static_assert(IMPACT_LANES * 16 <= kPlaneAlign, "the counters fit the block reserved for them");
     unsigned *done_count = reinterpret_cast<unsigned *>(buf->storage + buf->planes.sync + lane * 16);

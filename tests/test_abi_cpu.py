@@ -141,36 +141,69 @@ def test_loss_argument_checks_happen_before_any_device_work(lib):
         assert call(cfg=B.make_config(**kw)) == E, kw
 
 
+def _vp(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _same_target_bookkeeping(lib, h, ring, slots):
+    """impact_buffer_missing_targets against the oracle, for the batch `slots`."""
+    s = np.ascontiguousarray(slots, np.int32)
+    pos = np.full(max(len(s), 1), -7, np.int32)
+    n = ctypes.c_int32(-1)
+    assert lib.impact_buffer_missing_targets(h, len(s), _vp(s), _vp(pos), ctypes.byref(n)) == B.IMPACT_OK
+    want = ring.missing_targets(list(slots))
+    assert n.value == len(want) and pos[: n.value].tolist() == want
+    assert np.all(pos[n.value:] == -7)
+    return want
+
+
 def _lib_state_walk(lib, N, K, seed, steps=300):
     rng = np.random.default_rng(seed)
     rc, h, _ = _create(lib, N=N, K=K)
     assert rc == 0
     ring = RingOracle(N, K)
+    t_target = int(rng.integers(1, 7))
     for _ in range(steps):
-        if rng.random() < 0.5:
+        u = rng.random()
+        if u < 0.45:
             n = int(rng.integers(0, N + 2))
             out = np.full(max(n, 1), -7, np.int32)
-            rc = lib.impact_buffer_reserve(h, n, out.ctypes.data_as(ctypes.c_void_p))
+            rc = lib.impact_buffer_reserve(h, n, _vp(out))
             try:
-                want = ring.insert(n)
+                want = ring.insert(n, with_target=False)
                 assert rc == B.IMPACT_OK
                 assert out[:n].tolist() == want
             except BufferFull:
                 assert rc == B.IMPACT_ERR_BUFFER_FULL
                 assert np.all(out == -7)                       # untouched
-        else:
+        elif u < 0.9:
             Bn = int(rng.integers(0, N + 2))
             s = np.full(max(Bn, 1), -7, np.int32)
             c = np.full(max(Bn, 1), -7, np.int32)
-            rc = lib.impact_buffer_sample(h, Bn, s.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p))
+            rc = lib.impact_buffer_sample(h, Bn, _vp(s), _vp(c))
             try:
                 ws, wc = ring.sample(Bn)
                 assert rc == B.IMPACT_OK
                 assert s[:Bn].tolist() == ws and c[:Bn].tolist() == wc
+                # Algorithm 1: the target is evaluated on what is handed out for the first time ...
+                need = _same_target_bookkeeping(lib, h, ring, ws)
+                assert need == [i for i, k in enumerate(wc) if k == 0]
+                got_target = np.asarray([ws[i] for i in need], np.int32)
+                assert lib.impact_buffer_mark_target(h, len(got_target), _vp(got_target) if len(got_target) else None) == 0
+                ring.mark_target(got_target.tolist())
+                assert _same_target_bookkeeping(lib, h, ring, ws) == []
+                # ... one learner step is counted, and the target update falls on every t_target-th
+                t, due = ctypes.c_int64(-1), ctypes.c_int32(-1)
+                assert lib.impact_buffer_learner_step(h, t_target, ctypes.byref(t), ctypes.byref(due)) == 0
+                assert bool(due.value) == ring.learner_step(t_target) and t.value == ring.t
             except NotEnoughLive:
                 assert rc == B.IMPACT_ERR_NOT_ENOUGH_LIVE
                 assert np.all(s == -7) and np.all(c == -7)
+        else:
+            assert lib.impact_buffer_release_discarded(h) == B.IMPACT_OK
+            ring.release()
         assert lib.impact_buffer_num_live(h) == ring.num_live()
+        assert lib.impact_buffer_num_empty(h) == ring.num_empty()
     lib.impact_buffer_destroy(h)
 
 
@@ -184,20 +217,33 @@ def _walk(lib, h, ring, rng, N, steps):
     for _ in range(steps):
         n = int(rng.integers(0, N + 1))
         out = np.empty(max(n, 1), np.int32)
-        if rng.random() < 0.5:
-            rc = lib.impact_buffer_reserve(h, n, out.ctypes.data_as(ctypes.c_void_p))
+        u = rng.random()
+        if u < 0.45:
+            rc = lib.impact_buffer_reserve(h, n, _vp(out))
             try:
-                assert out[:n].tolist() == ring.insert(n) and rc == 0
+                assert out[:n].tolist() == ring.insert(n, with_target=False) and rc == 0
             except BufferFull:
                 assert rc == B.IMPACT_ERR_BUFFER_FULL
-        else:
+        elif u < 0.9:
             c = np.empty(max(n, 1), np.int32)
-            rc = lib.impact_buffer_sample(h, n, out.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p))
+            rc = lib.impact_buffer_sample(h, n, _vp(out), _vp(c))
             try:
                 ws, wc = ring.sample(n)
                 assert rc == 0 and out[:n].tolist() == ws and c[:n].tolist() == wc
+                need = _same_target_bookkeeping(lib, h, ring, ws)
+                if rng.random() < 0.5 and need:                      # some batches get their target output, some not yet
+                    got_target = np.asarray([ws[i] for i in need[::2]], np.int32)
+                    assert lib.impact_buffer_mark_target(h, len(got_target), _vp(got_target)) == 0
+                    ring.mark_target(got_target.tolist())
+                t = ctypes.c_int64(-1)
+                assert lib.impact_buffer_learner_step(h, 3, ctypes.byref(t), None) == 0
+                ring.learner_step(3)
+                assert t.value == ring.t
             except NotEnoughLive:
                 assert rc == B.IMPACT_ERR_NOT_ENOUGH_LIVE
+        else:
+            assert lib.impact_buffer_release_discarded(h) == 0
+            ring.release()
 
 
 @pytest.mark.parametrize("N,K", [(5, 2), (64, 3)])
@@ -209,7 +255,7 @@ def test_ring_state_survives_export_and_import(lib, N, K):
     ring = RingOracle(N, K)
     _walk(lib, h, ring, rng, N, 120)
     nbytes = lib.impact_buffer_state_bytes(h)
-    assert nbytes == 48 + 4 * N
+    assert nbytes == 56 + 5 * N
     state = np.zeros(nbytes, np.uint8)
     vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
     assert lib.impact_buffer_export_state(h, vp(state), nbytes - 1) == B.IMPACT_ERR_INVALID_ARG
@@ -218,13 +264,19 @@ def test_ring_state_survives_export_and_import(lib, N, K):
     rc, h2, _ = _create(lib, N=N, K=K)
     assert rc == 0 and lib.impact_buffer_num_live(h2) == 0
     # malformed records change nothing
-    for damage in ("magic", "count", "live", "cursor", "short"):
+    for damage in ("magic", "count", "count_low", "live", "cursor", "short", "flag", "time"):
         bad = state.copy()
-        words = bad.view(np.int32)
+        words = bad[: 56 + 4 * N].view(np.int32)      # header (14 words) and the per-slot counts
         if damage == "magic":
             words[0] ^= 1
         elif damage == "count":
-            words[12] = K
+            words[14] = K
+        elif damage == "count_low":
+            words[14] = -3
+        elif damage == "flag":
+            bad[56 + 4 * N] = 2
+        elif damage == "time":
+            words[13] = -1                       # high word of the step counter: negative
         elif damage == "live":
             words[10] += 1
         elif damage == "cursor":
@@ -237,9 +289,9 @@ def test_ring_state_survives_export_and_import(lib, N, K):
     assert lib.impact_buffer_import_state(h3, vp(state), nbytes) == B.IMPACT_ERR_INVALID_ARG
     lib.impact_buffer_destroy(h3)
     assert lib.impact_buffer_import_state(h2, vp(state), nbytes) == 0
-    assert lib.impact_buffer_num_live(h2) == ring.num_live()
+    assert lib.impact_buffer_num_live(h2) == ring.num_live() and lib.impact_buffer_num_empty(h2) == ring.num_empty()
     _walk(lib, h2, ring, rng, N, 120)
-    assert lib.impact_buffer_num_live(h2) == ring.num_live()
+    assert lib.impact_buffer_num_live(h2) == ring.num_live() and lib.impact_buffer_num_empty(h2) == ring.num_empty()
     lib.impact_buffer_destroy(h2)
 
 
@@ -264,4 +316,86 @@ def test_ring_at_full_workload_size_matches_oracle(lib):
     assert lib.impact_buffer_num_live(h) == 0
     assert lib.impact_buffer_sample(h, 1, s.ctypes.data_as(ctypes.c_void_p), c.ctypes.data_as(ctypes.c_void_p)) \
         == B.IMPACT_ERR_NOT_ENOUGH_LIVE
+    # the last batch's places wait for its gradient step; the three before it were freed as the next was drawn
+    assert lib.impact_buffer_num_empty(h) == N - Bn == ring.num_empty()
+    assert lib.impact_buffer_reserve(h, N, out.ctypes.data_as(ctypes.c_void_p)) == B.IMPACT_ERR_BUFFER_FULL
+    assert lib.impact_buffer_release_discarded(h) == 0
+    assert lib.impact_buffer_num_empty(h) == N
+    assert lib.impact_buffer_reserve(h, N, out.ctypes.data_as(ctypes.c_void_p)) == 0
+    lib.impact_buffer_destroy(h)
+
+
+def test_target_period_and_ppo_schedule_through_the_library(lib):
+    """Section 4.1.1's n = N K, and Section 3.2's PPO analogy on the library's own ring: K passes over the
+    same N minibatches between two target updates, the target evaluated once per minibatch."""
+    from oracle.buffer import target_period
+    for num_slots, Bn, K in ((65536, 16384, 4), (32768, 8192, 8), (64, 32, 2), (20, 4, 3), (7, 2, 5), (3, 4, 2)):
+        assert lib.impact_target_period(num_slots, Bn, K) == target_period(num_slots, Bn, K)
+    assert lib.impact_target_period(0, 4, 2) == 0 and lib.impact_target_period(8, 0, 2) == 0 and lib.impact_target_period(8, 4, 0) == 0
+    n_batches, K, Bn = 5, 3, 4
+    N = n_batches * Bn
+    period = lib.impact_target_period(N, Bn, K)
+    rc, h, _ = _create(lib, N=N, K=K)
+    assert rc == 0
+    out, s, c = (np.empty(N, np.int32) for _ in range(3))
+    for cycle in range(2):
+        assert lib.impact_buffer_reserve(h, N, _vp(out)) == 0
+        first_pass = []
+        for step in range(1, period + 1):
+            assert lib.impact_buffer_sample(h, Bn, _vp(s), _vp(c)) == 0
+            if step <= n_batches:
+                first_pass.append(s[:Bn].tolist())
+            assert s[:Bn].tolist() == first_pass[(step - 1) % n_batches]          # the same minibatches, pass after pass
+            assert c[:Bn].tolist() == [(step - 1) // n_batches] * Bn
+            due = ctypes.c_int32(-1)
+            assert lib.impact_buffer_learner_step(h, period, None, ctypes.byref(due)) == 0
+            assert bool(due.value) == (step == period)
+        assert lib.impact_buffer_num_live(h) == 0
+        assert lib.impact_buffer_release_discarded(h) == 0
+    assert lib.impact_buffer_learner_step(h, 0, None, None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_learner_step(None, 1, None, None) == B.IMPACT_ERR_INVALID_ARG
+    bad = np.array([0, N], np.int32)
+    n = ctypes.c_int32(0)
+    assert lib.impact_buffer_missing_targets(h, 2, _vp(bad), _vp(out), ctypes.byref(n)) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_missing_targets(h, 2, _vp(bad), _vp(out), None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_missing_targets(h, 0, None, None, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.impact_buffer_reset_lanes(h) == 0 and lib.impact_buffer_reset_lanes(None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_release_discarded(None) == B.IMPACT_ERR_INVALID_ARG
+    assert lib.impact_buffer_num_empty(None) == B.IMPACT_ERR_INVALID_ARG
+    lib.impact_buffer_destroy(h)
+
+
+def test_a_discarded_slot_is_not_reused_before_its_release(lib):
+    """Algorithm 1 discards a batch after its gradient step: between the sample that hands a slot out for the
+    K-th time and the release (or the next sample) no insert may take the slot."""
+    rc, h, _ = _create(lib, N=4, K=1)
+    assert rc == 0
+    out, s, c = (np.empty(4, np.int32) for _ in range(3))
+    assert lib.impact_buffer_reserve(h, 4, _vp(out)) == 0
+    assert lib.impact_buffer_sample(h, 3, _vp(s), _vp(c)) == 0 and s[:3].tolist() == [0, 1, 2]
+    assert lib.impact_buffer_num_live(h) == 1 and lib.impact_buffer_num_empty(h) == 0
+    assert lib.impact_buffer_reserve(h, 1, _vp(out)) == B.IMPACT_ERR_BUFFER_FULL      # the loss of slots 0-2 is still to come
+    assert lib.impact_buffer_release_discarded(h) == 0
+    assert lib.impact_buffer_reserve(h, 2, _vp(out)) == 0 and out[:2].tolist() == [0, 1]
+    # without an explicit release the next sample frees them
+    assert lib.impact_buffer_sample(h, 2, _vp(s), _vp(c)) == 0 and s[:2].tolist() == [3, 0]
+    assert lib.impact_buffer_num_empty(h) == 1                                        # slot 2; 3 and 0 wait
+    assert lib.impact_buffer_sample(h, 1, _vp(s), _vp(c)) == 0 and s[0] == 1
+    assert lib.impact_buffer_num_empty(h) == 3
+    lib.impact_buffer_destroy(h)
+
+
+def test_an_invalid_fused_call_leaves_the_handle_as_it_was(lib):
+    """impact_loss_fwd_bwd_from_buffer checks every argument before it touches the stream or the handle."""
+    rc, h, _ = _create(lib, N=8, K=2)
+    assert rc == 0
+    p = FAKE_DEV
+    out = B.impact_loss_out_t(p, p, None, None, p)
+    ws = lib.impact_loss_workspace_bytes(0, 4, 8, 3)
+    bad = B.make_config(gamma=float("nan"))
+    E = B.IMPACT_ERR_INVALID_ARG
+    call = lambda cfg, o=out, w=p, wb=ws, slots=p: lib.impact_loss_fwd_bwd_from_buffer(
+        h, 8, slots, p, p, p, ctypes.byref(cfg) if cfg else None, ctypes.byref(o) if o else None, w, wb, None)
+    assert call(bad) == E and call(None) == E and call(B.make_config(), o=None) == E
+    assert call(B.make_config(), w=None) == E and call(B.make_config(), wb=8) == E and call(B.make_config(), slots=None) == E
     lib.impact_buffer_destroy(h)

@@ -65,7 +65,10 @@ def test_insert_sample_gather_bit_exact(env, dist, storage):
     for step in range(12):
         Bn = int(rng.integers(1, 9))
         if binding.impact_buffer_num_live(buf) < Bn:
-            n = int(rng.integers(1, wl.num_slots - ob.num_live() + 1))
+            binding.impact_buffer_release_discarded(buf)
+            ob.release()
+            assert binding.impact_buffer_num_empty(buf) == ob.num_empty()
+            n = int(rng.integers(max(1, Bn - ob.num_live()), ob.num_empty() + 1))
             _fill(torch, binding, buf, ob, wl, n, 10 + step)      # lands in fragmented free slots
         slots, counts = binding.impact_buffer_sample(buf, Bn)
         ws, wc = ob.sample(Bn)
@@ -600,4 +603,127 @@ def test_errors_from_the_device_side_calls(env):
     slots, counts = binding.impact_buffer_sample(buf, 3)
     assert slots.tolist() == [0, 1, 2] and counts.tolist() == [0, 0, 0]
     assert binding.impact_buffer_num_live(buf) == 0          # K = 1: discarded after one traversal
+    buf.close()
+
+
+def test_learner_loop_of_algorithm_1_through_the_library(env):
+    """Algorithm 1's learner loop with the library keeping its books: workers insert batches without the
+    target's output; the learner samples, asks which trajectories still lack the target's output (those handed
+    out for the first time), appends it, computes loss and gradients, releases what was handed out for the K-th
+    time, counts the step and is told when the target update is due (every N K steps, Section 4.1.1).  Every
+    step's results against the oracle; the bookkeeping against the oracle's ring."""
+    torch, binding = env
+    wl = shape_workload(workloads.C3, T=16, B=16, num_slots=48, K=2)
+    say("case learner loop")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    ob = BufferOracle(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    period = binding.impact_target_period(wl.num_slots, wl.B, wl.K)
+    assert period == 6
+    held = {}                                        # slot -> index of its trajectory in `pool`
+    pool, n_pool, n_blocks = None, 0, 0
+    cfg = binding.config_from_hyper(wl.hyper)
+    syncs = []
+    for step in range(1, 15):
+        while binding.impact_buffer_num_empty(buf) >= wl.B:          # the workers send what fits
+            x = workloads.make_trajectories(wl, wl.B, stream=300 + n_blocks)
+            d = to_device(x, torch)
+            slots_in = binding.impact_buffer_insert(buf, {k: d[k] for k in ("worker", "actions", "rewards", "dones")})
+            assert slots_in.tolist() == ob.insert_records(x["worker"], x["actions"], x["rewards"], x["dones"])
+            for i, s in enumerate(slots_in):
+                held[int(s)] = n_pool + i
+            pool = x if pool is None else {k: np.concatenate([pool[k], x[k]], axis=0 if x[k].ndim == 1 else 1) for k in x}
+            n_pool += wl.B
+            n_blocks += 1
+        slots, counts = binding.impact_buffer_sample(buf, wl.B)
+        ws, wc = ob.sample(wl.B)
+        assert slots.tolist() == ws and counts.tolist() == wc
+        xb = workloads.take_trajectories(pool, np.asarray([held[int(s)] for s in slots]))
+        need = binding.impact_buffer_missing_targets(buf, slots)
+        assert need.tolist() == ob.missing_targets(ws) == [i for i, k in enumerate(wc) if k == 0]
+        if len(need):                                                # "if k = 0, evaluate B on target, append"
+            tgt = np.ascontiguousarray(xb["target"][:, need])
+            binding.impact_buffer_put_target(buf, slots[need], torch.from_numpy(tgt).cuda())
+            ob.put_target([ws[i] for i in need], tgt)
+        assert len(binding.impact_buffer_missing_targets(buf, slots)) == 0
+        learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+        out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner, values, boot, cfg)
+        # a full ring cannot take the workers' next batch before the loss above has been enqueued and the discards released
+        if binding.impact_buffer_num_empty(buf) < wl.B and binding.impact_buffer_num_live(buf) + wl.B <= wl.num_slots:
+            with pytest.raises(binding.ImpactError) as e:
+                binding.impact_buffer_reserve(buf, wl.num_slots - binding.impact_buffer_num_live(buf))
+            assert e.value.status == binding.IMPACT_ERR_BUFFER_FULL
+        binding.impact_buffer_release_discarded(buf)                 # "if k = K, discard"
+        ob.release()
+        t, due = binding.impact_buffer_learner_step(buf, period)     # "if t = 0 (mod t_target), update target"
+        assert t == step and due == ob.learner_step(period) == (step % period == 0)
+        syncs.append(due)
+        torch.cuda.synchronize()
+        check_against_oracle(wl, xb, {k: v.cpu().numpy() for k, v in out.items()}, label=f"learner loop step {step}")
+        assert binding.impact_buffer_num_live(buf) == ob.num_live() and binding.impact_buffer_num_empty(buf) == ob.num_empty()
+    assert syncs.count(True) == 2
+    buf.close()
+
+
+def test_records_of_the_last_traversal_survive_until_their_loss(env):
+    """A slot handed out for the K-th time stays out of the workers' reach until it is released: an insert
+    issued between that sample and the loss finds the ring full instead of overwriting what the loss reads."""
+    torch, binding = env
+    wl = shape_workload(workloads.C2, T=20, B=32, num_slots=32, K=1)
+    say("case last traversal, then insert, then loss")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, 32, stream=90)
+    y = workloads.make_trajectories(wl, 32, stream=91)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots, counts = binding.impact_buffer_sample(buf, 32)              # K = 1: this is every slot's last traversal
+    assert binding.impact_buffer_num_live(buf) == 0 and binding.impact_buffer_num_empty(buf) == 0
+    with pytest.raises(binding.ImpactError) as e:
+        binding.impact_buffer_insert(buf, to_device(y, torch))          # the workers' next batch: not yet
+    assert e.value.status == binding.IMPACT_ERR_BUFFER_FULL
+    cfg = binding.config_from_hyper(wl.hyper)
+    dev = to_device(x, torch)
+    out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), dev["learner"], dev["values"],
+                                                  dev["bootstrap"], cfg)
+    binding.impact_buffer_release_discarded(buf)
+    binding.impact_buffer_insert(buf, to_device(y, torch))              # same stream: ordered after the loss
+    torch.cuda.synchronize()
+    check_against_oracle(wl, x, {k: v.cpu().numpy() for k, v in out.items()}, label="loss of the last traversal")
+    slots2, _ = binding.impact_buffer_sample(buf, 32)
+    devy = to_device(y, torch)
+    out2 = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots2).cuda(), devy["learner"], devy["values"],
+                                                   devy["bootstrap"], cfg)
+    torch.cuda.synchronize()
+    check_against_oracle(wl, y, {k: v.cpu().numpy() for k, v in out2.items()}, label="loss of the batch that replaced it")
+    buf.close()
+
+
+def test_an_invalid_fused_call_enqueues_nothing_and_a_valid_one_follows(env):
+    """Arguments are checked before the completion counter is cleared or anything else touches the stream; a
+    counter left non-zero by a failed launch is recovered with impact_buffer_reset_lanes."""
+    torch, binding = env
+    wl = shape_workload(workloads.C3, B=64, num_slots=64)
+    say("case invalid fused call, then valid")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    buf.storage[-256:] = 0x5A                            # garbage in the block of completion counters
+    x = workloads.make_trajectories(wl, 64, stream=92)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots, _ = binding.impact_buffer_sample(buf, 64)
+    dev = to_device(x, torch)
+    args = (buf, torch.from_numpy(slots).cuda(), dev["learner"], dev["values"], dev["bootstrap"])
+    with pytest.raises(binding.ImpactError) as e:
+        binding.impact_loss_fwd_bwd_from_buffer(*args, binding.make_config(gamma=float("nan")))
+    assert e.value.status == binding.IMPACT_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert int(buf.storage[-256:].min()) == 0x5A and int(buf.storage[-256:].max()) == 0x5A     # nothing ran on the storage
+    cfg = binding.config_from_hyper(wl.hyper)
+    out = binding.impact_loss_fwd_bwd_from_buffer(*args, cfg)
+    torch.cuda.synchronize()
+    check_against_oracle(wl, x, {k: v.cpu().numpy() for k, v in out.items()}, label="valid call after an invalid one")
+    # a counter that a launch left behind non-zero (planted here from the host) makes the next launch skip the final
+    # sum; after impact_buffer_reset_lanes the lane is cleared again before its next launch
+    buf.storage[-256:-252] = 1
+    binding.impact_buffer_reset_lanes(buf)
+    out["loss5"].fill_(float("nan"))
+    out2 = binding.impact_loss_fwd_bwd_from_buffer(*args, cfg, out=out)
+    torch.cuda.synchronize()
+    check_against_oracle(wl, x, {k: v.cpu().numpy() for k, v in out2.items()}, label="after reset_lanes")
     buf.close()

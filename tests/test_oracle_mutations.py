@@ -95,22 +95,32 @@ RING_SRC = os.path.join(ROOT, "oracle", "buffer.py")
 # stands on an empty slot whenever there is one: on every reachable state that search finds its slot at once.)
 RING_MUTATIONS = [
     ("an item lives for K + 1 traversals", "if self.count[s] == self.K:", "if self.count[s] == self.K + 1:"),
+    ("a discarded item's place is free before its gradient step", "self.count[s] = DISCARDED", "self.count[s] = EMPTY"),
+    ("release frees nothing", "                self.count[s] = EMPTY\n", "                pass\n"),
+    ("the next sample does not release", "        self.release()                            # the previous", "        pass  # the previous"),
+    ("the target period counts trajectories, not batches", "return (num_slots // B) * K", "return num_slots * K"),
+    ("the target update is due one step late", "return self.t % t_target == 0", "return self.t % t_target == 1"),
+    ("the step counter stands still", "        self.t += 1\n", ""),
+    ("missing_targets lists the items that have one", "if not self.has_target[s]]", "if self.has_target[s]]"),
+    ("a fresh item inherits its place's target flag", "            self.has_target[self.w] = with_target\n", ""),
     ("the count returned includes this traversal", "counts.append(self.count[s])", "counts.append(self.count[s] + 1)"),
     ("sample does not skip empty slots", "while self.count[self.r] < 0:", "while False:"),
     ("the read cursor stays where it is", "            self.r = (self.r + 1) % self.N\n        return slots, counts", "        return slots, counts"),
-    ("an insert that fits exactly is refused", "if self.N - self.num_live() < n:", "if self.N - self.num_live() <= n:"),
+    ("an insert that fits exactly is refused", "if self.num_empty() < n:", "if self.num_empty() <= n:"),
     ("a fresh item starts at count one", "self.count[self.w] = 0", "self.count[self.w] = 1"),
 ]
 
 
 def _ring_pins(monkeypatch, module):
     import test_oracle_buffer as pins
-    for name in ("RingOracle", "BufferOracle", "BufferFull", "NotEnoughLive"):
+    for name in ("RingOracle", "BufferOracle", "BufferFull", "NotEnoughLive", "target_period"):
         monkeypatch.setattr(pins, name, getattr(module, name))
     for N, K in [(1, 1), (3, 1), (4, 2), (5, 3), (8, 3)]:
         pins.test_every_item_is_replayed_exactly_K_times_in_order(N, K)
     pins.test_full_ring_without_inserts_is_K_passes_of_the_same_minibatches()
     pins.test_fifo_and_replacement_after_discard()
+    pins.test_target_update_every_N_K_steps_is_ppo_s_schedule()
+    pins.test_items_inserted_with_their_target_output_need_none()
     pins.test_bad_arguments()
 
 
