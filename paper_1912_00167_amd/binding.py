@@ -16,7 +16,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libimpact.so")
+# IMPACT_LIB_PATH: load this build of the library instead (e.g. one compiled with sanitizers)
+LIB_PATH = os.environ.get("IMPACT_LIB_PATH") or os.path.join(_HERE, "libimpact.so")
 
 IMPACT_OK = 0
 IMPACT_ERR_INVALID_ARG = -1
