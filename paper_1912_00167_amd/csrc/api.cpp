@@ -553,6 +553,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.step_out = reinterpret_cast<float4 *>(out->step_outputs);
     a.partials = static_cast<float *>(workspace);
     a.num_segs = 1;
+    a.num_partials = num_tiles(B);
     if (num_tiles(B) <= SEG_MAX_TILES)
         a.seg_agg = reinterpret_cast<double *>(static_cast<char *>(workspace) +
                                                align_up((size_t)num_tiles(B) * SEG_MAX * PARTIAL_STRIDE * sizeof(float), 256));
@@ -602,7 +603,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     }
     if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
     if (!done_count) {
-        ReduceArgs r{a.partials, num_tiles(B) * a.num_segs, 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
+        ReduceArgs r{a.partials, a.num_partials, 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
         launch_reduce(r, s);
     }
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;

@@ -56,7 +56,8 @@ struct LossArgs {
     float *vs;                // [T][B] or null
     float *adv;               // [T][B] or null
     float4 *step_out;         // [T][B] records {dL/dV, vs, adv, 0} in place of the three tensors above, or null
-    float *partials;          // [num_tiles][PARTIAL_STRIDE]
+    float *partials;          // [num_partials][PARTIAL_STRIDE]
+    int num_partials;         // sets of partial sums the launch leaves (one per workgroup); set by the launcher
     // Long trajectories of a small batch are cut into num_segs time segments of seg_chunks chunks each,
     // one workgroup per (tile, segment).  The scan is affine in its carry, acc_t = A_t + P_t * carry, so a
     // first launch (phase 1) only finds every segment's A and P at its first step (seg_agg[seg][b][2]) and a

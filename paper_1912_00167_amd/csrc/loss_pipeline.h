@@ -10,6 +10,7 @@
 //   learner(...)           ratio, surrogate, entropy, KL and the gradients, written over the learner's
 //                          distribution parameters in LDS
 #pragma once
+#include <cstdlib>
 #include <type_traits>
 
 #include "loss_device.h"
@@ -26,10 +27,17 @@ namespace impact {
 // held up issuing loads into a full memory queue the others compute.
 // ST: storage type of the buffer-resident fields; LT: type of the learner's distribution tensor (fp32, or
 // bf16 as a network under mixed precision produces it; the gradients leave in fp32 either way).
-template <class Policy, typename ST, typename LT, bool SLOT, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
+//
+// G: tiles per workgroup.  Single-wavefront tiles (NW == 1) may be launched four to a workgroup: the four
+// wavefronts still walk their own tiles without ever meeting after the set-up, but they are neighbours in the
+// batch, start together on one compute unit and stay close in phase, so that the 32-byte pieces which each of
+// them reads and writes of every [T][B] row (one 128-byte line per four tiles) meet in the cache as whole lines.
+template <class Policy, typename ST, typename LT, bool SLOT, int NW, int G = 1>
+__global__ __launch_bounds__(64 * NW * G) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
 void loss_static(const LossArgs a)
 {
+    static_assert(G == 1 || NW == 1, "only single-wavefront tiles share a workgroup");
+    constexpr int NR = NW * G;                     // wavefronts per workgroup, each with staging regions of its own
     // fp32 learner rows are overwritten by their gradients in place; narrower ones get a region for them
     constexpr bool INPLACE = std::is_same<LT, float>::value;
     constexpr int W = Policy::W;                   // elements of a distribution tensor per step
@@ -44,47 +52,56 @@ void loss_static(const LossArgs a)
     constexpr bool CACHED = Policy::CACHED, TGT = Policy::TGT;
     // per-wavefront staging regions: actions, worker, target (storage dtype), cached pair (fp64),
     // learner / gradients (fp32)
-    __shared__ __align__(16) ST r_act_all[ACT > 0 ? NW : 1][ACT > 0 ? SPW * ACT : 8];
-    __shared__ __align__(16) ST r_wk_all[CACHED ? 1 : NW][CACHED ? 8 : SPW * W];
-    __shared__ __align__(16) ST r_tg_all[TGT ? NW : 1][TGT ? SPW * W : 8];
-    __shared__ __align__(16) double r_lp_all[CACHED ? NW : 1][CACHED ? SPW * 2 : 2];
+    __shared__ __align__(16) ST r_act_all[ACT > 0 ? NR : 1][ACT > 0 ? SPW * ACT : 8];
+    __shared__ __align__(16) ST r_wk_all[CACHED ? 1 : NR][CACHED ? 8 : SPW * W];
+    __shared__ __align__(16) ST r_tg_all[TGT ? NR : 1][TGT ? SPW * W : 8];
+    __shared__ __align__(16) double r_lp_all[CACHED ? NR : 1][CACHED ? SPW * 2 : 2];
     // two learner regions when they fit the 64 KB of static LDS: the next chunk's learner rows then load
     // while this chunk's gradients are still being produced in the other one
     constexpr int BEHAVIOUR_BYTES = (ACT + (CACHED ? 0 : W) + (TGT ? W : 0)) * (int)sizeof(ST) + (CACHED ? 16 : 0);
     constexpr int LEARNER_BYTES = W * (int)sizeof(LT);
     constexpr int LDS_ONE = NW * SPW * (BEHAVIOUR_BYTES + LEARNER_BYTES + (INPLACE ? 0 : W * 4)) + 4 * TCH * NB * 8 + 1024;
-    constexpr int NLN = (LDS_ONE + NW * SPW * LEARNER_BYTES <= 64 * 1024) ? 2 : 1;
+    constexpr int NLN = (LDS_ONE + NW * SPW * LEARNER_BYTES <= 64 * 1024) ? 2 : 1;     // (per tile: G tiles take G times this)
     // (two separate variables, and the chunk body is instantiated per parity, so that the compiler can
     // tell a read of one region from an asynchronous load still in flight into the other)
-    __shared__ __align__(16) LT r_ln0_all[NW][SPW * W];
-    __shared__ __align__(16) LT r_ln1_all[NLN == 2 ? NW : 1][NLN == 2 ? SPW * W : 8];
-    __shared__ __align__(16) float r_gr_all[INPLACE ? 1 : NW][INPLACE ? 4 : SPW * W];
-    __shared__ double sd[2][TCH * NB];
-    __shared__ double sg[2][TCH * NB];
+    __shared__ __align__(16) LT r_ln0_all[NR][SPW * W];
+    __shared__ __align__(16) LT r_ln1_all[NLN == 2 ? NR : 1][NLN == 2 ? SPW * W : 8];
+    __shared__ __align__(16) float r_gr_all[INPLACE ? 1 : NR][INPLACE ? 4 : SPW * W];
+    __shared__ double sd[G][2][TCH * NB];
+    __shared__ double sg[G][2][TCH * NB];
     // where the tile's trajectories start in the buffer: in steps (rewards, flags), and in bytes of the
     // distribution planes and of the action plane, whose slots are padded to 16 bytes
-    __shared__ int slot_row0[NB];
-    __shared__ unsigned slot_dist0[NB], slot_act0[NB], slot_lp0[NB];
-    __shared__ float red[NW][PARTIAL_STRIDE];
+    __shared__ int slot_row0_all[G][NB];
+    __shared__ unsigned slot_dist0_all[G][NB], slot_act0_all[G][NB], slot_lp0_all[G][NB];
+    __shared__ float red[NR][PARTIAL_STRIDE];
     __shared__ double exp_tbl[EXP_TABLE_SIZE];
     // A wavefront that walks its trajectories alone (NW == 1) reads their rewards and termination flags
     // from the buffer once, whole, instead of a few bytes per trajectory and chunk.
     constexpr bool PRE = NW == 1 && SLOT;
-    __shared__ ST pre_r[PRE ? NB * T_PRELOAD : 1];
-    __shared__ uint8_t pre_d[PRE ? NB * T_PRELOAD : 4];
-    __shared__ int pre_a[PRE && ACT == 0 ? NB * T_PRELOAD : 1];
+    __shared__ ST pre_r_all[G][PRE ? NB * T_PRELOAD : 1];
+    __shared__ uint8_t pre_d_all[G][PRE ? NB * T_PRELOAD : 4];
+    __shared__ int pre_a_all[G][PRE && ACT == 0 ? NB * T_PRELOAD : 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wreg = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront of the workgroup: selects the staging regions
+    const int wave = G > 1 ? 0 : wreg;             // wavefront of the tile: selects its share of a chunk's rows
+    const int grp = G > 1 ? wreg : 0;              // tile of the workgroup
+    int *slot_row0 = slot_row0_all[grp];
+    unsigned *slot_dist0 = slot_dist0_all[grp], *slot_act0 = slot_act0_all[grp], *slot_lp0 = slot_lp0_all[grp];
+    ST *pre_r = pre_r_all[grp];
+    uint8_t *pre_d = pre_d_all[grp];
+    int *pre_a = pre_a_all[grp];
+    const int tt = G > 1 ? lane : tid;             // "thread of the tile": its first NB run the per-trajectory work
     const int step = lane / P, part = lane % P;    // step within the wavefront, share of its dimensions
     const int rl = step / NB, bl = step % NB, tl = wave * RWP + rl;
     const bool lead = part == 0;                   // the lane that stores the step's scalars
     // one workgroup per (tile, time segment); a single segment unless the launcher cut the trajectories
     // (only the workgroup shape of small batches is ever launched that way: the others carry none of it)
     constexpr bool SEGS = NW == NWAVES;
-    const int ntiles = SEGS ? num_tiles(a.B) : (int)gridDim.x;
+    const int ntiles = SEGS ? num_tiles(a.B) : (int)gridDim.x;          // (workgroups per time segment)
     const int seg = SEGS ? (int)blockIdx.x / ntiles : 0;
-    const int tile = tile_of_block((int)blockIdx.x - seg * ntiles, ntiles);
+    const int tile_group = tile_of_block((int)blockIdx.x - seg * ntiles, ntiles);
+    const int tile = tile_group * G + grp;
     const bool agg_only = SEGS && a.phase == 1;    // first launch of a segmented step: the scan's pair only
     // The last tile of a batch may hold fewer than NB trajectories.  Its missing lanes shadow the last real
     // trajectory (every address stays inside the tensors) and drop their results; the tile takes the
@@ -92,15 +109,15 @@ void loss_static(const LossArgs a)
     const int b0 = tile * NB, nb = min(NB, a.B - b0);
     const bool mine = bl < nb;
     const int b = b0 + min(bl, nb - 1);
-    ST *r_act = r_act_all[ACT > 0 ? wave : 0], *r_wk = r_wk_all[CACHED ? 0 : wave], *r_tg = r_tg_all[TGT ? wave : 0];
-    double *r_lp = r_lp_all[CACHED ? wave : 0];
+    ST *r_act = r_act_all[ACT > 0 ? wreg : 0], *r_wk = r_wk_all[CACHED ? 0 : wreg], *r_tg = r_tg_all[TGT ? wreg : 0];
+    double *r_lp = r_lp_all[CACHED ? wreg : 0];
 
     float bad = 0.f;
     // the slot indices travel (possibly across the bus, from page-locked host memory) while the first
     // learner rows are requested, which need no slot, and the table is computed
     int my_slot = 0;
-    if (SLOT && tid < NB) {
-        const int at = b0 + min(tid, nb - 1);
+    if (SLOT && tt < NB) {
+        const int at = b0 + min(tt, nb - 1);
         if (a.slot_first >= 0) {                   // a run of consecutive slots (the ring's own order): nothing to read
             my_slot = a.slot_first + at;
             if (my_slot >= a.num_slots) my_slot -= a.num_slots;
@@ -130,16 +147,16 @@ void loss_static(const LossArgs a)
     if (tail_rows > 0) {
         ld_lrn.plan(a.B, tail_rows, nullptr, lane, nb * W * (int)sizeof(LT) / 16);
         if (!agg_only)
-            ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wave], lane);
+            ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wreg], lane);
     }
-    exp64_table_init(exp_tbl, tid, 64 * NW);
-    if (SLOT && tid < NB) {
+    exp64_table_init(exp_tbl, tid, 64 * NR);
+    if (SLOT && tt < NB) {
         int s = my_slot;
         if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
-        slot_row0[tid] = s * a.T;
-        slot_dist0[tid] = (unsigned)s * (unsigned)a.stride_dist;
-        slot_act0[tid] = (unsigned)s * (unsigned)a.stride_act;
-        slot_lp0[tid] = (unsigned)s * (unsigned)a.stride_lp;
+        slot_row0[tt] = s * a.T;
+        slot_dist0[tt] = (unsigned)s * (unsigned)a.stride_dist;
+        slot_act0[tt] = (unsigned)s * (unsigned)a.stride_act;
+        slot_lp0[tt] = (unsigned)s * (unsigned)a.stride_lp;
     }
     __syncthreads();
     if (tail_rows > 0) {
@@ -253,9 +270,9 @@ void loss_static(const LossArgs a)
     auto chunk = [&](auto parity, auto is_tail, int c) {
         constexpr int Q = decltype(parity)::value;
         constexpr bool TAIL = decltype(is_tail)::value;
-        LT *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wave] : r_ln0_all[wave];
-        LT *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wave] : r_ln0_all[wave];
-        float *r_gr = INPLACE ? (float *)r_ln : r_gr_all[INPLACE ? 0 : wave];     // where this chunk's gradients go
+        LT *r_ln = (NLN == 2 && Q == 1) ? r_ln1_all[wreg] : r_ln0_all[wreg];
+        LT *r_ln_next = (NLN == 2 && Q == 0) ? r_ln1_all[wreg] : r_ln0_all[wreg];
+        float *r_gr = INPLACE ? (float *)r_ln : r_gr_all[INPLACE ? 0 : wreg];     // where this chunk's gradients go
         const int t_base = c * TCH + wave * RWP;
         const int rows = TAIL ? min(RWP, a.T - t_base) : RWP;   // valid time rows of this wave, may be <= 0
         const int t = t_base + rl;
@@ -300,11 +317,11 @@ void loss_static(const LossArgs a)
         }
         // ---- scan: adv_t ----
         if (lead) {
-            sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
-            sg[par][tl * NB + bl] = valid ? sc.gco : 0.0;
+            sd[grp][par][tl * NB + bl] = valid ? sc.delta : 0.0;
+            sg[grp][par][tl * NB + bl] = valid ? sc.gco : 0.0;
         }
-        chunk_scan<TCH, NW>(sd[par], sg[par], carry, tid, SEGS && skip ? &coeff : nullptr);
-        const double adv = sd[par][tl * NB + bl];
+        chunk_scan<TCH, NW>(sd[grp][par], sg[grp][par], carry, tt, SEGS && skip ? &coeff : nullptr);
+        const double adv = sd[grp][par][tl * NB + bl];
         // the per-step outputs that depend on the scan alone leave now, ahead of the next chunk's loads
         if (valid && lead && !skip) {
             const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);        // V - vs = -adv
@@ -386,7 +403,8 @@ void loss_static(const LossArgs a)
         return;
     }
     // (the final sum's load blocks sized to the registers this policy's kernels have anyway)
-    store_partials<NW, Policy::SIMD_WAVES == 2 && !CACHED ? 32 : 16>(red, a, tile + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    // (one set of partial sums per workgroup: its G tiles, or the NW wavefronts of its one tile, are added up first)
+    store_partials<NR, Policy::SIMD_WAVES == 2 && !CACHED ? 32 : 16>(red, a, tile_group + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
 }
 
 
@@ -418,6 +436,61 @@ inline int waves_per_tile(const LossArgs &a, bool slot_major)
     return nw;
 }
 
+template <class Policy, int NW, int G>
+void launch_loss_static_shape(int dtype, bool slot_major, const LossArgs &a, dim3 grid, hipStream_t s)
+{
+    const dim3 block(64 * NW * G);
+    if (a.learner_bf16) {      // (instantiated for the fused form on a bf16 buffer; see learner_bf16_has_kernel)
+        hipLaunchKernelGGL((loss_static<Policy, bf16_t, bf16_t, true, NW, G>), grid, block, 0, s, a);
+    } else if (dtype == IMPACT_F32) {
+        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, float, true, NW, G>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_static<Policy, float, float, false, NW, G>), grid, block, 0, s, a);
+    } else {
+        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, true, NW, G>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, false, NW, G>), grid, block, 0, s, a);
+    }
+}
+
+// Static LDS of the kernel that a launch of this kind would run (0 if it cannot be found out).
+template <class Policy, int NW, int G>
+size_t lds_bytes_of(int dtype, bool slot_major, const LossArgs &a)
+{
+    hipFuncAttributes attr;
+    hipError_t e;
+    if (a.learner_bf16) e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, bf16_t, true, NW, G>));
+    else if (dtype == IMPACT_F32)
+        e = slot_major ? hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, float, float, true, NW, G>))
+                       : hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, float, float, false, NW, G>));
+    else
+        e = slot_major ? hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, float, true, NW, G>))
+                       : hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, float, false, NW, G>));
+    if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
+    return attr.sharedSizeBytes;
+}
+
+// A group of G tiles must leave room for a second group on the compute unit (two wavefronts per SIMD): its LDS
+// may take half of the unit's 160 KB.  Looked up once per kernel.
+template <class Policy, int G>
+bool group_fits_twice(int dtype, bool slot_major, const LossArgs &a)
+{
+    static int cache[2][2][2] = {};                // [learner bf16][dtype][slot major]: 0 unknown, 1 yes, 2 no
+    int &c = cache[a.learner_bf16 ? 1 : 0][dtype == IMPACT_F32 ? 0 : 1][slot_major ? 1 : 0];
+    if (c == 0) {
+        const size_t lds = lds_bytes_of<Policy, 1, G>(dtype, slot_major, a);
+        c = (lds > 0 && lds <= 80 * 1024) ? 1 : 2;
+    }
+    return c == 1;
+}
+
+// Single-wavefront tiles go four to a workgroup when the batch divides that way (and the groups deal out
+// evenly over the eight dies, which the block-to-tile map wants).
+constexpr int TILE_GROUP = 4;
+inline bool tile_groups_enabled()
+{
+    static const bool on = [] { const char *e = getenv("IMPACT_TILE_GROUPS"); return !(e && e[0] == '0'); }();
+    return on;
+}
+
 template <class Policy, int NW>
 void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
@@ -432,18 +505,18 @@ void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t 
         a.seg_chunks = (nchunk + want - 1) / want;
         a.num_segs = (nchunk + a.seg_chunks - 1) / a.seg_chunks;
     }
-    const dim3 grid(tiles * a.num_segs), block(64 * NW);
+    if constexpr (NW == 1) {
+        if (a.B % (NB * TILE_GROUP) == 0 && (tiles / TILE_GROUP) % 8 == 0 && tile_groups_enabled() &&
+            group_fits_twice<Policy, TILE_GROUP>(dtype, slot_major, a)) {
+            a.num_partials = tiles / TILE_GROUP;
+            launch_loss_static_shape<Policy, 1, TILE_GROUP>(dtype, slot_major, a, dim3(tiles / TILE_GROUP), s);
+            return;
+        }
+    }
+    a.num_partials = tiles * a.num_segs;
     for (int phase = a.num_segs > 1 ? 1 : 0; phase <= (a.num_segs > 1 ? 2 : 0); ++phase) {
         a.phase = phase;
-        if (a.learner_bf16) {      // (instantiated for the fused form on a bf16 buffer; see learner_bf16_has_kernel)
-            hipLaunchKernelGGL((loss_static<Policy, bf16_t, bf16_t, true, NW>), grid, block, 0, s, a);
-        } else if (dtype == IMPACT_F32) {
-            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, float, true, NW>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((loss_static<Policy, float, float, false, NW>), grid, block, 0, s, a);
-        } else {
-            if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, true, NW>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, false, NW>), grid, block, 0, s, a);
-        }
+        launch_loss_static_shape<Policy, NW, 1>(dtype, slot_major, a, dim3(tiles * a.num_segs), s);
     }
 }
 
