@@ -10,12 +10,32 @@
 //   learner(...)           ratio, surrogate, entropy, KL and the gradients, written over the learner's
 //                          distribution parameters in LDS
 #pragma once
-#include <cstdlib>
 #include <type_traits>
 
 #include "loss_device.h"
 
 namespace impact {
+
+constexpr int LDS_PER_CU = 160 * 1024;            // gfx950: LDS of a compute unit, and the most one workgroup may take
+
+// Static LDS of loss_static<Policy, ST, LT, SLOT, NW, G>, to within the padding between its arrays (kept in
+// step with the declarations in the kernel): what one tile takes, times G, plus what the workgroup shares.
+template <class Policy, typename ST, typename LT, bool SLOT, int NW>
+constexpr int lds_bytes_of_loss_static(int G)
+{
+    constexpr bool INPLACE = std::is_same<LT, float>::value, CACHED = Policy::CACHED, TGT = Policy::TGT;
+    constexpr int W = Policy::W, ACT = Policy::ACT, SPW = 64 / Policy::LANES, TCH = NW * (SPW / NB);
+    constexpr int ES = (int)sizeof(ST), EL = (int)sizeof(LT);
+    constexpr int behaviour = NW * SPW * ((ACT + (CACHED ? 0 : W) + (TGT ? W : 0)) * ES + (CACHED ? 16 : 0));
+    constexpr int learner_one = NW * SPW * W * EL;
+    constexpr int lds_one = NW * SPW * ((ACT + (CACHED ? 0 : W) + (TGT ? W : 0)) * ES + (CACHED ? 16 : 0) + W * EL + (INPLACE ? 0 : W * 4)) + 4 * TCH * NB * 8 + 1024;
+    constexpr int nln = (lds_one + learner_one <= 64 * 1024) ? 2 : 1;
+    constexpr bool PRE = NW == 1 && SLOT;
+    constexpr int preload = PRE ? NB * T_PRELOAD * (ES + 1 + (ACT == 0 ? 4 : 0)) : 0;
+    constexpr int per_tile = behaviour + nln * learner_one + (INPLACE ? 0 : NW * SPW * W * 4) + 4 * TCH * NB * 8 + 4 * NB * 4 +
+                             NW * PARTIAL_STRIDE * 4 + preload + 64;
+    return G * per_tile + EXP_TABLE_SIZE * 8 + 512;
+}
 
 // Order per chunk: (wait for the chunk's data) behaviour pass, scan, (issue the next chunk's loads)
 // learner pass, gradient stores.
@@ -28,10 +48,16 @@ namespace impact {
 // ST: storage type of the buffer-resident fields; LT: type of the learner's distribution tensor (fp32, or
 // bf16 as a network under mixed precision produces it; the gradients leave in fp32 either way).
 //
-// G: tiles per workgroup.  Single-wavefront tiles (NW == 1) may be launched four to a workgroup: the four
-// wavefronts still walk their own tiles without ever meeting after the set-up, but they are neighbours in the
-// batch, start together on one compute unit and stay close in phase, so that the 32-byte pieces which each of
-// them reads and writes of every [T][B] row (one 128-byte line per four tiles) meet in the cache as whole lines.
+// G: tiles per workgroup.  Single-wavefront tiles (NW == 1) are launched several to a workgroup where the LDS
+// allows: eight (one workgroup then fills a compute unit: two wavefronts on each SIMD) or four (two workgroups
+// per compute unit).  The wavefronts still walk their own tiles and never wait for each other after the
+// set-up, but they are neighbours in the batch, start together on one compute unit and stay close in phase:
+//   - the 32-byte pieces which each of them reads and writes of every [T][B] row (one 128-byte line per four
+//     tiles), and the ends of their learner and gradient row segments, meet in the cache as whole lines;
+//   - with eight, the two wavefronts that share a SIMD see each other's progress (a counter per tile in LDS,
+//     updated twice per chunk) and the one ahead lowers its priority.  Left to the SIMD's arbiter, which
+//     serves the older wavefront first, the pair ends 8 us apart and the compute units' last wavefronts
+//     set the kernel's end; with the hand-over the pair ends together.
 template <class Policy, typename ST, typename LT, bool SLOT, int NW, int G = 1>
 __global__ __launch_bounds__(64 * NW * G) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
 void loss_static(const LossArgs a)
@@ -81,6 +107,8 @@ void loss_static(const LossArgs a)
     __shared__ ST pre_r_all[G][PRE ? NB * T_PRELOAD : 1];
     __shared__ uint8_t pre_d_all[G][PRE ? NB * T_PRELOAD : 4];
     __shared__ int pre_a_all[G][PRE && ACT == 0 ? NB * T_PRELOAD : 1];
+    __shared__ int progress[G];                    // chunks each tile of the workgroup has completed
+    __shared__ int simd_count[4], simd_member[4][2];   // the tiles of the workgroup whose wavefronts sit on each SIMD
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wreg = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront of the workgroup: selects the staging regions
@@ -150,6 +178,8 @@ void loss_static(const LossArgs a)
             ld_lrn.issue(ld_lrn.chunk_base(a.learner, a.B, (nchunk - 1) * TCH + wave * RWP, b0), r_ln0_all[wreg], lane);
     }
     exp64_table_init(exp_tbl, tid, 64 * NR);
+    if (tid < G) progress[tid] = 0;
+    if (tid < 4) simd_count[tid] = 0;
     if (SLOT && tt < NB) {
         int s = my_slot;
         if (s < 0 || s >= a.num_slots) { bad = 1.f; s = min(max(s, 0), a.num_slots - 1); }
@@ -159,6 +189,30 @@ void loss_static(const LossArgs a)
         slot_lp0[tt] = (unsigned)s * (unsigned)a.stride_lp;
     }
     __syncthreads();
+    // Which tile of the workgroup shares my SIMD?  (HW_ID bits 5:4 name the SIMD.)  A workgroup of eight
+    // wavefronts normally lands two per SIMD; if it did not, everyone falls back to the priority bands.
+    int partner = -1;
+    if constexpr (G > 1) {
+        const int my_simd = (int)__builtin_amdgcn_s_getreg((4 << 0) | (4 << 6) | (1 << 11)) & 3;
+        if (lane == 0) {
+            const int at = atomicAdd(&simd_count[my_simd], 1);
+            if (at < 2) simd_member[my_simd][at] = grp;
+        }
+        __syncthreads();
+        const bool all_paired = simd_count[0] == 2 && simd_count[1] == 2 && simd_count[2] == 2 && simd_count[3] == 2;
+        if (all_paired) partner = simd_member[my_simd][0] == grp ? simd_member[my_simd][1] : simd_member[my_simd][0];
+        partner = __builtin_amdgcn_readfirstlane(partner);
+    }
+    const bool paired = partner >= 0;
+    auto yield_if_ahead = [&](int done) {
+        __hip_atomic_store(&progress[grp], done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int other = __hip_atomic_load(&progress[max(partner, 0)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int lead_by = __builtin_amdgcn_readfirstlane(done - other);
+        // ahead: lowest priority; behind: highest; level: the arbiter's own order (oldest first)
+        if (lead_by > 0) __builtin_amdgcn_s_setprio(0);
+        else if (lead_by < 0) __builtin_amdgcn_s_setprio(3);
+        else __builtin_amdgcn_s_setprio(2);
+    };
     if (tail_rows > 0) {
         if (ACT > 0) ld_act.plan(a.B, tail_rows, slot_act0, lane, nb * ACTR * (int)sizeof(ST) / 16);
         ld_dist.plan(a.B, tail_rows, slot_dist0, lane, nb * W * (int)sizeof(ST) / 16);
@@ -287,7 +341,10 @@ void loss_static(const LossArgs a)
         // the leader crosses into the next band first and the others outrank it until they follow.  Long
         // bands matter: while one wavefront is clearly favoured the two drift apart in phase and fill each
         // other's stalls, which alternating every chunk would undo.
-        set_priority_band((nchunk - 1 - c) / kPriorityBand);
+        // ... unless the other wavefront of my SIMD belongs to this workgroup (PAIRED, below): then the two watch
+        // each other's progress, counted in half chunks, and whoever is ahead yields.
+        if (paired) yield_if_ahead(2 * (nchunk - 1 - c));
+        else set_priority_band((nchunk - 1 - c) / kPriorityBand);
         // This chunk's loads are complete once only the previous chunk's gradient stores remain
         // (loads and stores of a wavefront retire in issue order).
         wait_all_but_youngest<(NLN == 2 && !TAIL) ? ChunkStorer<W, RWP>::NIT : 0>();
@@ -349,6 +406,7 @@ void loss_static(const LossArgs a)
         // that they fly during this chunk's learner pass.
         wave_lds_sync();
         wait_lds_reads_done();
+        if (paired) yield_if_ahead(2 * (nchunk - 1 - c) + 1);
         if (c > c_lo) {
             fetch_buffer_side(c - 1);
             if (NLN == 2 && !skip) fetch_learner(c - 1, r_ln_next);
@@ -436,59 +494,39 @@ inline int waves_per_tile(const LossArgs &a, bool slot_major)
     return nw;
 }
 
-template <class Policy, int NW, int G>
-void launch_loss_static_shape(int dtype, bool slot_major, const LossArgs &a, dim3 grid, hipStream_t s)
+// Tiles per workgroup for single-wavefront tiles of this kernel: eight or four, if workgroups of that size
+// still fill the compute unit's wavefront slots (4 SIMDs x the wavefronts per SIMD the policy's registers allow)
+// within its LDS; else one.
+template <class Policy, typename ST, typename LT, bool SLOT>
+constexpr int tile_group()
 {
-    const dim3 block(64 * NW * G);
-    if (a.learner_bf16) {      // (instantiated for the fused form on a bf16 buffer; see learner_bf16_has_kernel)
-        hipLaunchKernelGGL((loss_static<Policy, bf16_t, bf16_t, true, NW, G>), grid, block, 0, s, a);
-    } else if (dtype == IMPACT_F32) {
-        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, float, float, true, NW, G>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_static<Policy, float, float, false, NW, G>), grid, block, 0, s, a);
-    } else {
-        if (slot_major) hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, true, NW, G>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((loss_static<Policy, bf16_t, float, false, NW, G>), grid, block, 0, s, a);
+    for (int g : {8, 4}) {
+        const int lds = lds_bytes_of_loss_static<Policy, ST, LT, SLOT, 1>(g);
+        if (lds <= LDS_PER_CU && (LDS_PER_CU / lds) * g >= 4 * Policy::SIMD_WAVES) return g;
     }
+    return 1;
 }
 
-// Static LDS of the kernel that a launch of this kind would run (0 if it cannot be found out).
-template <class Policy, int NW, int G>
-size_t lds_bytes_of(int dtype, bool slot_major, const LossArgs &a)
+// One kernel variant: NW wavefronts per tile; for NW == 1 as many tiles per workgroup as tile_group() says,
+// provided the batch divides that way and the groups deal out evenly over the eight dies (which the
+// block-to-tile map wants); one tile per workgroup otherwise.  Returns the number of workgroups per time segment.
+template <class Policy, typename ST, typename LT, bool SLOT, int NW>
+int launch_loss_static_variant(LossArgs &a, hipStream_t s)
 {
-    hipFuncAttributes attr;
-    hipError_t e;
-    if (a.learner_bf16) e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, bf16_t, true, NW, G>));
-    else if (dtype == IMPACT_F32)
-        e = slot_major ? hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, float, float, true, NW, G>))
-                       : hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, float, float, false, NW, G>));
-    else
-        e = slot_major ? hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, float, true, NW, G>))
-                       : hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(&loss_static<Policy, bf16_t, float, false, NW, G>));
-    if (e != hipSuccess) { (void)hipGetLastError(); return 0; }
-    return attr.sharedSizeBytes;
-}
-
-// A group of G tiles must leave room for a second group on the compute unit (two wavefronts per SIMD): its LDS
-// may take half of the unit's 160 KB.  Looked up once per kernel.
-template <class Policy, int G>
-bool group_fits_twice(int dtype, bool slot_major, const LossArgs &a)
-{
-    static int cache[2][2][2] = {};                // [learner bf16][dtype][slot major]: 0 unknown, 1 yes, 2 no
-    int &c = cache[a.learner_bf16 ? 1 : 0][dtype == IMPACT_F32 ? 0 : 1][slot_major ? 1 : 0];
-    if (c == 0) {
-        const size_t lds = lds_bytes_of<Policy, 1, G>(dtype, slot_major, a);
-        c = (lds > 0 && lds <= 80 * 1024) ? 1 : 2;
+    const int tiles = num_tiles(a.B);
+    if constexpr (NW == 1) {
+        constexpr int G = tile_group<Policy, ST, LT, SLOT>();
+        if constexpr (G > 1) {
+            if (a.B % (NB * G) == 0 && (tiles / G) % 8 == 0) {
+                a.num_partials = tiles / G;
+                hipLaunchKernelGGL((loss_static<Policy, ST, LT, SLOT, 1, G>), dim3(tiles / G), dim3(64 * G), 0, s, a);
+                return tiles / G;
+            }
+        }
     }
-    return c == 1;
-}
-
-// Single-wavefront tiles go four to a workgroup when the batch divides that way (and the groups deal out
-// evenly over the eight dies, which the block-to-tile map wants).
-constexpr int TILE_GROUP = 4;
-inline bool tile_groups_enabled()
-{
-    static const bool on = [] { const char *e = getenv("IMPACT_TILE_GROUPS"); return !(e && e[0] == '0'); }();
-    return on;
+    a.num_partials = tiles * a.num_segs;
+    hipLaunchKernelGGL((loss_static<Policy, ST, LT, SLOT, NW, 1>), dim3(tiles * a.num_segs), dim3(64 * NW), 0, s, a);
+    return tiles;
 }
 
 template <class Policy, int NW>
@@ -505,18 +543,17 @@ void launch_loss_static_nw(int dtype, bool slot_major, LossArgs &a, hipStream_t 
         a.seg_chunks = (nchunk + want - 1) / want;
         a.num_segs = (nchunk + a.seg_chunks - 1) / a.seg_chunks;
     }
-    if constexpr (NW == 1) {
-        if (a.B % (NB * TILE_GROUP) == 0 && (tiles / TILE_GROUP) % 8 == 0 && tile_groups_enabled() &&
-            group_fits_twice<Policy, TILE_GROUP>(dtype, slot_major, a)) {
-            a.num_partials = tiles / TILE_GROUP;
-            launch_loss_static_shape<Policy, 1, TILE_GROUP>(dtype, slot_major, a, dim3(tiles / TILE_GROUP), s);
-            return;
-        }
-    }
-    a.num_partials = tiles * a.num_segs;
     for (int phase = a.num_segs > 1 ? 1 : 0; phase <= (a.num_segs > 1 ? 2 : 0); ++phase) {
         a.phase = phase;
-        launch_loss_static_shape<Policy, NW, 1>(dtype, slot_major, a, dim3(tiles * a.num_segs), s);
+        if (a.learner_bf16) {      // (instantiated for the fused form on a bf16 buffer; see learner_bf16_has_kernel)
+            launch_loss_static_variant<Policy, bf16_t, bf16_t, true, NW>(a, s);
+        } else if (dtype == IMPACT_F32) {
+            if (slot_major) launch_loss_static_variant<Policy, float, float, true, NW>(a, s);
+            else launch_loss_static_variant<Policy, float, float, false, NW>(a, s);
+        } else {
+            if (slot_major) launch_loss_static_variant<Policy, bf16_t, float, true, NW>(a, s);
+            else launch_loss_static_variant<Policy, bf16_t, float, false, NW>(a, s);
+        }
     }
 }
 
