@@ -143,7 +143,13 @@ typedef struct {
  *                                 neighbouring trajectories per wavefront, so a row of records is
  *                                 a whole 128-byte line per wavefront where the three separate
  *                                 tensors each receive a 32-byte piece of one; consumers read the
- *                                 fields as strided views (dL/dV = element 0 of every record). */
+ *                                 fields as strided views (dL/dV = element 0 of every record).
+ *   fractions          [2]        or NULL.  {share of the T*B steps on the clipped branch of the
+ *                                 surrogate, i.e. (adv > 0 and R > 1 + eps) or (adv < 0 and R < 1 - eps):
+ *                                 no policy gradient there (Appendix E); share of the steps whose
+ *                                 importance weight pi_target/pi_worker exceeds rho_bar, i.e. whose
+ *                                 rho_t is truncated (Section 2.2)}: what a training loop logs to see
+ *                                 how far the replayed data has drifted from the target policy. */
 typedef struct {
     float *grad_learner_dist;
     float *grad_values;
@@ -151,6 +157,7 @@ typedef struct {
     float *adv;
     float *loss5;
     float *step_outputs;
+    float *fractions;
 } impact_loss_out_t;
 
 /* Library version, "major.minor". */

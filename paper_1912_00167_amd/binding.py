@@ -82,7 +82,8 @@ class impact_batch_t(ctypes.Structure):
 
 class impact_loss_out_t(ctypes.Structure):
     _fields_ = [("grad_learner_dist", ctypes.c_void_p), ("grad_values", ctypes.c_void_p), ("vs", ctypes.c_void_p),
-                ("adv", ctypes.c_void_p), ("loss5", ctypes.c_void_p), ("step_outputs", ctypes.c_void_p)]
+                ("adv", ctypes.c_void_p), ("loss5", ctypes.c_void_p), ("step_outputs", ctypes.c_void_p),
+                ("fractions", ctypes.c_void_p)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -400,10 +401,12 @@ def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = T
         rec = torch.empty((T, B, 4), dtype=torch.float32, device=device)
         return dict(grad_dist=torch.empty((T, B, W), dtype=torch.float32, device=device), step_outputs=rec,
                     grad_values=rec[..., 0], vs=rec[..., 1], adv=rec[..., 2],
-                    loss5=torch.empty(5, dtype=torch.float32, device=device))
+                    loss5=torch.empty(5, dtype=torch.float32, device=device),
+                    fractions=torch.empty(2, dtype=torch.float32, device=device))
     out = dict(grad_dist=torch.empty((T, B, W), dtype=torch.float32, device=device),
                grad_values=torch.empty((T, B), dtype=torch.float32, device=device),
-               loss5=torch.empty(5, dtype=torch.float32, device=device))
+               loss5=torch.empty(5, dtype=torch.float32, device=device),
+               fractions=torch.empty(2, dtype=torch.float32, device=device))
     if want_targets:
         out["vs"] = torch.empty((T, B), dtype=torch.float32, device=device)
         out["adv"] = torch.empty((T, B), dtype=torch.float32, device=device)
@@ -412,9 +415,10 @@ def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = T
 
 def _out_struct(out: Dict[str, torch.Tensor]) -> impact_loss_out_t:
     if out.get("step_outputs") is not None:
-        return impact_loss_out_t(_ptr(out["grad_dist"]), None, None, None, _ptr(out["loss5"]), _ptr(out["step_outputs"]))
+        return impact_loss_out_t(_ptr(out["grad_dist"]), None, None, None, _ptr(out["loss5"]), _ptr(out["step_outputs"]),
+                                 _ptr(out.get("fractions")))
     return impact_loss_out_t(_ptr(out["grad_dist"]), _ptr(out["grad_values"]), _ptr(out.get("vs")),
-                             _ptr(out.get("adv")), _ptr(out["loss5"]), None)
+                             _ptr(out.get("adv")), _ptr(out["loss5"]), None, _ptr(out.get("fractions")))
 
 
 def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, bootstrap: torch.Tensor,

@@ -557,7 +557,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     if (num_tiles(B) <= SEG_MAX_TILES)
         a.seg_agg = reinterpret_cast<double *>(static_cast<char *>(workspace) +
                                                align_up((size_t)num_tiles(B) * SEG_MAX * PARTIAL_STRIDE * sizeof(float), 256));
-    a.done_count = done_count; a.loss5 = out->loss5;
+    a.done_count = done_count; a.loss5 = out->loss5; a.fractions = out->fractions;
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
@@ -603,7 +603,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     }
     if (!launched) launch_loss_generic(dist, dtype, slot_major, a, s);
     if (!done_count) {
-        ReduceArgs r{a.partials, a.num_partials, 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5};
+        ReduceArgs r{a.partials, a.num_partials, 1.0 / M, cfg->vf_coeff, cfg->ent_coeff, cfg->kl_coeff, out->loss5, out->fractions};
         launch_reduce(r, s);
     }
     return hipGetLastError() == hipSuccess ? IMPACT_OK : IMPACT_ERR_HIP;

@@ -69,6 +69,7 @@ struct LossArgs {
     // caller launches the reduction; loss5 is only written by the kernel in the first case
     unsigned *done_count;
     float *loss5;
+    float *fractions;         // [2] {clipped, truncated} shares of the steps, or null
 };
 
 struct ReduceArgs {
@@ -77,6 +78,7 @@ struct ReduceArgs {
     double inv_M;
     float vf_coeff, ent_coeff, kl_coeff;
     float *loss5;
+    float *fractions;
 };
 
 __host__ __device__ inline int num_tiles(int B) { return (B + NB - 1) / NB; }

@@ -374,12 +374,14 @@ __device__ __forceinline__ double surrogate_log_ratio(const LossArgs &a, double 
 }
 
 // Surrogate value s = min(R adv, clip(R) adv) and the weight g = dL/dlogp_theta(a) of the policy term.
-__device__ __forceinline__ void surrogate(const LossArgs &a, double R, double adv, double &s, double &g)
+// Returns whether the step sits on the clipped branch (no policy gradient).
+__device__ __forceinline__ bool surrogate(const LossArgs &a, double R, double adv, double &s, double &g)
 {
     const double Rc = fmin(fmax(R, a.clip_lo), a.clip_hi);
     s = fmin(R * adv, Rc * adv);
     const bool clipped = (adv > 0.0 && R > a.clip_hi) || (adv < 0.0 && R < a.clip_lo);
     g = clipped ? 0.0 : -adv * R * a.inv_M;
+    return clipped;
 }
 
 // Backward scan of one chunk of TCH time steps.  sd/sg hold delta and gamma*lambda*c for
@@ -426,21 +428,20 @@ __device__ __forceinline__ double wave_sum(double x)
 // U tiles per lane, from tile i0 on, 64 apart: all the loads first (one exposed memory latency), then the
 // additions in the order of the tiles.  GUARD: the block may reach past the last tile.
 template <int U, bool GUARD>
-__device__ __forceinline__ void add_tile_block(const float *partials, int i0, int num_tiles, double (&v)[5])
+__device__ __forceinline__ void add_tile_block(const float *partials, int i0, int num_tiles, double (&v)[7])
 {
-    float4 q[U];
-    float q4[U];
+    float4 q[U], q4[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int i = GUARD ? min(i0 + 64 * u, num_tiles - 1) : i0 + 64 * u;
         q[u] = *(const float4 *)(partials + (size_t)i * PARTIAL_STRIDE);
-        q4[u] = partials[(size_t)i * PARTIAL_STRIDE + 4];
+        q4[u] = *(const float4 *)(partials + (size_t)i * PARTIAL_STRIDE + 4);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!GUARD || i0 + 64 * u < num_tiles) {
             v[0] += (double)q[u].x; v[1] += (double)q[u].y; v[2] += (double)q[u].z; v[3] += (double)q[u].w;
-            v[4] += (double)q4[u];
+            v[4] += (double)q4[u].x; v[5] += (double)q4[u].y; v[6] += (double)q4[u].z;
         }
     }
 }
@@ -450,21 +451,22 @@ __device__ __forceinline__ void add_tile_block(const float *partials, int i0, in
 // An invalid index anywhere in the batch (flagged in the fifth partial) turns all five into NaN.
 // The wavefront that runs this is the last one at work on the chip, so every memory latency here is
 // exposed: the loads go out in blocks as large as the registers hold.
-// UMAX: tiles per lane in the largest block (5 registers each: a kernel that runs three wavefronts per
-// SIMD on 168 registers takes 16, one that has 256 takes 32).
-template <int UMAX = 16>
+// Blocks of 16 tiles per lane (8 registers each); with tile groups a launch leaves a few hundred sets of sums,
+// one round of loads.
 __device__ __forceinline__ void reduce_tiles(const float *partials, int num_tiles, double inv_M, float vf_coeff,
-                                             float ent_coeff, float kl_coeff, float *loss5, int lane)
+                                             float ent_coeff, float kl_coeff, float *loss5, float *fractions, int lane)
 {
-    static_assert(UMAX == 16 || UMAX == 32, "block sizes of the cascade");
-    double v[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    double v[7] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
     int done = 0;                                  // tiles before this one are summed
-    for (; num_tiles - done >= 64 * UMAX; done += 64 * UMAX) add_tile_block<UMAX, false>(partials, done + lane, num_tiles, v);
-    if (UMAX == 32 && num_tiles - done >= 64 * 16) { add_tile_block<16, false>(partials, done + lane, num_tiles, v); done += 64 * 16; }
+    for (; num_tiles - done >= 64 * 16; done += 64 * 16) add_tile_block<16, false>(partials, done + lane, num_tiles, v);
     for (; done < num_tiles; done += 64 * 8) add_tile_block<8, true>(partials, done + lane, num_tiles, v);
 #pragma unroll
-    for (int j = 0; j < 5; ++j) v[j] = wave_sum(v[j]);
+    for (int j = 0; j < 7; ++j) v[j] = wave_sum(v[j]);
     if (lane == 0) {
+        if (fractions) {                           // counts of steps (exact in fp32 per tile, in fp64 here) over M
+            fractions[0] = (float)(v[5] * inv_M);
+            fractions[1] = (float)(v[6] * inv_M);
+        }
         const double pg = -v[0] * inv_M, vf = v[1] * inv_M, h = v[2] * inv_M, kl = v[3] * inv_M;
         const double total = pg + (double)vf_coeff * vf - (double)ent_coeff * h + (double)kl_coeff * kl;
         const float out[5] = {(float)total, (float)pg, (float)vf, (float)h, (float)kl};
@@ -477,14 +479,16 @@ __device__ __forceinline__ void reduce_tiles(const float *partials, int num_tile
 // Sum the per-thread loss terms over the workgroup and store them for the final reduction.  With a
 // completion counter (zero before the launch) the workgroup that finishes last does that reduction
 // itself and leaves the counter at zero again; without one a separate launch follows.
-template <int NW = NWAVES, int UMAX = 16>
+template <int NW = NWAVES>
 __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], const LossArgs &a, int tile, int tid,
-                                               float s, float v, float h, float k, float bad)
+                                               float s, float v, float h, float k, float bad, float clipped, float truncated)
 {
     const int lane = tid & 63, wave = tid >> 6;
     s = wave_sum(s); v = wave_sum(v); h = wave_sum(h); k = wave_sum(k); bad = wave_sum(bad);
+    clipped = wave_sum(clipped); truncated = wave_sum(truncated);
     if (lane == 0) {
         red[wave][0] = s; red[wave][1] = v; red[wave][2] = h; red[wave][3] = k; red[wave][4] = bad;
+        red[wave][5] = clipped; red[wave][6] = truncated;
     }
     __syncthreads();
     if (wave != 0) return;
@@ -492,7 +496,7 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], con
     if (lane == 0) {
         float *mine = a.partials + (size_t)tile * PARTIAL_STRIDE;
 #pragma unroll
-        for (int j = 0; j < 5; ++j) {
+        for (int j = 0; j < 7; ++j) {
             float t = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) t += red[w][j];
@@ -512,7 +516,7 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], con
     // Every other tile's sums were acknowledged before its count.  Copies of those lines that this die's
     // cache may hold from an earlier launch are dropped before they are read (acquire: invalidate only).
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    reduce_tiles<UMAX>(a.partials, (int)gridDim.x, a.inv_M, a.vf_coeff, a.ent_coeff, a.kl_coeff, a.loss5, lane);
+    reduce_tiles(a.partials, (int)gridDim.x, a.inv_M, a.vf_coeff, a.ent_coeff, a.kl_coeff, a.loss5, a.fractions, lane);
     if (lane == 0) *a.done_count = 0;
 }
 

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
     const double ce = a.ent_coeff * a.inv_M, ck = a.kl_coeff * a.inv_M;
 
     double carry = 0.0;
-    float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
+    float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f, n_clipped = 0.f, n_truncated = 0.f;
     const int nchunk = (a.T + TC - 1) / TC;
 
     for (int c = nchunk - 1; c >= 0; --c) {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         const size_t s_buf = SLOT ? ((size_t)slot * a.T + t) : s_tm;
 
         float V = 0.f;
-        double H = 0.0, KL = 0.0, R = 0.0;
+        double H = 0.0, KL = 0.0, R = 0.0, w_step = 0.0;
         ScanInputs sc = {0.0, 0.0};
         int act = 0;
         // quantities the gradient pass needs again
@@ -139,7 +139,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                 }
                 H += A * (kHalfLog2Pi + 0.5);
             }
-            sc = scan_inputs(a, exp(lw), r, done, V, Vn);
+            w_step = exp(lw);
+            sc = scan_inputs(a, w_step, r, done, V, Vn);
             R = exp(surrogate_log_ratio(a, lr1, lw));
         }
         sd[par][tl * NB + bl] = valid ? sc.delta : 0.0;
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
 
         if (valid) {
             double s, g;
-            surrogate(a, R, adv, s, g);
+            n_clipped += surrogate(a, R, adv, s, g) ? 1.f : 0.f;
+            n_truncated += (w_step > (double)a.rho_bar) ? 1.f : 0.f;
             float *gd = a.grad_dist + s_tm * W;
             if (DIST == IMPACT_CATEGORICAL) {
                 const double logS_l = log(S_l), logS_t = log(S_t);
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             sum_k += (float)KL;
         }
     }
-    store_partials(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    store_partials(red, a, tile, tid, sum_s, sum_v, sum_h, sum_k, bad, n_clipped, n_truncated);
 }
 
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s)
@@ -216,7 +218,7 @@ void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a
 
 __global__ __launch_bounds__(64) void reduce_partials(const ReduceArgs r)
 {
-    reduce_tiles(r.partials, r.num_tiles, r.inv_M, r.vf_coeff, r.ent_coeff, r.kl_coeff, r.loss5, threadIdx.x);
+    reduce_tiles(r.partials, r.num_tiles, r.inv_M, r.vf_coeff, r.ent_coeff, r.kl_coeff, r.loss5, r.fractions, threadIdx.x);
 }
 
 void launch_reduce(const ReduceArgs &r, hipStream_t s)

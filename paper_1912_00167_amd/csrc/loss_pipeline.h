@@ -266,6 +266,7 @@ void loss_static(const LossArgs a)
         }
     }
     float sum_s = 0.f, sum_v = 0.f, sum_h = 0.f, sum_k = 0.f;
+    float n_clipped = 0.f, n_truncated = 0.f;      // steps on the clipped branch; steps with pi_target / pi_worker above rho_bar
     // The per-step scalars of a chunk are loaded one chunk ahead as well, into registers: a load issued
     // at the start of a chunk would have to wait for the previous chunk's gradient stores, since
     // outstanding loads and stores of a wavefront retire in issue order.
@@ -417,7 +418,7 @@ void loss_static(const LossArgs a)
         if (rows > 0 && !skip) {
             // ---- learner: ratio, surrogate, entropy, KL; gradients replace the learner's rows in LDS ----
             double s, H, KL;
-            Policy::learner(kept, r_ln + step * W, r_gr + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
+            const bool clipped = Policy::learner(kept, r_ln + step * W, r_gr + step * W, part, adv, w, a, ce, ck, exp_tbl, s, H, KL);
             char *gbase = st_grad.chunk_base(a.grad_dist, a.B, t_base, b0);
             if (TAIL) st_grad.template store<false>(gbase, r_gr, rows, lane, nb * W * 4 / 16);
             else st_grad.template store<true>(gbase, r_gr, rows, lane);
@@ -427,6 +428,8 @@ void loss_static(const LossArgs a)
                 sum_v += (float)(0.5 * adv * adv);
                 sum_h += (float)H;
                 sum_k += (float)KL;
+                n_clipped += clipped ? 1.f : 0.f;
+                n_truncated += (w > (double)a.rho_bar) ? 1.f : 0.f;
             }
         }
         if (NLN == 1) {
@@ -462,7 +465,7 @@ void loss_static(const LossArgs a)
     }
     // (the final sum's load blocks sized to the registers this policy's kernels have anyway)
     // (one set of partial sums per workgroup: its G tiles, or the NW wavefronts of its one tile, are added up first)
-    store_partials<NR, Policy::SIMD_WAVES == 2 && !CACHED ? 32 : 16>(red, a, tile_group + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad);
+    store_partials<NR>(red, a, tile_group + seg * ntiles, tid, sum_s, sum_v, sum_h, sum_k, bad, n_clipped, n_truncated);
 }
 
 

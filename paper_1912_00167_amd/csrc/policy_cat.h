@@ -85,7 +85,7 @@ struct CatPolicy {
     // own: this step's learner logits in LDS; grad: where its gradients go (the same place for fp32
     // logits: all of them are read before the first is overwritten)
     template <typename LT>
-    __device__ __forceinline__ static void learner(const Kept &k, const LT *own, float *grad, int part, double adv,
+    __device__ __forceinline__ static bool learner(const Kept &k, const LT *own, float *grad, int part, double adv,
                                                    double w, const LossArgs &a, double ce_, double ck_,
                                                    const double *exp_tbl, double &s, double &H_, double &KL_)
     {
@@ -128,7 +128,7 @@ struct CatPolicy {
         const double R1 = CACHED ? exp64(xl - k.lt, exp_tbl) / Sl : exp64(xl - k.xt, exp_tbl) * (k.St / Sl);
         const double R = surrogate_ratio(a, R1, w);
         double g;
-        surrogate(a, R, adv, s, g);
+        const bool clipped = surrogate(a, R, adv, s, g);
         const float gf = (float)g;
         const float one_minus_pa = (float)(Sl_others / Sl);               // 1 - p_a without cancellation
 #pragma unroll
@@ -141,6 +141,7 @@ struct CatPolicy {
         }
         H_ = (double)H;
         KL_ = (double)KL;
+        return clipped;
     }
 };
 

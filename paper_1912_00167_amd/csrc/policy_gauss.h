@@ -97,7 +97,7 @@ struct GaussPolicy {
     // own: this step's learner parameters in LDS; grad: where its gradients go (the same place for fp32
     // parameters: every element is read before it is overwritten)
     template <typename LT>
-    __device__ __forceinline__ static void learner(const Kept &k, const LT *own, float *grad, int part, double adv,
+    __device__ __forceinline__ static bool learner(const Kept &k, const LT *own, float *grad, int part, double adv,
                                                    double w, const LossArgs &a, double ce, double ck,
                                                    const double *exp_tbl, double &s, double &H, double &KL)
     {
@@ -119,7 +119,7 @@ struct GaussPolicy {
         // exponentiated once (the two factors alone can leave the fp64 range in opposite directions)
         const double R = exp64(surrogate_log_ratio(a, (k.Qt - Ql) + (k.St - Sl), k.lw), exp_tbl);
         double g;
-        surrogate(a, R, adv, s, g);
+        const bool clipped = surrogate(a, R, adv, s, g);
         // With E = 1 / (2 sigma^2):  dL/dmu = (2g (a - mu) + 2 ck (mu - mu_t)) E
         //   dL/dls = 2g (a - mu)^2 E - 2 ck (sigma_t^2 + (mu - mu_t)^2) E + (ck - g - ce)
         const double g2 = 2.0 * g, ck2 = 2.0 * ck, c0 = ck - g - ce;
@@ -147,6 +147,7 @@ struct GaussPolicy {
         }
         // KL(pi_target || pi_theta) = sum_d [ log sigma - log sigma_t + q_d / 2 - 1/2 ]
         KL = TGT ? (Sl - k.St) + pair_sum<P>(Qk) - 0.5 * D : 0.0;
+        return clipped;
     }
 };
 

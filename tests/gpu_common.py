@@ -122,6 +122,24 @@ def check_against_oracle(wl, x, got, hyper=None, label="", cached=None):
                 viol[near] = np.minimum(viol[near], alt[near])
             report["near_kink_steps"] = int(near.sum())
     report["grad_dist"] = float(viol.max())
+    if "fractions" in got:
+        # shares of clipped steps (Appendix E's min/clip: no policy gradient) and of truncated importance weights
+        # (Section 2.2), counted from the oracle's ratio, advantages and log-probabilities; a step whose ratio or
+        # weight lies within rounding of its threshold may be counted either way
+        R, adv, lp = np.asarray(want["ratio"]), np.asarray(want["adv"]), np.asarray(want["logp3"])
+        w = np.exp(lp[..., 1] - lp[..., 2])
+        if math.isfinite(h.eps):
+            clipped = ((adv > 0) & (R > 1 + h.eps)) | ((adv < 0) & (R < 1 - h.eps))
+            unsure_c = int(((np.abs(R - (1 + h.eps)) <= 2e-5 * (1 + h.eps)) | (np.abs(R - (1 - h.eps)) <= 2e-5) | (np.abs(adv) <= 1e-12)).sum())
+        else:
+            clipped, unsure_c = np.zeros_like(R, bool), 0
+        truncated = w > h.rho_bar
+        unsure_t = int((np.abs(w - h.rho_bar) <= 1e-6 * max(h.rho_bar, 1e-30)).sum())
+        for name, count, unsure, value in (("clipped", int(clipped.sum()), unsure_c, float(got["fractions"][0])),
+                                           ("truncated", int(truncated.sum()), unsure_t, float(got["fractions"][1]))):
+            lo, hi = (count - unsure) / M, (count + unsure) / M
+            report[name] = value
+            assert lo * (1 - 1e-6) - 1e-9 <= value <= hi * (1 + 1e-6) + 1e-9, f"{label}: fraction {name} = {value}, oracle counts {count} +- {unsure} of {M}"
     say(f"    parity {label}: " + ", ".join(f"{k}={v:.3g}" if isinstance(v, float) else f"{k}={v}"
                                               for k, v in report.items()))
     for k in ("vs", "adv", "loss5", "grad_values", "grad_dist"):

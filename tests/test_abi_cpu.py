@@ -37,7 +37,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(B.impact_buffer_desc_t) == 28
     assert ctypes.sizeof(B.impact_loss_config_t) == 40
     assert ctypes.sizeof(B.impact_batch_t) == 6 * ctypes.sizeof(ctypes.c_void_p)
-    assert ctypes.sizeof(B.impact_loss_out_t) == 6 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(B.impact_loss_out_t) == 7 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def _create(lib, dist=0, T=4, A=3, N=8, K=2, storage=0, ptr=FAKE_DEV, nbytes=None):
