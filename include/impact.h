@@ -97,6 +97,11 @@ typedef struct {
  *                                  instead of the target-worker clipped one; rho_clip is then unused
  *                           bit 2: learner_dist holds bfloat16 values (a network under mixed precision);
  *                                  the gradients are fp32 all the same
+ *                           bit 3: the learner-side tensors and the per-step outputs are batch-major:
+ *                                  learner_dist [B][T][W], values [B][T], grad_learner_dist [B][T][W],
+ *                                  grad_values, vs, adv [B][T], step_outputs [B][T][4] (the layout a
+ *                                  network that runs over trajectories, e.g. a recurrent one, produces).
+ *                                  The fields of `batch` stay time-major.  Runs on the shape-generic kernels.
  *                           bits 8-11: lane of impact_loss_fwd_bwd_from_buffer, 0..15 (see there); other
  *                                  calls ignore it */
 typedef struct {
@@ -110,6 +115,7 @@ typedef struct {
 #define IMPACT_FLAG_FORCE_GENERIC 1u
 #define IMPACT_FLAG_RATIO_WORKER 2u
 #define IMPACT_FLAG_LEARNER_BF16 4u
+#define IMPACT_FLAG_BATCH_MAJOR 8u
 #define IMPACT_FLAG_LANE(n) (((uint32_t)(n) & 15u) << 8)
 #define IMPACT_LANES 16
 

@@ -35,6 +35,7 @@ IMPACT_BF16 = 1
 IMPACT_FLAG_FORCE_GENERIC = 1
 IMPACT_FLAG_RATIO_WORKER = 2
 IMPACT_FLAG_LEARNER_BF16 = 4
+IMPACT_FLAG_BATCH_MAJOR = 8
 IMPACT_LANES = 16
 
 
@@ -413,6 +414,12 @@ def alloc_loss_out(T: int, B: int, W: int, device="cuda", want_targets: bool = T
     return out
 
 
+def _tbw(learner: torch.Tensor, cfg: impact_loss_config_t) -> Tuple[int, int, int]:
+    """T, B, W from the learner tensor: [T][B][W], or [B][T][W] under IMPACT_FLAG_BATCH_MAJOR."""
+    d0, d1, W = (int(x) for x in learner.shape)
+    return (d1, d0, W) if cfg.flags & IMPACT_FLAG_BATCH_MAJOR else (d0, d1, W)
+
+
 def _out_struct(out: Dict[str, torch.Tensor]) -> impact_loss_out_t:
     if out.get("step_outputs") is not None:
         return impact_loss_out_t(_ptr(out["grad_dist"]), None, None, None, _ptr(out["loss5"]), _ptr(out["step_outputs"]),
@@ -426,10 +433,10 @@ def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, boots
                         out: Optional[Dict[str, torch.Tensor]] = None, workspace: Optional[torch.Tensor] = None,
                         stream=None) -> Dict[str, torch.Tensor]:
     d = dist_code(dist)
-    T, B, W = (int(x) for x in learner.shape)
+    T, B, W = _tbw(learner, cfg)
     A = W if d == IMPACT_CATEGORICAL else W // 2
     if out is None:
-        out = alloc_loss_out(T, B, W, learner.device)
+        out = alloc_loss_out(*((B, T, W) if cfg.flags & IMPACT_FLAG_BATCH_MAJOR else (T, B, W)), learner.device)
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(d, T, B, A), dtype=torch.uint8, device=learner.device)
     b, o = _batch_struct(batch), _out_struct(out)
@@ -445,7 +452,7 @@ def impact_loss_fwd_bwd_static(dist, learner: torch.Tensor, values: torch.Tensor
                                out: Dict[str, torch.Tensor], stream=None) -> Dict[str, torch.Tensor]:
     """The caller brings every tensor (outputs included): this call allocates nothing, here or in the library."""
     d = dist_code(dist)
-    T, B, W = (int(x) for x in learner.shape)
+    T, B, W = _tbw(learner, cfg)
     A = W if d == IMPACT_CATEGORICAL else W // 2
     b, o = _batch_struct(batch), _out_struct(out)
     cfg = _cfg_for(cfg, learner)
@@ -459,9 +466,9 @@ def impact_loss_fwd_bwd_from_buffer(buf: Buffer, dev_slots: torch.Tensor, learne
                                     values: torch.Tensor, bootstrap: torch.Tensor, cfg: impact_loss_config_t,
                                     out: Optional[Dict[str, torch.Tensor]] = None,
                                     workspace: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
-    T, B, W = (int(x) for x in learner.shape)
+    T, B, W = _tbw(learner, cfg)
     if out is None:
-        out = alloc_loss_out(T, B, W, learner.device)
+        out = alloc_loss_out(*((B, T, W) if cfg.flags & IMPACT_FLAG_BATCH_MAJOR else (T, B, W)), learner.device)
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(buf.dist, T, B, buf.A), dtype=torch.uint8,
                                 device=learner.device)

@@ -535,6 +535,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.T = T; a.B = B; a.A = A;
     a.learner = learner; a.values = values; a.bootstrap = bootstrap;
     a.learner_bf16 = (cfg->flags & IMPACT_FLAG_LEARNER_BF16) ? 1 : 0;
+    a.batch_major = (cfg->flags & IMPACT_FLAG_BATCH_MAJOR) ? 1 : 0;
     a.worker = cached ? nullptr : batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
     a.logp = batch.logp;
     a.rewards = batch.rewards; a.dones = batch.dones;
@@ -561,7 +562,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
 
     // The specialised kernels move whole 16-byte vectors of NB-trajectory row segments.
     const int W = dist == IMPACT_CATEGORICAL ? A : 2 * A;
-    bool fast = !(cfg->flags & IMPACT_FLAG_FORCE_GENERIC);
+    bool fast = !(cfg->flags & (IMPACT_FLAG_FORCE_GENERIC | IMPACT_FLAG_BATCH_MAJOR));   // (batch-major tensors: generic kernels only)
     if (B % NB) {
         // A ragged last tile: the specialised kernels move 16-byte vectors of time-major row segments, so
         // every row of such a tensor has to start on a vector boundary and the ragged segment has to be a

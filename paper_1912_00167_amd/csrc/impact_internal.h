@@ -36,6 +36,7 @@ struct LossArgs {
     // Where given, `worker` is null, and `target` may be (then the KL coefficient is zero).
     const double *logp;
     int learner_bf16;
+    int batch_major;          // learner, values and every per-step output are [B][T][..] instead of [T][B][..] (generic kernels only)
     const int32_t *slots;     // device [B]; slot-major only
     int num_slots;
     int slot_first;           // >= 0: trajectory b lies in slot (slot_first + b) mod num_slots and `slots` is not read

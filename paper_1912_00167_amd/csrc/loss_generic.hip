@@ -63,6 +63,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         const bool valid = b_ok && t < a.T;
         const int par = c & 1;
         const size_t s_tm = (size_t)t * a.B + b;
+        // the learner's tensors and the outputs: time-major [T][B] like the batch, or batch-major [B][T]
+        const size_t s_ln = a.batch_major ? (size_t)b * a.T + t : s_tm;
         const size_t s_buf = SLOT ? ((size_t)slot * a.T + t) : s_tm;
 
         float V = 0.f;
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
         // quantities the gradient pass needs again
         float m_l = 0.f, m_t = 0.f;
         double S_l = 1.0, S_t = 1.0;
-        const LT *zl = (const LT *)a.learner + s_tm * W;
+        const LT *zl = (const LT *)a.learner + s_ln * W;
         // in the buffer's planes a slot's trajectory starts at a multiple of the plane's stride
         const size_t dist_at = SLOT ? (size_t)slot * a.stride_dist + (size_t)t * W * sizeof(ST) : s_tm * W * sizeof(ST);
         const ST *zt = (const ST *)((const char *)a.target + dist_at);
@@ -86,8 +88,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
                             : SLOT ? (const double *)((const char *)a.logp + (size_t)slot * a.stride_lp) + 2 * (size_t)t
                                    : a.logp + 2 * s_tm;
         if (valid) {
-            V = a.values[s_tm];
-            const float Vn = (t + 1 < a.T) ? a.values[s_tm + a.B] : a.bootstrap[b];
+            V = a.values[s_ln];
+            const float Vn = (t + 1 < a.T) ? a.values[s_ln + (a.batch_major ? 1 : a.B)] : a.bootstrap[b];
             const float r = widen(((const ST *)a.rewards)[s_buf]);
             const bool done = a.dones[s_buf] != 0;
             double lw, lr1;      // log(pi_target / pi_worker), log(pi_theta / pi_target) at the action taken
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             double s, g;
             n_clipped += surrogate(a, R, adv, s, g) ? 1.f : 0.f;
             n_truncated += (w_step > (double)a.rho_bar) ? 1.f : 0.f;
-            float *gd = a.grad_dist + s_tm * W;
+            float *gd = a.grad_dist + s_ln * W;
             if (DIST == IMPACT_CATEGORICAL) {
                 const double logS_l = log(S_l), logS_t = log(S_t);
                 double others = 0.0;                     // 1 - p_a as a sum, free of cancellation
@@ -178,11 +180,11 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             }
             const float gV = (float)(-(double)a.vf_coeff * adv * a.inv_M);   // V - vs = -adv
             if (a.step_out) {
-                a.step_out[s_tm] = make_float4(gV, (float)((double)V + adv), (float)adv, 0.f);
+                a.step_out[s_ln] = make_float4(gV, (float)((double)V + adv), (float)adv, 0.f);
             } else {
-                a.grad_values[s_tm] = gV;
-                if (a.vs) a.vs[s_tm] = (float)((double)V + adv);
-                if (a.adv) a.adv[s_tm] = (float)adv;
+                a.grad_values[s_ln] = gV;
+                if (a.vs) a.vs[s_ln] = (float)((double)V + adv);
+                if (a.adv) a.adv[s_ln] = (float)adv;
             }
             sum_s += (float)s;
             sum_v += (float)(0.5 * adv * adv);

@@ -727,3 +727,26 @@ def test_an_invalid_fused_call_enqueues_nothing_and_a_valid_one_follows(env):
     torch.cuda.synchronize()
     check_against_oracle(wl, x, {k: v.cpu().numpy() for k, v in out2.items()}, label="after reset_lanes")
     buf.close()
+
+
+@pytest.mark.parametrize("name,kw", [("C2", dict(T=50, B=64, num_slots=128)), ("C5", dict(T=64, B=40, num_slots=64))])
+def test_batch_major_learner_tensors_with_the_gather_fused(env, name, kw):
+    """Slot-major buffer fields and batch-major learner tensors: every tensor of the call is then laid out
+    trajectory by trajectory."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], **kw)
+    say(f"case batch-major fused {name} {kw}")
+    buf = binding.Buffer(wl.dist, wl.T, wl.A, wl.num_slots, wl.K, wl.storage)
+    x = workloads.make_trajectories(wl, wl.num_slots, stream=93)
+    binding.impact_buffer_insert(buf, to_device(x, torch))
+    slots = np.ascontiguousarray(np.random.default_rng(9).permutation(wl.num_slots)[: wl.B].astype(np.int32))
+    xb = workloads.take_trajectories(x, slots)
+    learner, values, boot = (torch.from_numpy(xb[k]).cuda() for k in ("learner", "values", "bootstrap"))
+    out = binding.impact_loss_fwd_bwd_from_buffer(buf, torch.from_numpy(slots).cuda(), learner.transpose(0, 1).contiguous(),
+                                                  values.t().contiguous(), boot,
+                                                  binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_BATCH_MAJOR))
+    torch.cuda.synchronize()
+    got = {k: out[k].transpose(0, 1).contiguous().cpu().numpy() for k in ("grad_dist", "grad_values", "vs", "adv")}
+    got.update(loss5=out["loss5"].cpu().numpy(), fractions=out["fractions"].cpu().numpy())
+    check_against_oracle(wl, xb, got, label=f"batch-major fused {name}")
+    buf.close()

@@ -254,3 +254,29 @@ def test_episode_end_patterns(env, dist, pattern):
     for flags in (0, FORCE_GENERIC):
         got = gpu_loss(torch, binding, wl, x, flags=flags)
         check_against_oracle(wl, x, got, label=f"episode ends {pattern} {dist} flags={flags}")
+
+
+@pytest.mark.parametrize("name,kw", [("C1", {}), ("C2", dict(T=50, B=40)), ("C3", dict(T=33, B=24)), ("C5", dict(T=40, B=21, storage="f32")),
+                                     ("C4", dict(T=100, B=256))])
+@pytest.mark.parametrize("packed", [False, True], ids=["separate", "packed"])
+def test_batch_major_learner_tensors(env, name, kw, packed):
+    """The learner's distribution, the values and every per-step output handed over trajectory by trajectory
+    ([B][T][..], as a network that runs over whole trajectories produces them): the same numbers as time-major,
+    element for element, and the oracle's within tolerance."""
+    torch, binding = env
+    wl = shape_workload(workloads.WORKLOADS[name], **{"storage": "f32", **kw})
+    x = workloads.make_batch(wl, stream=29)
+    say(f"case batch-major {name} {kw} packed={packed}")
+    d = {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in x.items()}
+    cfg_bm = binding.config_from_hyper(wl.hyper, binding.IMPACT_FLAG_BATCH_MAJOR)
+    out = binding.impact_loss_fwd_bwd(wl.dist, d["learner"].transpose(0, 1).contiguous(), d["values"].t().contiguous(),
+                                      d["bootstrap"], d, cfg_bm,
+                                      out=binding.alloc_loss_out(wl.B, wl.T, wl.W, packed=packed))
+    torch.cuda.synchronize()
+    assert out["grad_dist"].shape == (wl.B, wl.T, wl.W) and out["vs"].shape == (wl.B, wl.T)
+    got = {k: out[k].transpose(0, 1).contiguous().cpu().numpy() for k in ("grad_dist", "grad_values", "vs", "adv")}
+    got.update(loss5=out["loss5"].cpu().numpy(), fractions=out["fractions"].cpu().numpy())
+    check_against_oracle(wl, x, got, label=f"batch-major {name}")
+    tm = gpu_loss(torch, binding, wl, x, flags=FORCE_GENERIC)          # the same kernels on time-major tensors
+    for k in got:
+        np.testing.assert_array_equal(got[k], tm[k], err_msg=k)
