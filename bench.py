@@ -34,7 +34,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 # same counters read for copy kernels of known size (profiles/loss_static_gauss17_C5_fused.md).  Each figure
 # is tied to the kernel sources it was taken on (kernel_sources_digest below): once any of them changes, the
 # benchmark reports null until the counters are taken again.
-MEASURED_TRAFFIC = {}       # workload -> (bytes per launch, digest of the kernel sources at that time)
+MEASURED_TRAFFIC = {       # workload -> (bytes per launch, digest of the kernel sources at that time)
+    "C5": (2.0 * 346514 * 1024 + 310707 * 1024, "48a635d54e3d43a6"),     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
+    "C4": (2.0 * 97563 * 1024 + 69734 * 1024, "48a635d54e3d43a6"),
+}
 
 
 def kernel_sources_digest() -> str:
@@ -340,6 +343,9 @@ def main() -> int:
     ap.add_argument("--series", metavar="FILE", help="also write the bracketed launches' durations (step, ms, ...; one per line) to FILE")
     ap.add_argument("--table", action="store_true",
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
+    ap.add_argument("--table-workloads", default=",".join(sorted(workloads.WORKLOADS)),
+                    help="with --table: the workloads to include (comma-separated; default all)")
+    ap.add_argument("--table-repeats", type=int, default=5, help="with --table: timing repeats per line (median reported)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -352,7 +358,7 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.table:
-        table(torch, binding, sorted(workloads.WORKLOADS))
+        table(torch, binding, [w for w in args.table_workloads.split(",") if w], repeats=args.table_repeats)
         return 0
     wl = workloads.WORKLOADS[args.workload]
     T, B, W = wl.T, wl.B, wl.W
