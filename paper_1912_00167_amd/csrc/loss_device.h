@@ -9,6 +9,12 @@
 
 #include "impact_internal.h"
 
+// The explicit waits of these kernels (vmcnt accounting of loads and stores in issue order, and the ordering of the
+// partial sums before the completion count in store_partials) are written for the gfx9 family's counters.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "libimpact's kernels are written for gfx950"
+#endif
+
 namespace impact {
 
 typedef uint16_t bf16_t;
@@ -503,9 +509,14 @@ __device__ __forceinline__ void store_partials(float (*red)[PARTIAL_STRIDE], con
             __hip_atomic_store(mine + j, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (a.done_count) {
-            // My sums must be out before my count.  A release fence would do it, but it also writes the
-            // whole cache back, gradients and all, once per workgroup; the sums are written through as
-            // device-scope stores instead, and the count waits for their acknowledgement.
+            // My sums must be visible device-wide before my count is.  The compiler's release at agent scope on
+            // this target is "write the L2's dirty lines back (buffer_wbl2 sc1), then s_waitcnt vmcnt(0)": the
+            // write-back is for earlier ordinary stores, the wait makes sure that every earlier store has been
+            // acknowledged before anything later is issued (vmcnt counts stores as well as loads on gfx9).
+            // The sums above are agent-scope atomic stores, which compile to write-through stores
+            // (global_store_dword ... sc1): they leave no dirty line behind, so the write-back (the whole L2,
+            // gradients and all, once per workgroup: +90 us per launch) has nothing to add and the wait alone
+            // orders them before the count.
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             before = __hip_atomic_fetch_add(a.done_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
