@@ -80,9 +80,15 @@ typedef struct {
  *   IMPACT_BUFFER_CACHE_LOGP      keep those two (fp64, computed when the worker's and the target's
  *                                 distributions are handed over) and not the worker's distribution
  *   IMPACT_BUFFER_NO_TARGET_DIST  with CACHE_LOGP: do not keep the target's distribution either;
- *                                 the loss then has no KL term (kl_coeff must be 0) */
+ *                                 the loss then has no KL term (kl_coeff must be 0)
+ * A storage variant of the action taken (Algorithm 1's batches carry it with every step):
+ *   IMPACT_BUFFER_ACTIONS_U8      categorical policies with A <= 256: the buffer keeps the index of the
+ *                                 action as one byte instead of an int32, and `actions` of
+ *                                 impact_buffer_insert and impact_buffer_gather is uint8 [T][n].  An
+ *                                 index >= A is flagged by the loss as any other (NaN in loss5). */
 #define IMPACT_BUFFER_CACHE_LOGP 1u
 #define IMPACT_BUFFER_NO_TARGET_DIST 2u
+#define IMPACT_BUFFER_ACTIONS_U8 4u
 
 /* Hyper-parameters of the loss.
  *   gamma, lambda           discount and GAE-lambda of the V-trace advantage (Section 3.1)
@@ -102,6 +108,10 @@ typedef struct {
  *                                  grad_values, vs, adv [B][T], step_outputs [B][T][4] (the layout a
  *                                  network that runs over trajectories, e.g. a recurrent one, produces).
  *                                  The fields of `batch` stay time-major.  Runs on the shape-generic kernels.
+ *                           bit 4: impact_loss_fwd_bwd only, categorical policies with A <= 256: batch->actions
+ *                                  is uint8 [T][B] (what impact_buffer_gather writes from a buffer with
+ *                                  IMPACT_BUFFER_ACTIONS_U8).  impact_loss_fwd_bwd_from_buffer ignores it:
+ *                                  there the buffer's own flag decides.
  *                           bits 8-11: lane of impact_loss_fwd_bwd_from_buffer, 0..15 (see there); other
  *                                  calls ignore it */
 typedef struct {
@@ -116,13 +126,15 @@ typedef struct {
 #define IMPACT_FLAG_RATIO_WORKER 2u
 #define IMPACT_FLAG_LEARNER_BF16 4u
 #define IMPACT_FLAG_BATCH_MAJOR 8u
+#define IMPACT_FLAG_ACTIONS_U8 16u
 #define IMPACT_FLAG_LANE(n) (((uint32_t)(n) & 15u) << 8)
 #define IMPACT_LANES 16
 
 /* The buffer-resident part of a batch (what a worker sent plus the target
  * network's evaluation appended at k = 0, Algorithm 1).  All device pointers.
  *   worker_dist, target_dist  [T][B][W]
- *   actions                   int32 [T][B] (categorical) or float [T][B][D] (Gaussian)
+ *   actions                   int32 [T][B] (categorical; uint8 [T][B] where the ACTIONS_U8 flags say so)
+ *                             or float [T][B][D] (Gaussian)
  *   rewards                   [T][B]
  *   dones                     uint8 [T][B]; 1 = the transition at t ended the episode
  *   logp                      double [T][B][2] = {log pi_worker(a), log pi_target(a)}, or NULL.

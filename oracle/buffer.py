@@ -127,15 +127,20 @@ class RingOracle:
 class BufferOracle(RingOracle):
     """Ring bookkeeping plus the stored records (slot-major), for gather checks."""
 
-    def __init__(self, dist: str, T: int, A: int, num_slots: int, K: int, storage: str = "f32"):
+    def __init__(self, dist: str, T: int, A: int, num_slots: int, K: int, storage: str = "f32",
+                 actions_u8: bool = False):
         super().__init__(num_slots, K)
+        if actions_u8 and (dist != "categorical" or A > 256):
+            raise ValueError("one-byte action indices: categorical policies with at most 256 actions")
         self.dist, self.T, self.A, self.storage = dist, T, A, storage
         self.W = A if dist == "categorical" else 2 * A
         fdt = np.float32 if storage == "f32" else np.uint16
         N = num_slots
         self.worker = np.zeros((N, T, self.W), fdt)
         self.target = np.zeros((N, T, self.W), fdt)
-        self.actions = np.zeros((N, T), np.int32) if dist == "categorical" else np.zeros((N, T, A), fdt)
+        # categorical: the index of the action taken, as int32 or (a storage variant) as one byte
+        idt = np.uint8 if actions_u8 else np.int32
+        self.actions = np.zeros((N, T), idt) if dist == "categorical" else np.zeros((N, T, A), fdt)
         self.rewards = np.zeros((N, T), fdt)
         self.dones = np.zeros((N, T), np.uint8)
 

@@ -36,6 +36,7 @@ IMPACT_FLAG_FORCE_GENERIC = 1
 IMPACT_FLAG_RATIO_WORKER = 2
 IMPACT_FLAG_LEARNER_BF16 = 4
 IMPACT_FLAG_BATCH_MAJOR = 8
+IMPACT_FLAG_ACTIONS_U8 = 16
 IMPACT_LANES = 16
 
 
@@ -44,6 +45,7 @@ def IMPACT_FLAG_LANE(n: int) -> int:
 
 IMPACT_BUFFER_CACHE_LOGP = 1
 IMPACT_BUFFER_NO_TARGET_DIST = 2
+IMPACT_BUFFER_ACTIONS_U8 = 4
 
 EXPORTS = [
     "impact_version", "impact_status_string",
@@ -252,6 +254,9 @@ class Buffer:
         self.dist, self.T, self.A, self.num_slots, self.K = self.desc.dist, T, A, num_slots, K
         self.W = A if self.dist == IMPACT_CATEGORICAL else 2 * A
         self.float_dtype = torch.float32 if self.desc.storage == IMPACT_F32 else torch.bfloat16
+        # what `actions` of insert and gather holds
+        self.action_dtype = (self.float_dtype if self.dist != IMPACT_CATEGORICAL
+                             else torch.uint8 if flags & IMPACT_BUFFER_ACTIONS_U8 else torch.int32)
         self.device = self.storage.device
 
     def close(self) -> None:
@@ -335,6 +340,8 @@ def impact_buffer_reserve(buf: Buffer, n: int) -> np.ndarray:
 def impact_buffer_insert(buf: Buffer, src: Dict[str, torch.Tensor], stream=None) -> np.ndarray:
     """src: time-major fp32 device tensors worker/actions/rewards/dones (+ optional target)."""
     n = int(src["worker"].shape[1])
+    if buf.dist == IMPACT_CATEGORICAL and src["actions"].dtype != buf.action_dtype:
+        raise TypeError(f"actions: expected {buf.action_dtype}, got {src['actions'].dtype}")
     slots = np.empty(n, dtype=np.int32)
     b = _batch_struct(src, need_target=False)
     _check(load().impact_buffer_insert(buf.handle, n, ctypes.byref(b), slots.ctypes.data_as(ctypes.c_void_p),
@@ -362,7 +369,7 @@ def impact_buffer_sample(buf: Buffer, B: int, out_slots: Optional[np.ndarray] = 
 def alloc_batch(buf: Buffer, B: int) -> Dict[str, torch.Tensor]:
     """Device tensors able to receive a gathered batch (storage dtype)."""
     fd, dev, T = buf.float_dtype, buf.device, buf.T
-    acts = (torch.empty((T, B), dtype=torch.int32, device=dev) if buf.dist == IMPACT_CATEGORICAL
+    acts = (torch.empty((T, B), dtype=buf.action_dtype, device=dev) if buf.dist == IMPACT_CATEGORICAL
             else torch.empty((T, B, buf.A), dtype=fd, device=dev))
     out = dict(actions=acts, rewards=torch.empty((T, B), dtype=fd, device=dev),
                dones=torch.empty((T, B), dtype=torch.uint8, device=dev))

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libimpact.so")
 
-SOURCES = ["api.cpp", "loss_cat.hip", "loss_cat_cached.hip", "loss_gauss.hip", "loss_gauss_cached.hip",
+SOURCES = ["api.cpp", "loss_cat.hip", "loss_cat_cached.hip", "loss_cat_u8.hip", "loss_gauss.hip", "loss_gauss_cached.hip",
            "loss_generic.hip", "buffer_kernels.hip", "static_workspace.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall"]

@@ -27,7 +27,8 @@ bool desc_ok(const impact_buffer_desc_t *d)
     // keep every element index of a plane below 2^40 and W within int range
     if ((double)d->num_slots * d->T * (2.0 * d->A) > 1.0e12) return false;
     if (d->A > (1 << 20)) return false;
-    if (d->flags & ~(IMPACT_BUFFER_CACHE_LOGP | IMPACT_BUFFER_NO_TARGET_DIST)) return false;
+    if (d->flags & ~(IMPACT_BUFFER_CACHE_LOGP | IMPACT_BUFFER_NO_TARGET_DIST | IMPACT_BUFFER_ACTIONS_U8)) return false;
+    if ((d->flags & IMPACT_BUFFER_ACTIONS_U8) && (d->dist != IMPACT_CATEGORICAL || d->A > 256)) return false;
     if ((d->flags & IMPACT_BUFFER_NO_TARGET_DIST) && !(d->flags & IMPACT_BUFFER_CACHE_LOGP)) return false;
     return true;
 }
@@ -41,6 +42,7 @@ struct Planes {
     size_t worker, target, actions, rewards, dones, logp, sync, total;
     size_t stride_dist, stride_act, stride_rew, stride_done, stride_lp;
     bool has_worker, has_target, has_logp;
+    int act_bytes;                 // categorical: bytes of an action index in the action plane (4, or 1)
 };
 
 Planes plane_layout(const impact_buffer_desc_t &d)
@@ -50,7 +52,8 @@ Planes plane_layout(const impact_buffer_desc_t &d)
     const size_t N = (size_t)d.num_slots, T = (size_t)d.T;
     Planes p;
     p.stride_dist = align_up(T * W * es, 16);
-    p.stride_act = align_up(d.dist == IMPACT_CATEGORICAL ? T * 4 : T * d.A * es, 16);
+    p.act_bytes = (d.flags & IMPACT_BUFFER_ACTIONS_U8) ? 1 : 4;
+    p.stride_act = align_up(d.dist == IMPACT_CATEGORICAL ? T * (size_t)p.act_bytes : T * d.A * es, 16);
     p.stride_rew = T * es;
     p.stride_done = T;
     p.stride_lp = T * 2 * sizeof(double);
@@ -348,7 +351,7 @@ static void cache_logp_field(impact_buffer *buf, int which, const float *dist_f3
         while (j < n && slots[j] == slots[j - 1] + 1) ++j;
         LogpArgs a{dist_f32, buf->storage + buf->planes.actions, reinterpret_cast<double *>(buf->storage + buf->planes.logp),
                    d.dist, d.storage, d.T, n, d.A, i, slots[i], j - i, which, buf->planes.stride_act,
-                   buf->planes.stride_lp};
+                   buf->planes.stride_lp, buf->planes.act_bytes};
         launch_cache_logp(a, s);
         i = j;
     }
@@ -378,7 +381,8 @@ impact_status_t impact_buffer_insert(impact_buffer_t *buf, int32_t n, const impa
     if (src->target_dist && pl.has_target)
         scatter_field(fk, src->target_dist, base + pl.target, pl.stride_dist / es, d.T, n, buf->W(), out_slots, s);
     if (d.dist == IMPACT_CATEGORICAL)
-        scatter_field(PLANE_I32, src->actions, base + pl.actions, pl.stride_act / 4, d.T, n, 1, out_slots, s);
+        scatter_field(pl.act_bytes == 1 ? PLANE_U8 : PLANE_I32, src->actions, base + pl.actions,
+                      pl.stride_act / (size_t)pl.act_bytes, d.T, n, 1, out_slots, s);
     else
         scatter_field(fk, src->actions, base + pl.actions, pl.stride_act / es, d.T, n, d.A, out_slots, s);
     if (pl.has_logp) {
@@ -473,7 +477,7 @@ impact_status_t impact_buffer_gather(impact_buffer_t *buf, int32_t B, const int3
     if (pl.has_worker) go(pl.worker, pl.stride_dist, dst->worker_dist, buf->W(), es);
     if (pl.has_target) go(pl.target, pl.stride_dist, dst->target_dist, buf->W(), es);
     if (pl.has_logp) go(pl.logp, pl.stride_lp, dst->logp, 4, 4);      // a pair of doubles, copied as four words
-    if (d.dist == IMPACT_CATEGORICAL) go(pl.actions, pl.stride_act, dst->actions, 1, 4);
+    if (d.dist == IMPACT_CATEGORICAL) go(pl.actions, pl.stride_act, dst->actions, 1, pl.act_bytes);
     else go(pl.actions, pl.stride_act, dst->actions, d.A, es);
     go(pl.rewards, pl.stride_rew, dst->rewards, 1, es);
     go(pl.dones, pl.stride_done, dst->dones, 1, 1);
@@ -508,6 +512,9 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
                                 size_t workspace_bytes, unsigned *done_count, hipStream_t s, bool check_only = false)
 {
     const bool slot_major = planes != nullptr;     // the batch fields are the buffer's planes, read in place
+    // one-byte action indices: the buffer's own storage variant, or what the caller says of a gathered batch
+    const bool act_u8 = slot_major ? planes->act_bytes == 1 : cfg && (cfg->flags & IMPACT_FLAG_ACTIONS_U8);
+    if (act_u8 && (dist != IMPACT_CATEGORICAL || A > 256)) return IMPACT_ERR_INVALID_ARG;
     if (dist != IMPACT_CATEGORICAL && dist != IMPACT_DIAG_GAUSSIAN) return IMPACT_ERR_INVALID_ARG;
     if (dtype != IMPACT_F32 && dtype != IMPACT_BF16) return IMPACT_ERR_INVALID_ARG;
     if (T < 1 || B < 1 || A < 1 || A > (1 << 20)) return IMPACT_ERR_INVALID_ARG;
@@ -538,6 +545,7 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     a.batch_major = (cfg->flags & IMPACT_FLAG_BATCH_MAJOR) ? 1 : 0;
     a.worker = cached ? nullptr : batch.worker_dist; a.target = batch.target_dist; a.actions = batch.actions;
     a.logp = batch.logp;
+    a.act_bytes = act_u8 ? 1 : 4;
     a.rewards = batch.rewards; a.dones = batch.dones;
     a.slots = dev_slots; a.num_slots = num_slots; a.slot_first = slot_first;
     a.gamma = cfg->gamma; a.lambda = cfg->lambda; a.rho_bar = cfg->rho_bar; a.c_bar = cfg->c_bar;

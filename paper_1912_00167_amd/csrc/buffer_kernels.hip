@@ -250,7 +250,8 @@ __global__ __launch_bounds__(256) void cache_logp(const LogpArgs a)
         const char *act_slot = (const char *)a.actions_plane + (size_t)(a.slot0 + s) * a.stride_act;
         double lp;
         if (DIST == IMPACT_CATEGORICAL) {
-            const int act = min(max(((const int *)act_slot)[t], 0), a.A - 1);   // (the loss flags an index out of range)
+            const int stored = a.act_bytes == 1 ? (int)((const uint8_t *)act_slot)[t] : ((const int *)act_slot)[t];
+            const int act = min(max(stored, 0), a.A - 1);   // (the loss flags an index out of range)
             float m = z[0];
             for (int k = 1; k < a.A; ++k) m = fmaxf(m, z[k]);
             double S = 0.0;

@@ -30,6 +30,7 @@ struct LossArgs {
     const void *worker;
     const void *target;
     const void *actions;
+    int act_bytes;            // categorical: the action index is an int32 (4) or one byte (1)
     const void *rewards;
     const uint8_t *dones;
     // cached log pi_worker(a), log pi_target(a): [T][B][2] or the buffer's plane [slot][T][2], or null.
@@ -95,6 +96,8 @@ bool launch_loss_cat_static(int dtype, bool slot_major, LossArgs &a, hipStream_t
 bool launch_loss_gauss_static(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 // ... on cached log-probabilities (a.logp; with the KL term if a.target is there)
 bool launch_loss_cat_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
+// ... for one-byte action indices (a.act_bytes == 1), all three forms
+bool launch_loss_cat_u8(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 bool launch_loss_gauss_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_reduce(const ReduceArgs &r, hipStream_t s);
@@ -131,6 +134,7 @@ struct LogpArgs {
     int dist, storage, T, n, A;
     int i0, slot0, cnt, which;
     size_t stride_act, stride_lp;    // bytes between slots
+    int act_bytes;                   // categorical: bytes of an action index in the plane (4 or 1)
 };
 void launch_cache_logp(const LogpArgs &a, hipStream_t s);
 

@@ -17,6 +17,7 @@ static bool launch_mode(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 
 bool launch_loss_cat_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s)
 {
+    if (a.act_bytes == 1) return launch_loss_cat_u8(dtype, slot_major, a, s);
     return a.target ? launch_mode<POLICY_CACHED_TARGET>(dtype, slot_major, a, s)
                     : launch_mode<POLICY_CACHED>(dtype, slot_major, a, s);
 }

@@ -94,7 +94,8 @@ __global__ __launch_bounds__(NTHREADS) void loss_generic(const LossArgs a)
             const bool done = a.dones[s_buf] != 0;
             double lw, lr1;      // log(pi_target / pi_worker), log(pi_theta / pi_target) at the action taken
             if (DIST == IMPACT_CATEGORICAL) {
-                act = ((const int *)act_slot)[SLOT ? (size_t)t : s_tm];
+                const size_t act_at = SLOT ? (size_t)t : s_tm;
+                act = a.act_bytes == 1 ? (int)((const uint8_t *)act_slot)[act_at] : ((const int *)act_slot)[act_at];
                 if (act < 0 || act >= A) { bad = 1.f; act = min(max(act, 0), A - 1); }
                 if (has_target) softmax_stats(zt, A, m_t, S_t);
                 softmax_stats(zl, A, m_l, S_l);

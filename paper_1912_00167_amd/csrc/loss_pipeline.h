@@ -6,6 +6,7 @@
 //                          is read for the KL term only, if it is kept at all)
 //   SIMD_WAVES             wavefronts per SIMD that the kernels' register use allows
 //   Kept                   registers that live from the behaviour pass to the learner pass
+//   Index                  categorical: the type of an action index in the batch (int32_t, or uint8_t)
 //   behaviour(...)         worker and target passes at the action taken: returns pi_target / pi_worker
 //   learner(...)           ratio, surrogate, entropy, KL and the gradients, written over the learner's
 //                          distribution parameters in LDS
@@ -69,6 +70,8 @@ void loss_static(const LossArgs a)
     constexpr int W = Policy::W;                   // elements of a distribution tensor per step
     constexpr int ACT = Policy::ACT;               // elements of the action tensor per step; 0: one int32 index
     constexpr int ACTR = ACT > 0 ? ACT : 1;
+    using Index = typename Policy::Index;          // ACT == 0: how the batch stores an action index
+    constexpr unsigned IB = (unsigned)sizeof(Index);
     constexpr int P = Policy::LANES;               // lanes that share a step
     constexpr int SPW = 64 / P;                    // steps per wavefront
     constexpr int RWP = SPW / NB;                  // time rows per wavefront
@@ -234,7 +237,7 @@ void loss_static(const LossArgs a)
             at[q] = j * T_PRELOAD + t;
             rv[q] = ((const ST *)a.rewards)[from];
             dv[q] = a.dones[from];
-            av[q] = ACT == 0 ? *(const int *)((const char *)a.actions + slot_act0[j] + 4u * (unsigned)t) : 0;
+            av[q] = ACT == 0 ? (int)*(const Index *)((const char *)a.actions + slot_act0[j] + IB * (unsigned)t) : 0;
         }
 #pragma unroll
         for (int q = 0; q < NPRE; ++q) {
@@ -286,8 +289,8 @@ void loss_static(const LossArgs a)
         if (!PRE) {
             nx_r = ((const ST *)a.rewards)[s_buf];
             nx_done = a.dones[s_buf];
-            if (ACT == 0) nx_act = SLOT ? *(const int *)((const char *)a.actions + my_act0 + 4u * (unsigned)tc)
-                                        : ((const int *)a.actions)[s_tm];
+            if (ACT == 0) nx_act = SLOT ? (int)*(const Index *)((const char *)a.actions + my_act0 + IB * (unsigned)tc)
+                                        : (int)((const Index *)a.actions)[s_tm];
         }
     };
     // full chunks: wave-uniform chunk address plus constant lane offsets, as for the tensors above
@@ -304,7 +307,7 @@ void loss_static(const LossArgs a)
             nx_r = *(const ST *)(uniform_ptr((const ST *)a.rewards + first_buf) + step_buf * (unsigned)sizeof(ST));
             nx_done = *(const uint8_t *)(uniform_ptr(a.dones + first_buf) + step_buf);
             if (ACT == 0)
-                nx_act = *(const int *)(uniform_ptr((const int *)a.actions + first_buf) + (SLOT ? my_act0 + 4u * (unsigned)rl : step_tm * 4u));
+                nx_act = (int)*(const Index *)(uniform_ptr((const Index *)a.actions + first_buf) + (SLOT ? my_act0 + IB * (unsigned)rl : step_tm * IB));
         }
     };
     float V_later = 0.f;      // PRE: the values of the chunk processed before this one (one chunk later in time)

@@ -18,8 +18,11 @@ namespace impact {
 // MODE: POLICY_FULL reads the worker's and the target's logits; the cached modes take log pi_worker(a)
 // and log pi_target(a) as stored by the buffer (lp[0], lp[1]) and read the target's logits, if they are
 // kept, for the KL term only.
-template <int A, int P, int MODE = POLICY_FULL>
+// IndexT: how the batch stores the index of the action taken (int32_t; uint8_t for the one-byte storage variant).
+template <int A, int P, int MODE = POLICY_FULL, typename IndexT = int32_t>
 struct CatPolicy {
+    using Index = IndexT;
+    static_assert(sizeof(IndexT) == 4 || A <= 256, "a one-byte index names at most 256 actions");
     static constexpr int W = A, ACT = 0, LANES = P;
     static constexpr bool CACHED = MODE != POLICY_FULL, TGT = MODE != POLICY_CACHED;
     static constexpr int SIMD_WAVES = 3;           // wavefronts per SIMD that the kernels' registers (<= 168) allow

@@ -19,6 +19,7 @@ namespace impact {
 // parameters, if they are kept, for the KL term only.
 template <int D, int P, int MODE = POLICY_FULL>
 struct GaussPolicy {
+    using Index = int32_t;                         // (no action index: the action is a vector of ACT elements)
     static constexpr int W = 2 * D, ACT = D, LANES = P;
     static constexpr bool CACHED = MODE != POLICY_FULL, TGT = MODE != POLICY_CACHED;
     static constexpr int SIMD_WAVES = D <= 3 ? 3 : 2;   // wavefronts per SIMD that the kernels' registers allow

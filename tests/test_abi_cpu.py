@@ -83,6 +83,19 @@ def test_storage_of_a_buffer_that_caches_log_probabilities(lib):
     assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == 0
 
 
+def test_storage_of_a_buffer_with_one_byte_action_indices(lib):
+    up = lambda x, a: (x + a - 1) // a * a
+    for T, A, N, storage in ((50, 18, 64, 0), (13, 256, 24, 1), (100, 6, 8, 0)):
+        es = 4 if storage == 0 else 2
+        planes = [N * up(T * A * es, 16)] * 2 + [N * up(T, 16), N * T * es, N * T]
+        d = B.impact_buffer_desc_t(0, T, A, N, 2, storage, B.IMPACT_BUFFER_ACTIONS_U8)
+        assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == sum(up(p + 16, 256) for p in planes) + 256
+    # an index of one byte names at most 256 actions, and a Gaussian policy's action is no index
+    for dist, A in ((0, 257), (1, 3)):
+        d = B.impact_buffer_desc_t(dist, 8, A, 16, 1, 0, B.IMPACT_BUFFER_ACTIONS_U8)
+        assert lib.impact_buffer_storage_bytes(ctypes.byref(d)) == 0
+
+
 def test_invalid_descriptors_and_arguments(lib):
     for kw in (dict(K=0), dict(N=0), dict(T=0), dict(A=0), dict(dist=2), dict(storage=3)):
         d = dict(dist=0, T=4, A=3, N=8, K=2, storage=0)

@@ -202,3 +202,28 @@ def test_gather_is_an_index_loop(dist, storage):
             else:
                 assert np.array_equal(w, oracle.quantize_bf16(src)[0])
             assert out["dones"][t, i] == x["dones"][t, s]
+
+
+def test_one_byte_action_indices_are_a_storage_variant_only():
+    """The records come back as they went in, as bytes; the variant exists for index actions of at most 256 values."""
+    import pytest
+    from oracle.buffer import BufferOracle
+    rng = np.random.default_rng(0)
+    T, A, n = 7, 256, 5
+    worker = rng.standard_normal((T, n, A)).astype(np.float32)
+    actions = rng.integers(0, A, (T, n)).astype(np.int32)
+    actions[0, 0], actions[1, 1] = 255, 0
+    rewards = rng.standard_normal((T, n)).astype(np.float32)
+    dones = (rng.random((T, n)) < 0.2).astype(np.uint8)
+    a, b = BufferOracle("categorical", T, A, 8, 2), BufferOracle("categorical", T, A, 8, 2, actions_u8=True)
+    sa = a.insert_records(worker, actions, rewards, dones, target=worker)
+    sb = b.insert_records(worker, actions, rewards, dones, target=worker)
+    assert sa == sb
+    ga, gb = a.gather(sa[::-1]), b.gather(sb[::-1])
+    assert ga["actions"].dtype == np.int32 and gb["actions"].dtype == np.uint8
+    np.testing.assert_array_equal(ga["actions"], gb["actions"].astype(np.int32))
+    np.testing.assert_array_equal(gb["actions"], actions[:, ::-1].astype(np.uint8))
+    with pytest.raises(ValueError):
+        BufferOracle("categorical", T, 257, 8, 2, actions_u8=True)
+    with pytest.raises(ValueError):
+        BufferOracle("gaussian", T, 3, 8, 2, actions_u8=True)
