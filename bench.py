@@ -57,14 +57,14 @@ def measured_traffic(workload: str):
     return entry[0] if entry and entry[1] == kernel_sources_digest() else None
 
 
-def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False) -> int:
+def algorithmic_bytes_per_step(wl, cached=None, learner_bf16=False, actions_u8=False) -> int:
     """Each input read once, each output written once (single pass), per (t, b) step.
     cached: None (both distributions in the batch), or "with_target" / "no_target": the buffer keeps
     log pi_worker(a), log pi_target(a) as two doubles in place of the worker's distribution (and of the
     target's, which only the KL term needs)."""
     es = 4 if wl.storage == "f32" else 2
     W = wl.A if wl.dist == workloads.CATEGORICAL else 2 * wl.A
-    action = 4 if wl.dist == workloads.CATEGORICAL else wl.A * es
+    action = (1 if actions_u8 else 4) if wl.dist == workloads.CATEGORICAL else wl.A * es
     behaviour = {None: 2 * W * es, "with_target": 16 + W * es, "no_target": 16}[cached]
     reads = (2 if learner_bf16 else 4) * W + behaviour + action + es + 1 + 4      # learner, behaviour side, action, reward, done, value
     writes = 4 * W + 12                                  # gradient of the distribution, of the value, vs, adv
@@ -92,6 +92,8 @@ def fill_ring(torch, binding, wl, buf, block: int):
         cur = dict(learner=[], values=[], bootstrap=[])
         for i, x in enumerate(parts):
             d = {k: torch.from_numpy(v).cuda() for k, v in x.items()}
+            if wl.dist == workloads.CATEGORICAL:                # (a buffer may keep action indices as bytes)
+                d["actions"] = d["actions"].to(buf.action_dtype)
             slots = binding.impact_buffer_insert(buf, d)
             first = (q * per_batch + i) * block
             assert slots[0] == first and slots[-1] == first + block - 1
@@ -317,6 +319,18 @@ def table(torch, binding, names, repeats: int = 5) -> None:
         print(f"| {wl.name} | fused, cached log pi(a) pair ({bps} B/step; target distribution {what}) | {t_c:.1f} | "
               f"{steps / t_c * 1e6:.3e} | {gbs:.0f} | {gbs / 80:.1f} | {clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
         buf.close()
+        if wl.dist == workloads.CATEGORICAL and wl.A <= 256:
+            # the same step on a buffer that keeps the index of the action taken as one byte (a storage variant)
+            buf = binding.Buffer(wl.dist, T, wl.A, wl.num_slots, wl.K, wl.storage, flags=binding.IMPACT_BUFFER_ACTIONS_U8)
+            del learner, values, boot
+            learner, values, boot = fill_ring(torch, binding, wl, buf, min(B, 4096))
+            t_u = timed(lambda i: binding.impact_loss_fwd_bwd_from_buffer(buf, slots[i % nq], learner[i % nq], values[i % nq],
+                                                                          boot[i % nq], cfg, out=outs2[i % 2], workspace=ws), n_calls)
+            bps = algorithmic_bytes_per_step(wl, actions_u8=True)
+            gbs = bps * steps / t_u / 1e3
+            print(f"| {wl.name} | fused, action indices as bytes ({bps} B/step) | {t_u:.1f} | {steps / t_u * 1e6:.3e} | "
+                  f"{gbs:.0f} | {gbs / 80:.1f} | {clip * 100:.1f} % | {trunc * 100:.1f} % |", flush=True)
+            buf.close()
         del learner, values, boot, out, outs2
         gc.collect()
     gc.enable()

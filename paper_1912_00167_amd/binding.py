@@ -179,6 +179,20 @@ def _ptr(t: Optional[torch.Tensor]):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _expect(name: str, t: Optional[torch.Tensor], dtype, shape, optional: bool = False) -> None:
+    """The C side sees addresses only: a tensor of another element type or shape than the call reads or
+    writes would send a kernel outside the allocation, so that is refused here."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name}: missing")
+    if t.dtype is not dtype and (not isinstance(dtype, tuple) or t.dtype not in dtype):
+        want = " or ".join(str(d) for d in dtype) if isinstance(dtype, tuple) else str(dtype)
+        raise TypeError(f"{name}: expected {want}, got {t.dtype}")
+    if t.shape != shape:                               # (torch.Size compares equal to a tuple of the same numbers)
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+
+
 def _stream(stream) -> ctypes.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -247,7 +261,10 @@ class Buffer:
         nbytes = int(load().impact_buffer_storage_bytes(ctypes.byref(self.desc)))
         if nbytes == 0:
             raise ImpactError(IMPACT_ERR_INVALID_ARG, "impact_buffer_storage_bytes")
-        self.storage = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+        # (the library wants its storage on a 256-byte boundary; device allocations are, host ones may not be)
+        self._raw = torch.zeros(nbytes + 255, dtype=torch.uint8, device=device)
+        skip = -self._raw.data_ptr() % 256
+        self.storage = self._raw[skip: skip + nbytes]
         self.handle = ctypes.c_void_p()
         _check(load().impact_buffer_create(ctypes.byref(self.desc), _ptr(self.storage), nbytes,
                                            ctypes.byref(self.handle)), "impact_buffer_create")
@@ -340,8 +357,15 @@ def impact_buffer_reserve(buf: Buffer, n: int) -> np.ndarray:
 def impact_buffer_insert(buf: Buffer, src: Dict[str, torch.Tensor], stream=None) -> np.ndarray:
     """src: time-major fp32 device tensors worker/actions/rewards/dones (+ optional target)."""
     n = int(src["worker"].shape[1])
-    if buf.dist == IMPACT_CATEGORICAL and src["actions"].dtype != buf.action_dtype:
-        raise TypeError(f"actions: expected {buf.action_dtype}, got {src['actions'].dtype}")
+    T, f32 = buf.T, torch.float32
+    _expect("worker", src.get("worker"), f32, (T, n, buf.W))
+    _expect("target", src.get("target"), f32, (T, n, buf.W), optional=True)
+    if buf.dist == IMPACT_CATEGORICAL:
+        _expect("actions", src.get("actions"), buf.action_dtype, (T, n))
+    else:
+        _expect("actions", src.get("actions"), f32, (T, n, buf.A))
+    _expect("rewards", src.get("rewards"), f32, (T, n))
+    _expect("dones", src.get("dones"), torch.uint8, (T, n))
     slots = np.empty(n, dtype=np.int32)
     b = _batch_struct(src, need_target=False)
     _check(load().impact_buffer_insert(buf.handle, n, ctypes.byref(b), slots.ctypes.data_as(ctypes.c_void_p),
@@ -351,6 +375,7 @@ def impact_buffer_insert(buf: Buffer, src: Dict[str, torch.Tensor], stream=None)
 
 def impact_buffer_put_target(buf: Buffer, slots: np.ndarray, target: torch.Tensor, stream=None) -> None:
     slots = np.ascontiguousarray(slots, dtype=np.int32)
+    _expect("target", target, torch.float32, (buf.T, slots.size, buf.W))
     _check(load().impact_buffer_put_target(buf.handle, slots.size, slots.ctypes.data_as(ctypes.c_void_p),
                                            _ptr(target), _stream(stream)), "impact_buffer_put_target")
 
@@ -382,11 +407,53 @@ def alloc_batch(buf: Buffer, B: int) -> Dict[str, torch.Tensor]:
     return out
 
 
+def _expect_batch(dist: int, fdt, idt, T: int, B: int, A: int, batch: Dict[str, torch.Tensor], gather_from=None) -> None:
+    """Element types and shapes of the buffer-resident part of a time-major batch (fdt: its float type; idt: the
+    type of a categorical action index).  gather_from: the buffer whose planes a gather fills it from."""
+    W = A if dist == IMPACT_CATEGORICAL else 2 * A
+    if gather_from is not None:
+        need_worker = not gather_from.flags & IMPACT_BUFFER_CACHE_LOGP
+        need_target = not gather_from.flags & IMPACT_BUFFER_NO_TARGET_DIST
+        need_logp = bool(gather_from.flags & IMPACT_BUFFER_CACHE_LOGP)
+    else:
+        need_logp = batch.get("logp") is not None
+        need_worker, need_target = not need_logp, not need_logp
+    _expect("worker", batch.get("worker"), fdt, (T, B, W), optional=not need_worker)
+    _expect("target", batch.get("target"), fdt, (T, B, W), optional=not need_target)
+    _expect("logp", batch.get("logp"), torch.float64, (T, B, 2), optional=not need_logp)
+    if dist == IMPACT_CATEGORICAL:
+        _expect("actions", batch.get("actions"), idt, (T, B))
+    else:
+        _expect("actions", batch.get("actions"), fdt, (T, B, A))
+    _expect("rewards", batch.get("rewards"), fdt, (T, B))
+    _expect("dones", batch.get("dones"), torch.uint8, (T, B))
+
+
+def _expect_learner_side(T: int, B: int, W: int, learner, values, bootstrap, cfg, out) -> None:
+    bm = bool(cfg.flags & IMPACT_FLAG_BATCH_MAJOR)
+    tb = (B, T) if bm else (T, B)
+    _expect("learner", learner, (torch.float32, torch.bfloat16), tb + (W,))
+    _expect("values", values, torch.float32, tb)
+    _expect("bootstrap", bootstrap, torch.float32, (B,))
+    f32 = torch.float32
+    _expect("grad_dist", out.get("grad_dist"), f32, tb + (W,))
+    _expect("loss5", out.get("loss5"), f32, (5,))
+    _expect("fractions", out.get("fractions"), f32, (2,), optional=True)
+    if out.get("step_outputs") is not None:
+        _expect("step_outputs", out["step_outputs"], f32, tb + (4,))
+    else:
+        _expect("grad_values", out.get("grad_values"), f32, tb)
+        _expect("vs", out.get("vs"), f32, tb, optional=True)
+        _expect("adv", out.get("adv"), f32, tb, optional=True)
+
+
 def impact_buffer_gather(buf: Buffer, dev_slots: torch.Tensor, dst: Optional[Dict[str, torch.Tensor]] = None,
                          stream=None) -> Dict[str, torch.Tensor]:
     B = int(dev_slots.numel())
     if dst is None:
         dst = alloc_batch(buf, B)
+    _expect("slots", dev_slots, torch.int32, (B,))
+    _expect_batch(buf.dist, buf.float_dtype, buf.action_dtype, buf.T, B, buf.A, dst, gather_from=buf)
     b = _batch_struct(dst)
     _check(load().impact_buffer_gather(buf.handle, B, _ptr(dev_slots), ctypes.byref(b), _stream(stream)),
            "impact_buffer_gather")
@@ -446,6 +513,8 @@ def impact_loss_fwd_bwd(dist, learner: torch.Tensor, values: torch.Tensor, boots
         out = alloc_loss_out(*((B, T, W) if cfg.flags & IMPACT_FLAG_BATCH_MAJOR else (T, B, W)), learner.device)
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(d, T, B, A), dtype=torch.uint8, device=learner.device)
+    _expect_learner_side(T, B, W, learner, values, bootstrap, cfg, out)
+    _expect_batch(d, batch["rewards"].dtype, torch.uint8 if cfg.flags & IMPACT_FLAG_ACTIONS_U8 else torch.int32, T, B, A, batch)
     b, o = _batch_struct(batch), _out_struct(out)
     cfg = _cfg_for(cfg, learner)
     _check(load().impact_loss_fwd_bwd(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
@@ -461,6 +530,8 @@ def impact_loss_fwd_bwd_static(dist, learner: torch.Tensor, values: torch.Tensor
     d = dist_code(dist)
     T, B, W = _tbw(learner, cfg)
     A = W if d == IMPACT_CATEGORICAL else W // 2
+    _expect_learner_side(T, B, W, learner, values, bootstrap, cfg, out)
+    _expect_batch(d, batch["rewards"].dtype, torch.uint8 if cfg.flags & IMPACT_FLAG_ACTIONS_U8 else torch.int32, T, B, A, batch)
     b, o = _batch_struct(batch), _out_struct(out)
     cfg = _cfg_for(cfg, learner)
     _check(load().impact_loss_fwd_bwd_static(d, dtype_code(batch["rewards"].dtype), T, B, A, _ptr(learner), _ptr(values),
@@ -479,6 +550,10 @@ def impact_loss_fwd_bwd_from_buffer(buf: Buffer, dev_slots: torch.Tensor, learne
     if workspace is None:
         workspace = torch.empty(impact_loss_workspace_bytes(buf.dist, T, B, buf.A), dtype=torch.uint8,
                                 device=learner.device)
+    if W != buf.W or T != buf.T:
+        raise ValueError(f"learner: a buffer of trajectories [{buf.T}][.][{buf.W}] cannot serve a batch [{T}][{B}][{W}]")
+    _expect("slots", dev_slots, torch.int32, (B,))
+    _expect_learner_side(T, B, W, learner, values, bootstrap, cfg, out)
     o = _out_struct(out)
     cfg = _cfg_for(cfg, learner)
     _check(load().impact_loss_fwd_bwd_from_buffer(buf.handle, B, _ptr(dev_slots), _ptr(learner), _ptr(values),

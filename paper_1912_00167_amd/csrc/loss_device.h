@@ -452,9 +452,10 @@ __device__ __forceinline__ void add_tile_block(const float *partials, int i0, in
     }
 }
 
-// The five loss terms from the tiles' partial sums, by one wavefront and in an order that depends on
-// nothing but the number of tiles: lane l adds tiles l, l + 64, ... in fp64, then the lanes combine.
-// An invalid index anywhere in the batch (flagged in the fifth partial) turns all five into NaN.
+// The five loss terms, and the shares of clipped and of truncated steps, from the workgroups' partial sums, by
+// one wavefront and in an order that depends on nothing but their number: lane l adds sets l, l + 64, ... in
+// fp64, then the lanes combine.  An invalid index anywhere in the batch (flagged in the fifth partial) turns
+// the five loss terms into NaN.
 // The wavefront that runs this is the last one at work on the chip, so every memory latency here is
 // exposed: the loads go out in blocks as large as the registers hold.
 // Blocks of 16 tiles per lane (8 registers each); with tile groups a launch leaves a few hundred sets of sums,
