@@ -16,7 +16,9 @@ SOURCES = ["api.cpp", "loss_cat.hip", "loss_cat_cached.hip", "loss_cat_u8.hip", 
            "loss_generic.hip", "buffer_kernels.hip", "static_workspace.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall"]
-DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# (-Wno-pass-failed: where a workgroup's LDS already bounds the occupancy below what a kernel asks for in
+# registers, the compiler says so for every such instantiation)
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-pass-failed"]
 
 
 def _compile(src: str) -> str:

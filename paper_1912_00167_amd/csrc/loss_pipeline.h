@@ -60,7 +60,7 @@ constexpr int lds_bytes_of_loss_static(int G)
 //     serves the older wavefront first, the pair ends 8 us apart and the compute units' last wavefronts
 //     set the kernel's end; with the hand-over the pair ends together.
 template <class Policy, typename ST, typename LT, bool SLOT, int NW, int G = 1>
-__global__ __launch_bounds__(64 * NW * G) __attribute__((amdgpu_waves_per_eu(2)))   // two wavefronts per SIMD, at least
+__global__ __launch_bounds__(64 * NW * G) __attribute__((amdgpu_waves_per_eu(Policy::SIMD_WAVES)))   // the occupancy the launcher's sizing assumes, at least
 void loss_static(const LossArgs a)
 {
     static_assert(G == 1 || NW == 1, "only single-wavefront tiles share a workgroup");
