@@ -294,8 +294,14 @@ impact_status_t impact_buffer_import_state(impact_buffer_t *buf, const void *hos
         h.num_slots != d.num_slots || h.K != d.K || h.storage != d.storage || h.flags != d.flags)
         return IMPACT_ERR_INVALID_ARG;
     if (h.w < 0 || h.w >= d.num_slots || h.r < 0 || h.r >= d.num_slots || h.t < 0) return IMPACT_ERR_INVALID_ARG;
-    std::vector<int32_t> count(d.num_slots);
-    std::vector<uint8_t> has_target(d.num_slots);
+    std::vector<int32_t> count;
+    std::vector<uint8_t> has_target;
+    try {
+        count.resize((size_t)d.num_slots);
+        has_target.resize((size_t)d.num_slots);
+    } catch (...) {                                // (no exception may cross the C boundary)
+        return IMPACT_ERR_INVALID_ARG;
+    }
     std::memcpy(count.data(), src + sizeof h, count.size() * sizeof(int32_t));
     std::memcpy(has_target.data(), src + sizeof h + count.size() * sizeof(int32_t), has_target.size());
     int32_t live = 0, empty = 0;
