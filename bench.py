@@ -353,7 +353,7 @@ def main() -> int:
     ap.add_argument("--no-variants", action="store_true",
                     help="time the headline configuration only (for profiler runs: one kind of launch in the trace)")
     ap.add_argument("--event-every", type=int, default=4, choices=(1, 2, 4, 8, 16),
-                    help="bracket every N-th launch with a pair of HIP events (default 4)")
+                    help="in the bracketed phase that follows the timed region: a pair of HIP events around every N-th launch (default 4)")
     ap.add_argument("--series", metavar="FILE", help="also write the bracketed launches' durations (step, ms, ...; one per line) to FILE")
     ap.add_argument("--table", action="store_true",
                     help="instead of the JSON line: a markdown table of all workloads (loss, gather, fused)")
@@ -392,48 +392,65 @@ def main() -> int:
     pinned = [torch.empty(B, dtype=torch.int32).pin_memory() for _ in range(depth)]
     pinned_np = [p.numpy() for p in pinned]
     counts_np = np.empty(B, dtype=np.int32)
-    # One pair of HIP events per staging buffer, around the launch on the stream it goes to; a pair is
-    # read and recorded again when its buffer comes round (a fresh pair per step would leave hundreds of
-    # unread events behind, and recording then slows down).
+    # A staging buffer is free again once the launch that read it has finished: the stream gets one marker event
+    # per `mark_every` launches (two in rotation), and a step waits for the marker that covers the launch which
+    # last used its buffer (16 steps back, so that marker was recorded at least 9 launches ago).
+    mark_every = 8
+    marks = [torch.cuda.Event() for _ in range(depth // mark_every)]
+    # The bracketed phase (after the timed region): a pair of timing events around every `every`-th launch, one
+    # pair per staging buffer.  The two records between back-to-back launches cost the stream about 2.5 us each,
+    # which is why the timed region carries none.
     pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(depth)]
+    every = args.event_every
+    assert depth % every == 0 and depth % mark_every == 0
     in_flight = [0] * depth                        # 1 + the step that holds the buffer
+    bracketed = [False] * depth
     kept_steps = []
     state = dict(step=0, outs=outs)
     kernel_times = []
-    host_marks = []                                # host clock before and after each step's records and launch
+    host_marks = {}                                # step -> host clock before and after its records and launch
 
-    # Only every `every`-th launch is bracketed: the two records between back-to-back launches cost the
-    # stream about 5 us per step (217 us per step against 211 with every fourth launch bracketed), which
-    # would be charged to the throughput; the sampled launches give the kernel's average duration.
-    every = args.event_every if args.steps >= args.event_every else 1
-    assert depth % every == 0
-
-    def retire(j, keep):
+    def retire(j):
         if in_flight[j]:
-            jj = (j + every - 1) // every * every % depth      # the first bracketed launch at or after this one
-            pairs[jj][1].synchronize()             # the kernel has read pinned[j]: the staging buffer is free again
-            if keep and j % every == 0:
+            m = in_flight[j] - 1
+            marks[(m // mark_every) % len(marks)].synchronize()    # the kernel has read pinned[j]: the buffer is free again
+            if bracketed[j]:
                 kernel_times.append(pairs[j][0].elapsed_time(pairs[j][1]))
-                kept_steps.append(in_flight[j] - 1)
+                kept_steps.append(m)
+                bracketed[j] = False
             in_flight[j] = 0
 
-    def one_step(timed):
+    def drain():
+        """Wait for everything issued; collect the bracketed launches' times."""
+        torch.cuda.synchronize()
+        for j in range(depth):
+            if bracketed[j]:
+                kernel_times.append(pairs[j][0].elapsed_time(pairs[j][1]))
+                kept_steps.append(in_flight[j] - 1)
+                bracketed[j] = False
+            in_flight[j] = 0
+
+    def one_step(bracket=False):
         i = state["step"]
         j = i % depth
-        retire(j, timed)
+        retire(j)
         if binding.impact_buffer_num_live(buf) < B:
             refill(binding, buf)
         binding.impact_buffer_sample(buf, B, pinned_np[j], counts_np)
         q = int(pinned_np[j][0]) // B              # ring order: batch q holds slots [qB, (q+1)B)
-        host_marks.append(time.perf_counter())
-        if j % every == 0:
+        t_host = time.perf_counter()
+        bracket = bracket and j % every == 0
+        if bracket:
             pairs[j][0].record(stream)
         binding.impact_loss_fwd_bwd_from_buffer(buf, pinned[j], learner[q % n_batches], values[q % n_batches],
                                                 boot[q % n_batches], cfg, out=state["outs"][i % 2], workspace=workspace,
                                                 stream=stream)
-        if j % every == 0:
+        if bracket:
             pairs[j][1].record(stream)
-        host_marks.append(time.perf_counter())
+            bracketed[j] = True
+        if i % mark_every == mark_every - 1:
+            marks[(i // mark_every) % len(marks)].record(stream)
+        host_marks[i] = (t_host, time.perf_counter())
         in_flight[j] = i + 1
         state["step"] = i + 1
 
@@ -446,23 +463,34 @@ def main() -> int:
     settle_steps = 0
     t_settle = time.perf_counter()
     while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms or settle_steps < depth:
-        one_step(False)
+        one_step()
         settle_steps += 1
     for _ in range(args.warmup):
-        one_step(False)
-    for j in range(depth):
-        retire(j, False)
-    torch.cuda.synchronize()
+        one_step()
+    drain()
 
+    # The timed region: K steps between two events on the launch stream (the kernel's average duration per
+    # launch, dispatch included, is their distance over K) and between two readings of the host clock.
+    region = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
     t0 = time.perf_counter()
+    region[0].record(stream)
     for k in range(args.steps):
-        one_step(True)
+        one_step()
+    region[1].record(stream)
     issued = time.perf_counter() - t0              # host side done; the device may still be working
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    for j in range(depth):
-        retire(j, True)
-    assert len(kernel_times) == len(kept_steps) >= args.steps // every
+    drain()
+    kernel_ms = region[0].elapsed_time(region[1]) / args.steps
+
+    # The bracketed phase: the same steps with a pair of events around every `every`-th launch, for the
+    # launch-by-launch series and as a cross-check of the figure above (it runs a little higher: the records
+    # themselves take stream time).
+    n_br = max(every, min(args.steps, 128) // every * every)
+    for _ in range(n_br):
+        one_step(bracket=True)
+    drain()
+    assert len(kernel_times) == len(kept_steps) == n_br // every
     main_times, main_steps = list(kernel_times), list(kept_steps)
 
     # The same step with the per-step scalars written as packed records (a layout variant of the outputs,
@@ -472,18 +500,16 @@ def main() -> int:
         state["outs"] = [binding.alloc_loss_out(T, B, W, packed=True) for _ in range(2)]
         n_var = min(args.steps, 256)
         for _ in range(32):
-            one_step(False)
-        for j in range(depth):
-            retire(j, False)
-        del kernel_times[:]
+            one_step()
+        drain()
+        ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        ev[0].record(stream)
         for _ in range(n_var):
-            one_step(True)
-        torch.cuda.synchronize()
-        for j in range(depth):
-            retire(j, True)
-        variant = float(np.mean(kernel_times))
+            one_step()
+        ev[1].record(stream)
+        drain()
+        variant = ev[0].elapsed_time(ev[1]) / n_var
         state["outs"] = outs
-    kernel_times = main_times
 
     # Successive steps alternating between two streams (a lane of the buffer's completion counters, a
     # workspace and output tensors each): one launch starts while the other drains.  Whole-step throughput
@@ -537,32 +563,29 @@ def main() -> int:
             perms.append((perm.pin_memory(), learner[q].index_select(1, order).contiguous(),
                           values[q].index_select(1, order).contiguous(), boot[q].index_select(0, order).contiguous()))
         torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_var // 4)]
+        ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
         for i in range(32 + n_var):
             sl, ln, va, bo = perms[i % n_batches]
-            k = i - 32
-            if k >= 0 and k % 4 == 0:
-                ev[k // 4][0].record(stream)
+            if i == 32:
+                ev[0].record(stream)
             binding.impact_loss_fwd_bwd_from_buffer(buf, sl, ln, va, bo, cfg, out=outs[i % 2], workspace=workspace, stream=stream)
-            if k >= 0 and k % 4 == 0:
-                ev[k // 4][1].record(stream)
+        ev[1].record(stream)
         torch.cuda.synchronize()
-        sc_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        sc_ms = ev[0].elapsed_time(ev[1]) / n_var
         scattered = {"kernel_ms": sc_ms, "frac": algorithmic_bytes_per_step(wl) * T * B / (sc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                      "what": "the batch's slots scattered over a quarter of the ring (shuffled), index array in page-locked "
-                             "host memory read by the kernel; HIP events around every fourth launch"}
+                             "host memory read by the kernel; two HIP events around the launches, their distance per launch"}
         del perms
     copy_ceiling = device_copy_ceiling(torch)
     gc.enable()
     if args.series:
         with open(args.series, "w") as f:
-            for x, k in zip(kernel_times, main_steps):     # step, kernel ms, host ms in the launch, host ms since the previous launch
-                since = (host_marks[2 * k] - host_marks[2 * k - 1]) * 1e3 if k else 0.0
-                f.write(f"{k} {x:.4f} {(host_marks[2 * k + 1] - host_marks[2 * k]) * 1e3:.4f} {since:.4f}\n")
+            for x, k in zip(main_times, main_steps):       # step, kernel ms, host ms in the launch, host ms since the previous launch
+                since = (host_marks[k][0] - host_marks[k - 1][1]) * 1e3 if k - 1 in host_marks else 0.0
+                f.write(f"{k} {x:.4f} {(host_marks[k][1] - host_marks[k][0]) * 1e3:.4f} {since:.4f}\n")
 
     loss = outs[(args.warmup + args.steps - 1) % 2]["loss5"].cpu().numpy()
     assert np.all(np.isfinite(loss)), f"non-finite loss {loss}"
-    kernel_ms = float(np.mean(kernel_times))
     steps_per_call = T * B
     ms_per_step = wall * 1e3 / args.steps
     bytes_per_call = algorithmic_bytes_per_step(wl) * steps_per_call
@@ -587,7 +610,8 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None if args.packed_outputs else measured_traffic(args.workload),
                      "kernel_ms": kernel_ms, "kernel": "fused loss kernel (the last workgroup sums the loss terms)",
-                     "kernel_launches_timed": len(kernel_times),
+                     "kernel_launches_timed": args.steps,
+                     "kernel_ms_bracketed": float(np.mean(main_times)), "kernel_launches_bracketed": len(main_times),
                      "device_copy_ceiling_GBps": copy_ceiling,
                      "frac_of_copy_ceiling": achieved / copy_ceiling},
     }
