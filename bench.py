@@ -341,11 +341,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=128)
-    # After idle the chip runs its first ~12 ms of sustained load with launches up to 20 % longer than in the
+    # After idle the chip runs its first 12-30 ms of sustained load with launches up to 35 % longer than in the
     # steady state that follows (kernel trace in profiles/).  Whatever --warmup says, the run therefore starts
     # with an untimed settle phase of this many steps of the same fused launch (reported as config.settle_steps).
-    ap.add_argument("--settle-ms", type=float, default=40.0,
-                    help="untimed settle phase before the warm-up: at least this much device time of fused steps (default 40)")
+    ap.add_argument("--settle-ms", type=float, default=100.0,
+                    help="untimed settle phase before the warm-up: at least this much device time of fused steps (default 100)")
     ap.add_argument("--workload", default="C5", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--packed-outputs", action="store_true",
@@ -430,7 +430,8 @@ def main() -> int:
                 bracketed[j] = False
             in_flight[j] = 0
 
-    def one_step(bracket=False):
+    def one_step(bracket=False, mark=None):
+        """mark: an event to record on the stream right before this step's launch."""
         i = state["step"]
         j = i % depth
         retire(j)
@@ -440,6 +441,8 @@ def main() -> int:
         q = int(pinned_np[j][0]) // B              # ring order: batch q holds slots [qB, (q+1)B)
         t_host = time.perf_counter()
         bracket = bracket and j % every == 0
+        if mark is not None:
+            mark.record(stream)
         if bracket:
             pairs[j][0].record(stream)
         binding.impact_loss_fwd_bwd_from_buffer(buf, pinned[j], learner[q % n_batches], values[q % n_batches],
@@ -469,13 +472,13 @@ def main() -> int:
         one_step()
     drain()
 
-    # The timed region: K steps between two events on the launch stream (the kernel's average duration per
-    # launch, dispatch included, is their distance over K) and between two readings of the host clock.
+    # The timed region: K steps between two readings of the host clock, and their K launches between two events
+    # on the launch stream (the kernel's average duration per launch, dispatch included, is their distance over K;
+    # the first is recorded right before the first launch: the device is idle while the host samples for it).
     region = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
     t0 = time.perf_counter()
-    region[0].record(stream)
     for k in range(args.steps):
-        one_step()
+        one_step(mark=region[0] if k == 0 else None)
     region[1].record(stream)
     issued = time.perf_counter() - t0              # host side done; the device may still be working
     torch.cuda.synchronize()
