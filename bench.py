@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, AMD's published peak
 # is tied to the kernel sources it was taken on (kernel_sources_digest below): once any of them changes, the
 # benchmark reports null until the counters are taken again.
 MEASURED_TRAFFIC = {       # workload -> (bytes per launch, digest of the kernel sources at that time)
-    "C5": (2.0 * 346376 * 1024 + 310750 * 1024, "149be1ba5e349676"),     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
-    "C4": (2.0 * 97579 * 1024 + 69757 * 1024, "149be1ba5e349676"),
+    "C5": (2.0 * 345216 * 1024 + 311039 * 1024, "85a392199a80d103"),     # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch
+    "C4": (2.0 * 97612 * 1024 + 69751 * 1024, "85a392199a80d103"),
 }
 
 

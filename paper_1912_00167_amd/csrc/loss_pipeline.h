@@ -116,7 +116,11 @@ void loss_static(const LossArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wreg = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront of the workgroup: selects the staging regions
     const int wave = G > 1 ? 0 : wreg;             // wavefront of the tile: selects its share of a chunk's rows
-    const int grp = G > 1 ? wreg : 0;              // tile of the workgroup
+    // Tile of the workgroup.  Of eight wavefronts, w and w + 4 normally share a SIMD (placement is round-robin) and
+    // are kept in step by the hand-over below: they take neighbouring tiles, whose learner and gradient row
+    // segments meet in one 128-byte line (a tile's row of 8 x W floats need not end on a line boundary), so that
+    // the line is fetched once and written once.  (Any one-to-one assignment is correct.)
+    const int grp = G == 8 ? (((wreg & 3) << 1) | (wreg >> 2)) : G > 1 ? wreg : 0;
     int *slot_row0 = slot_row0_all[grp];
     unsigned *slot_dist0 = slot_dist0_all[grp], *slot_act0 = slot_act0_all[grp], *slot_lp0 = slot_lp0_all[grp];
     ST *pre_r = pre_r_all[grp];
