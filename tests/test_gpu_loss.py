@@ -41,6 +41,7 @@ RAGGED = [
     ("gaussian", 96, 16, 3), ("gaussian", 50, 8, 6),
     # many actions / dimensions: no specialised kernel
     ("categorical", 6, 16, 300), ("gaussian", 5, 8, 40),
+    ("categorical", 3, 4, 20000), ("gaussian", 2, 3, 5000),     # ... thousands of them
     # batches that end in a ragged tile of the specialised kernels (rows and ragged segment whole 16-byte vectors)
     ("categorical", 50, 10, 18), ("categorical", 21, 500, 18), ("categorical", 9, 4, 4), ("categorical", 30, 20, 6),
     ("gaussian", 40, 12, 6), ("gaussian", 19, 36, 17), ("gaussian", 5, 2, 6), ("gaussian", 70, 100, 3),
