@@ -344,7 +344,11 @@ size_t impact_loss_workspace_bytes(int32_t dist, int32_t T, int32_t B, int32_t A
  * Errors: INVALID_ARG (NULL or misaligned pointers, T,B,A < 1, non-finite gamma/lambda/
  * coefficients, negative truncation levels, rho_clip < 1, eps < 0), HIP.
  * A categorical action outside [0, A) is clamped for addressing and turns all
- * five losses into NaN. */
+ * five losses into NaN.
+ * Calls that may be on the device together need a workspace and outputs each and must go to different
+ * streams: the calls of one stream share a completion counter inside the library (one per stream, for up
+ * to 64 streams per device), with which the kernel's last workgroup sums the loss terms.  Beyond that
+ * number, and while the stream is being captured into a graph, the sum runs as a second small launch. */
 impact_status_t impact_loss_fwd_bwd(int32_t dist, int32_t batch_dtype, int32_t T, int32_t B, int32_t A,
                                     const void *learner_dist, const float *values, const float *bootstrap,
                                     const impact_batch_t *batch, const impact_loss_config_t *cfg,

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libimpact.so")
 
 SOURCES = ["api.cpp", "loss_cat.hip", "loss_cat_cached.hip", "loss_cat_u8.hip", "loss_gauss.hip", "loss_gauss_cached.hip",
-           "loss_generic.hip", "buffer_kernels.hip", "static_workspace.hip"]
+           "loss_generic.hip", "buffer_kernels.hip", "static_workspace.hip", "stream_counters.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall"]
 # (-Wno-pass-failed: where a workgroup's LDS already bounds the occupancy below what a kernel asks for in

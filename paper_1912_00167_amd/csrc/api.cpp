@@ -542,6 +542,8 @@ static impact_status_t run_loss(int dist, int dtype, const Planes *planes, int T
     if ((out->vs && !aligned16(out->vs)) || (out->adv && !aligned16(out->adv))) return IMPACT_ERR_INVALID_ARG;
     if ((double)T * B * (2.0 * A) > 1.0e12) return IMPACT_ERR_INVALID_ARG;
     if (check_only) return IMPACT_OK;              // every argument check is above this line, every HIP call below
+    // a call without a buffer handle takes its completion counter from the library's per-stream table, if it can
+    if (!done_count && !slot_major) done_count = done_counter_of_stream(s);
 
     LossArgs a;
     std::memset(&a, 0, sizeof(a));

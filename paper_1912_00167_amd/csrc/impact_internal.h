@@ -101,6 +101,9 @@ bool launch_loss_cat_u8(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 bool launch_loss_gauss_cached(int dtype, bool slot_major, LossArgs &a, hipStream_t s);
 void launch_loss_generic(int dist, int dtype, bool slot_major, const LossArgs &a, hipStream_t s);
 void launch_reduce(const ReduceArgs &r, hipStream_t s);
+// A completion counter (zero between launches) for a loss call on this stream that has no buffer handle, or null
+// (stream_counters.hip): with one, the kernel's last workgroup sums the loss terms and no second launch follows.
+unsigned *done_counter_of_stream(hipStream_t s);
 void launch_zero_words(unsigned *p, int n, hipStream_t s);
 
 // Buffer data movement.  A "run" is cnt consecutive slots starting at slot0 that take

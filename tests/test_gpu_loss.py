@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import workloads
-from gpu_common import check_against_oracle, gpu_loss, say, shape_workload, wide_range_inputs
+from gpu_common import check_against_oracle, gpu_loss, say, shape_workload, to_device, wide_range_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -281,3 +281,83 @@ def test_batch_major_learner_tensors(env, name, kw, packed):
     tm = gpu_loss(torch, binding, wl, x, flags=FORCE_GENERIC)          # the same kernels on time-major tensors
     for k in got:
         np.testing.assert_array_equal(got[k], tm[k], err_msg=k)
+
+
+def test_calls_without_a_buffer_on_one_and_on_two_streams(env):
+    """impact_loss_fwd_bwd takes its completion counter from the library's per-stream table: calls in a row on one
+    stream, and calls that overlap on two streams (a workspace and outputs each), must give the same bits as a call
+    on its own, every time."""
+    torch, binding = env
+    for name, kw in (("C2", dict(T=50, B=512)), ("C5", dict(T=40, B=2048, storage="f32")), ("C3", dict(T=700, B=24))):
+        wl = shape_workload(workloads.WORKLOADS[name], **kw)
+        say(f"case time-major calls on one and two streams {name} {kw}")
+        xs = [workloads.make_batch(wl, stream=60 + i) for i in range(2)]
+        ds = [to_device(x, torch) for x in xs]
+        cfg = binding.config_from_hyper(wl.hyper)
+        call = lambda d, out, ws, stream=None: binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg,
+                                                                          out=out, workspace=ws, stream=stream)
+        nbytes = binding.impact_loss_workspace_bytes(wl.dist, wl.T, wl.B, wl.A)
+        want = []
+        for x, d in zip(xs, ds):
+            out = call(d, binding.alloc_loss_out(wl.T, wl.B, wl.W), torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
+            torch.cuda.synchronize()
+            check_against_oracle(wl, x, {k: v.cpu().numpy() for k, v in out.items()}, label=f"{name} alone")
+            want.append({k: v.clone() for k, v in out.items()})
+        # in a row on the current stream, alternating the two batches
+        out, ws = binding.alloc_loss_out(wl.T, wl.B, wl.W), torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for i in range(12):
+            call(ds[i % 2], out, ws)
+            if i % 5 == 4:
+                torch.cuda.synchronize()
+                for k in out:
+                    assert torch.equal(out[k], want[i % 2][k]), (name, "in a row", i, k)
+        torch.cuda.synchronize()
+        # overlapping on two streams
+        lanes = [dict(stream=torch.cuda.Stream(), out=binding.alloc_loss_out(wl.T, wl.B, wl.W),
+                      ws=torch.empty(nbytes, dtype=torch.uint8, device="cuda")) for _ in range(2)]
+        for rnd in range(6):
+            for n, ln in enumerate(lanes):
+                which = (rnd + n) % 2
+                with torch.cuda.stream(ln["stream"]):
+                    for v in ln["out"].values():
+                        v.fill_(float("nan"))
+                call(ds[which], ln["out"], ln["ws"], stream=ln["stream"])
+            torch.cuda.synchronize()
+            for n, ln in enumerate(lanes):
+                for k in ln["out"]:
+                    assert torch.equal(ln["out"][k], want[(rnd + n) % 2][k]), (name, "two streams", rnd, n, k)
+
+
+def test_a_call_without_a_buffer_replays_in_a_captured_graph(env):
+    """While its stream is being captured the call does not use the per-stream counter (a replay may run beside other
+    work of that stream): it records its loss kernel and the small launch that sums the loss terms.  Every replay,
+    with eager calls on the same stream in between, gives the eager result."""
+    torch, binding = env
+    wl = shape_workload(workloads.C2, T=50, B=256)
+    say("case time-major call in a graph")
+    x = workloads.make_batch(wl, stream=77)
+    d = to_device(x, torch)
+    cfg = binding.config_from_hyper(wl.hyper)
+    out = binding.alloc_loss_out(wl.T, wl.B, wl.W)
+    ws = torch.empty(binding.impact_loss_workspace_bytes(wl.dist, wl.T, wl.B, wl.A), dtype=torch.uint8, device="cuda")
+    step = lambda: binding.impact_loss_fwd_bwd(wl.dist, d["learner"], d["values"], d["bootstrap"], d, cfg, out=out, workspace=ws)
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        d["learner"].copy_(torch.from_numpy((x["learner"] + 0.1 * rep * rng.standard_normal(x["learner"].shape)).astype(np.float32)))
+        step()                                           # eager, with the stream's counter
+        torch.cuda.synchronize()
+        eager = {k: v.clone() for k, v in out.items()}
+        for v in out.values():
+            v.fill_(float("nan"))
+        junk = (torch.randn(1 << 16, device="cuda") * 2).sum()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for k in eager:
+            assert torch.equal(out[k], eager[k]), (rep, k)

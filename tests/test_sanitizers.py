@@ -65,6 +65,7 @@ void launch_zero_words(unsigned *, int, hipStream_t) {}
 void launch_insert_plane(PlaneKind, const PlaneCopyArgs &, hipStream_t) {}
 void launch_gather_plane(const GatherArgs &, hipStream_t) {}
 void launch_cache_logp(const LogpArgs &, hipStream_t) {}
+unsigned *done_counter_of_stream(hipStream_t) { return nullptr; }
 }
 extern "C" impact_status_t impact_loss_fwd_bwd_static(int32_t, int32_t, int32_t, int32_t, int32_t, const void *, const float *,
                                                       const float *, const impact_batch_t *, const impact_loss_config_t *,
